@@ -1,0 +1,180 @@
+/*
+ * abs_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain, slow, CPU-only statement of what the ABS-SGD data-parallel hot path
+ * computes.  It exists only so that tests, the smoke check and the benchmark's
+ * CPU-baseline leg can compare the GPU library against it.  It shares no code,
+ * header, table or helper with the HIP library and must never be called from
+ * the product path.
+ *
+ * What it follows (ABS-SGD paper, Section "Algorithm", Algorithm 1):
+ *   - Step 2, initialisation:  G_t^i = 0,  M_t^i = 0.
+ *   - Step 2, inner loop:      G_t^i += (sum of the per-sample gradients of one
+ *                              reference batch);  M_t^i += M_r.
+ *   - Step 1:                  Gbar_{t-1} = (sum_i G_{t-1}^i) / (sum_i M_{t-1}^i)
+ *                              (the weighted gradient averaging mechanism).
+ *   - Update:                  x_{t+1} = x_t - gamma * Gbar_{t-1}   (delay of one
+ *                              iteration; heterogeneous-aware delayed synchronous
+ *                              parallel mechanism).
+ * The paper uses plain SGD (Section "Conclusions and Future Work").  The task this
+ * oracle serves asks for momentum SGD with weight decay on top of it; the
+ * conventional coupled form is used,
+ *       d = Gbar + wd*x ;  v = mu*v + d ;  x = x - gamma*v ,
+ * which is exactly the paper's rule when mu = 0 and wd = 0.
+ *
+ * A reference batch arrives as its MEAN gradient g (what a backward pass over
+ * M_r samples of a mean-reduced loss yields), so the sum of its per-sample
+ * gradients is M_r * g.
+ *
+ * Precision: everything in IEEE double.  Inputs (fp32 or bf16 gradients, fp32
+ * hyper-parameters) are widened exactly before use.
+ *
+ * A second family, oracle32_*, restates the same steps in fp32 with one fixed
+ * operation order so that an fp32 implementation following that order can be
+ * compared bit for bit.  It is pinned against the double family in the CPU
+ * tests; it is not the judge of accuracy, the double family is.
+ *
+ * The loops over the n parameters are independent per element; the only
+ * parallelism is "#pragma omp parallel for" over that index.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- helpers ----------------------------------------------------------- */
+
+/* bfloat16 is the upper half of an IEEE binary32: widening is a 16-bit shift. */
+static inline float bf16_bits_to_float(uint16_t b)
+{
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ---- double family: the definition ------------------------------------ */
+
+/* Algorithm 1, Step 2, initialisation: G_t^i = 0. (M_t^i = 0 is the caller's
+ * integer.) */
+void oracle_zero(double *G, int64_t n_params)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_params; ++i) G[i] = 0.0;
+}
+
+/* Algorithm 1, Step 2, inner loop, one reference batch of M_r samples whose
+ * mean gradient is g (fp32): G += M_r * g.  The caller adds M_r to M_t^i. */
+void oracle_accumulate_f32(double *G, const float *g, int64_t n_params, int64_t M_r)
+{
+    const double m = (double)M_r;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_params; ++i) G[i] += m * (double)g[i];
+}
+
+/* Same, gradient stored as bfloat16 bit patterns. */
+void oracle_accumulate_bf16(double *G, const uint16_t *g, int64_t n_params, int64_t M_r)
+{
+    const double m = (double)M_r;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_params; ++i)
+        G[i] += m * (double)bf16_bits_to_float(g[i]);
+}
+
+/* Algorithm 1, Step 1 + parameter update, with the delayed accumulators
+ * G[0..N-1] and batch sizes M[0..N-1] of the previous iteration.
+ * Returns 1 and touches nothing when sum(M) == 0 (G_{-1} = 0 with no batch
+ * size defined: the first iteration applies nothing); else returns 0.
+ * Workers with M[i] == 0 hold G[i] == 0 by the initialisation above, so the
+ * plain sum over all N workers is the definition. */
+int oracle_sync_update(double *x, double *v, const double *const *G, const int64_t *M,
+                       int N, int64_t n_params, double gamma, double mu, double wd)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const double Mt = (double)M_total;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < N; ++i) s += G[i][j];
+        const double Gbar = s / Mt;
+        const double d = Gbar + wd * x[j];
+        v[j] = mu * v[j] + d;
+        x[j] = x[j] - gamma * v[j];
+    }
+    return 0;
+}
+
+/* ---- fp32 family with a fixed operation order -------------------------- */
+
+/* first != 0: this is the first reference batch since the accumulator was
+ * reset, so G = 0 and the result is the rounded product.  Otherwise one fused
+ * multiply-add. */
+void oracle32_accumulate_f32(float *G, const float *g, int64_t n_params, int64_t M_r,
+                             int first)
+{
+    const float m = (float)M_r;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_params; ++i)
+        G[i] = first ? m * g[i] : fmaf(m, g[i], G[i]);
+}
+
+void oracle32_accumulate_bf16(float *G, const uint16_t *g, int64_t n_params, int64_t M_r,
+                              int first)
+{
+    const float m = (float)M_r;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_params; ++i) {
+        const float gi = bf16_bits_to_float(g[i]);
+        G[i] = first ? m * gi : fmaf(m, gi, G[i]);
+    }
+}
+
+/* Order: s = G[i0]; s += G[i] for the remaining workers with M[i] > 0 in
+ * ascending i; Gbar = s / (float)sum(M) (correctly rounded divide);
+ * d = fma(wd, x, Gbar); v = fma(mu, v, d); x = fma(-gamma, v, x). */
+int oracle32_sync_update(float *x, float *v, const float *const *G, const int64_t *M, int N,
+                         int64_t n_params, float gamma, float mu, float wd)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const float Mt = (float)M_total;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        float s = 0.0f;
+        int seen = 0;
+        for (int i = 0; i < N; ++i) {
+            if (M[i] <= 0) continue;
+            s = seen ? s + G[i][j] : G[i][j];
+            seen = 1;
+        }
+        const float Gbar = s / Mt;
+        const float d = fmaf(wd, x[j], Gbar);
+        const float vn = fmaf(mu, v[j], d);
+        v[j] = vn;
+        x[j] = fmaf(-gamma, vn, x[j]);
+    }
+    return 0;
+}

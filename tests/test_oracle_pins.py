@@ -1,0 +1,361 @@
+"""CPU tests that pin the oracle to facts fixed by the paper and by arithmetic,
+none of which come from the oracle itself (nor from the GPU path).
+
+Each test names the passage of the ABS-SGD paper it rests on.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import abs_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+F32 = np.float32
+
+
+def _f32(*vals):
+    return np.array(vals, dtype=np.float32)
+
+
+def _read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [Fraction(v) for v in vals]
+    return out
+
+
+# ---------------------------------------------------------------------------
+# 1. worked example (Algorithm 1 Step 1 + update), values derived by hand
+# ---------------------------------------------------------------------------
+
+def test_worked_example_weighted_average_and_three_updates():
+    gold = _read_golden("worked_example.txt")
+    M_r = 32
+    G0 = np.zeros(2)
+    G1 = np.zeros(2)
+    orc.accumulate(G0, _f32(0.5, 1.0), M_r)
+    for g in (_f32(0.1, 0.2), _f32(0.3, -0.2), _f32(0.2, 0.6)):
+        orc.accumulate(G1, g, M_r)
+    M = [32, 96]
+    # fp32 inputs 0.1, 0.3 ... are not exact decimals: tolerance is fp32 input rounding
+    np.testing.assert_allclose(G0, [16.0, 32.0], rtol=1e-7)
+    np.testing.assert_allclose(G1, [19.2, 19.2], rtol=1e-7)
+
+    x = np.array([1.0, -2.0])
+    v = np.zeros(2)
+    for step in (1, 2, 3):
+        assert orc.sync_update(x, v, [G0, G1], M, 0.1, 0.9, 0.0005)
+        np.testing.assert_allclose(v, [float(f) for f in gold[f"v{step}"]], rtol=2e-7)
+        np.testing.assert_allclose(x, [float(f) for f in gold[f"x{step}"]], rtol=2e-7)
+
+    # the weighted average is NOT the plain mean of worker means here
+    x = np.zeros(2)
+    v = np.zeros(2)
+    orc.sync_update(x, v, [G0, G1], M, 1.0, 0.0, 0.0)   # x = -Gbar
+    np.testing.assert_allclose(-x, [float(f) for f in gold["gbar"]], rtol=2e-7)
+    unweighted = np.array([float(f) for f in gold["unweighted"]])
+    assert np.all(np.abs(-x - unweighted) > 0.05)
+
+
+def test_worked_example_exact_with_dyadic_inputs():
+    """Same structure with inputs that are exact in binary, so the double oracle
+    must hit the rational result exactly (to 1 ulp of double)."""
+    M_r = 32
+    G0, G1 = np.zeros(2), np.zeros(2)
+    orc.accumulate(G0, _f32(0.5, 1.0), M_r)
+    for g in (_f32(0.125, 0.25), _f32(0.375, -0.25), _f32(0.25, 0.5)):
+        orc.accumulate(G1, g, M_r)
+    assert G0.tolist() == [16.0, 32.0]
+    assert G1.tolist() == [24.0, 16.0]
+    x, v = np.zeros(2), np.zeros(2)
+    orc.sync_update(x, v, [G0, G1], [32, 96], 1.0, 0.0, 0.0)
+    assert (-x).tolist() == [40.0 / 128.0, 48.0 / 128.0]
+
+
+# ---------------------------------------------------------------------------
+# 2. equal batch sizes => plain mean (weighted gradient averaging mechanism)
+# ---------------------------------------------------------------------------
+
+def test_equal_counts_reduce_to_plain_mean():
+    rng = np.random.default_rng(1)
+    P, N, M_r, m = 257, 5, 32, 3
+    means = rng.standard_normal((N, m, P)).astype(F32)
+    G = [np.zeros(P) for _ in range(N)]
+    for i in range(N):
+        for j in range(m):
+            orc.accumulate(G[i], means[i, j], M_r)
+    x, v = np.zeros(P), np.zeros(P)
+    orc.sync_update(x, v, G, [m * M_r] * N, 1.0, 0.0, 0.0)
+    worker_means = means.astype(np.float64).mean(axis=1)       # each worker's own mean
+    np.testing.assert_allclose(-x, worker_means.mean(axis=0), rtol=0, atol=1e-14)
+
+
+def test_unequal_counts_weight_by_sample_share():
+    rng = np.random.default_rng(2)
+    P, M_r = 64, 32
+    m = [1, 2, 5]
+    means = [rng.standard_normal((mi, P)).astype(F32) for mi in m]
+    G = [np.zeros(P) for _ in m]
+    for i, mm in enumerate(means):
+        for g in mm:
+            orc.accumulate(G[i], g, M_r)
+    x, v = np.zeros(P), np.zeros(P)
+    orc.sync_update(x, v, G, [mi * M_r for mi in m], 1.0, 0.0, 0.0)
+    # sum_i (M_i / M) * (worker i's mean)
+    total = sum(m)
+    expect = sum((mi / total) * mm.astype(np.float64).mean(axis=0) for mi, mm in zip(m, means))
+    np.testing.assert_allclose(-x, expect, rtol=0, atol=1e-14)
+    plain = np.mean([mm.astype(np.float64).mean(axis=0) for mm in means], axis=0)
+    assert np.max(np.abs(-x - plain)) > 1e-3
+
+
+# ---------------------------------------------------------------------------
+# 3. N = 1, mu = 0, wd = 0  =>  SGD with exactly one iteration of delay
+#    (Algorithm 1 with G_{-1} = 0; Appendix, proof of Theorem 1, first display)
+# ---------------------------------------------------------------------------
+
+def test_single_worker_is_one_step_delayed_sgd():
+    rng = np.random.default_rng(3)
+    P, T, M_r, gamma = 33, 6, 32, 0.05
+    g = rng.standard_normal((T, P)).astype(F32)
+    x0 = rng.standard_normal(P).astype(F32)
+
+    xs = []
+    orc.run(x0, 1, T, M_r, gamma, 0.0, 0.0, lambda t, i: [g[t]],
+            record=lambda t, x, v: xs.append(x.copy()))
+
+    # independent five-line delayed SGD: x_{t+1} = x_t - gamma * gbar_{t-1}, gbar_{-1} = 0
+    ref = x0.astype(np.float64)
+    prev = np.zeros(P)
+    for t in range(T):
+        ref = ref - gamma * prev
+        prev = g[t].astype(np.float64)
+        np.testing.assert_allclose(xs[t], ref, rtol=0, atol=1e-14)
+    # first iteration applied nothing
+    np.testing.assert_array_equal(xs[0], x0.astype(np.float64))
+
+
+def test_first_iteration_is_a_noop_even_with_weight_decay():
+    """G_{-1} = 0 and no batch size exists for it: nothing is applied, the state
+    is untouched (Algorithm 1, initialisation)."""
+    x = np.array([1.0, -3.0])
+    v = np.array([0.25, 0.5])
+    G = [np.zeros(2), np.zeros(2)]
+    assert orc.sync_update(x, v, G, [0, 0], 0.1, 0.9, 0.01) is False
+    assert x.tolist() == [1.0, -3.0] and v.tolist() == [0.25, 0.5]
+
+
+# ---------------------------------------------------------------------------
+# 4. delay invariant: x_{t+1} does not depend on the gradients of iteration t
+# ---------------------------------------------------------------------------
+
+def test_update_ignores_current_iteration_gradients():
+    rng = np.random.default_rng(4)
+    P, N, T, M_r = 40, 3, 4, 32
+    g = rng.standard_normal((T, N, 2, P)).astype(F32)
+    x0 = rng.standard_normal(P).astype(F32)
+
+    def run(gg):
+        return orc.run(x0, N, T, M_r, 0.1, 0.9, 5e-4, lambda t, i: list(gg[t, i]))[0]
+
+    base = run(g)
+    g2 = g.copy()
+    g2[T - 1] += 7.0                       # perturb only the last iteration's gradients
+    np.testing.assert_array_equal(run(g2), base)
+    g3 = g.copy()
+    g3[T - 2] += 7.0                       # the one before is applied in the last iteration
+    assert np.max(np.abs(run(g3) - base)) > 0.1
+
+
+# ---------------------------------------------------------------------------
+# 5. closed forms of the update recursion
+# ---------------------------------------------------------------------------
+
+def test_constant_gradient_momentum_closed_form():
+    gbar, mu, gamma, steps = 0.375, 0.9, 0.1, 25
+    G = [np.full(3, 32 * gbar)]
+    x, v = np.array([1.0, 0.0, -1.0]), np.zeros(3)
+    x_init = x.copy()
+    for n in range(1, steps + 1):
+        orc.sync_update(x, v, G, [32], gamma, mu, 0.0)
+        v_n = gbar * (1 - mu ** n) / (1 - mu)
+        x_n = x_init - gamma * gbar * (n - mu * (1 - mu ** n) / (1 - mu)) / (1 - mu)
+        np.testing.assert_allclose(v, v_n, rtol=1e-13)
+        np.testing.assert_allclose(x, x_n, rtol=1e-12, atol=1e-13)
+
+
+def test_pure_weight_decay_closed_form():
+    gamma, wd, steps = 0.1, 0.05, 12
+    G = [np.zeros(2)]
+    x, v = np.array([2.0, -0.5]), np.zeros(2)
+    for _ in range(steps):
+        orc.sync_update(x, v, G, [32], gamma, 0.0, wd)
+    np.testing.assert_allclose(x, np.array([2.0, -0.5]) * (1 - gamma * wd) ** steps, rtol=1e-13)
+
+
+def test_momentum_and_weight_decay_match_two_term_linear_recurrence():
+    """With constant Gbar = g the pair (x, v) follows a 2x2 affine map; compare
+    with that map applied through numpy matrix algebra."""
+    g, gamma, mu, wd, steps = -0.2, 0.1, 0.9, 0.01, 9
+    A = np.array([[1 - gamma * wd, -gamma * mu], [wd, mu]])   # acts on (x, v)
+    b = np.array([-gamma * g, g])
+    s = np.array([0.7, 0.0])
+    G = [np.full(1, 64 * g)]
+    x, v = np.array([0.7]), np.zeros(1)
+    for _ in range(steps):
+        s = A @ s + b
+        orc.sync_update(x, v, G, [64], gamma, mu, wd)
+    np.testing.assert_allclose([x[0], v[0]], s, rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# 6. regrouping invariants: Gbar is (sum of all per-sample gradients)/(samples)
+# ---------------------------------------------------------------------------
+
+def _gbar(groups, M_r_of):
+    """groups[i] = list of (mean_gradient, samples) for worker i."""
+    P = groups[0][0][0].size
+    G, M = [], []
+    for batches in groups:
+        Gi, Mi = np.zeros(P), 0
+        for g, m in batches:
+            orc.accumulate(Gi, g, m)
+            Mi += m
+        G.append(Gi)
+        M.append(Mi)
+    x, v = np.zeros(P), np.zeros(P)
+    orc.sync_update(x, v, G, M, 1.0, 0.0, 0.0)
+    return -x
+
+
+def test_regrouping_leaves_average_unchanged():
+    rng = np.random.default_rng(6)
+    P = 50
+    a, b, c, d = (rng.standard_normal(P).astype(F32) for _ in range(4))
+    base = _gbar([[(a, 32), (b, 32)], [(c, 32)], [(d, 64)]], None)
+    # permute workers
+    np.testing.assert_allclose(_gbar([[(d, 64)], [(a, 32), (b, 32)], [(c, 32)]], None), base,
+                               rtol=0, atol=1e-15)
+    # move a micro-batch to another worker
+    np.testing.assert_allclose(_gbar([[(a, 32)], [(c, 32), (b, 32)], [(d, 64)]], None), base,
+                               rtol=0, atol=1e-15)
+    # split a 64-sample batch into two 32-sample batches with the same mean
+    np.testing.assert_allclose(_gbar([[(a, 32), (b, 32)], [(c, 32)], [(d, 32), (d, 32)]], None),
+                               base, rtol=0, atol=1e-15)
+    # an idle worker changes nothing
+    np.testing.assert_allclose(_gbar([[(a, 32), (b, 32)], [], [(c, 32)], [(d, 64)]], None), base,
+                               rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------
+# 7. brute force on tiny inputs, in exact rational arithmetic, from per-sample
+#    gradients (Algorithm 1 Step 2 sums PER-SAMPLE gradients)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_brute_force_per_sample_rational(seed):
+    rng = np.random.default_rng(100 + seed)
+    P, N, T, M_r = 5, 3, 4, 4
+    gamma, mu, wd = F32(0.1), F32(0.9), F32(5e-4)
+    fg, fm, fw = Fraction(float(gamma)), Fraction(float(mu)), Fraction(float(wd))
+    m = rng.integers(0 if seed == 2 else 1, 4, size=(T, N))      # seed 2 allows idle workers
+    if seed == 2:
+        m[1, :] = 0                                              # a whole iteration with no samples
+    # per-sample gradients are multiples of 1/256 so every micro-batch mean is exact in fp32
+    samples = {(t, i, j): rng.integers(-512, 513, size=(M_r, P))
+               for t in range(T) for i in range(N) for j in range(int(m[t, i]))}
+    x0 = (rng.integers(-1024, 1025, size=P) / 512.0).astype(F32)
+
+    def batches(t, i):
+        return [(samples[(t, i, j)].sum(axis=0) / (256.0 * M_r)).astype(F32)
+                for j in range(int(m[t, i]))]
+
+    x_o, v_o, hist = orc.run(x0, N, T, M_r, gamma, mu, wd, batches)
+
+    # brute force: expand every sample, average them all at once, exact rationals
+    x = [Fraction(float(a)) for a in x0]
+    v = [Fraction(0)] * P
+    for t in range(T):
+        if t >= 1:
+            all_samples = [samples[(t - 1, i, j)][s]
+                           for i in range(N) for j in range(int(m[t - 1, i])) for s in range(M_r)]
+            if all_samples:
+                cnt = len(all_samples)
+                for p in range(P):
+                    gbar = Fraction(int(sum(int(s[p]) for s in all_samples)), 256 * cnt)
+                    d = gbar + fw * x[p]
+                    v[p] = fm * v[p] + d
+                    x[p] = x[p] - fg * v[p]
+        assert hist[t] == [int(mm) * M_r for mm in m[t]]         # batch sizes are exact integers
+    np.testing.assert_allclose(x_o, [float(a) for a in x], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(v_o, [float(a) for a in v], rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------
+# 8. bf16 gradients widen exactly
+# ---------------------------------------------------------------------------
+
+def test_bf16_gradients_widen_exactly():
+    vals = np.array([1.0, -2.5, 0.00390625, 3.0e-5, -1.0e10, 0.0], dtype=F32)
+    bits = (vals.view(np.uint32) >> 16).astype(np.uint16)        # truncate: these ARE bf16 values now
+    widened = (bits.astype(np.uint32) << 16).view(F32).astype(np.float64)
+    G = np.zeros(vals.size)
+    orc.accumulate(G, bits, 3)
+    np.testing.assert_array_equal(G, 3.0 * widened)
+    # 1.0 and -2.5 are representable: survive unchanged
+    assert G[0] == 3.0 and G[1] == -7.5
+
+
+# ---------------------------------------------------------------------------
+# 9. the fixed-order fp32 restatement stays within fp32 rounding of the definition
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fp32_family_tracks_double_family(dtype):
+    import abs_workloads as wl
+    rng = np.random.default_rng(9)
+    P, N, T, M_r = 4099, 4, 6, 32
+    gamma, mu, wd = F32(0.1), F32(0.9), F32(5e-4)
+    m = rng.integers(0, 4, size=(T, N))
+    pool = [(rng.standard_normal(P) * 0.01).astype(F32) for _ in range(8)]
+    if dtype == "bf16":
+        pool = [wl.to_bf16_bits(g) for g in pool]
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+
+    def batches(t, i):
+        return [pool[(3 * t + 5 * i + j) % 8] for j in range(int(m[t, i]))]
+
+    x64, v64, h64 = orc.run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64")
+    x32, v32, h32 = orc.run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f32")
+    assert h64 == h32
+    assert x32.dtype == F32
+    # norm-wise: a handful of fp32 roundings per step on O(0.05) values
+    assert np.max(np.abs(x32 - x64)) <= 1e-6 * np.max(np.abs(x64))
+    assert np.max(np.abs(v32 - v64)) <= 1e-6 * np.max(np.abs(v64))
+    # and it really is a different precision
+    assert np.max(np.abs(x32 - x64)) > 0
+
+
+def test_fp32_family_first_batch_overwrites_stale_accumulator():
+    G = np.full(4, 123.0, dtype=F32)
+    g = _f32(1.0, 2.0, -3.0, 0.5)
+    orc.accumulate32(G, g, 32, first=True)
+    np.testing.assert_array_equal(G, _f32(32, 64, -96, 16))
+    orc.accumulate32(G, g, 32, first=False)
+    np.testing.assert_array_equal(G, _f32(64, 128, -192, 32))
+
+
+def test_fp32_family_skips_idle_workers():
+    Ga = _f32(32.0, 64.0)
+    stale = _f32(1e30, -1e30)
+    x, v = _f32(0, 0), _f32(0, 0)
+    assert orc.sync_update32(x, v, [stale, Ga], [0, 32], 1.0, 0.0, 0.0)
+    np.testing.assert_array_equal(x, _f32(-1.0, -2.0))
+    assert orc.sync_update32(x, v, [stale, Ga], [0, 0], 1.0, 0.0, 0.0) is False
