@@ -1,0 +1,196 @@
+/*
+ * abs_sgd.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot
+ * path of ABS-SGD (delayed synchronous SGD with adaptive batch size).
+ *
+ * Vocabulary (the paper's Algorithm 1 in brackets):
+ *   P          number of parameters                      [n]
+ *   K          number of workers                         [N]
+ *   n_samples  samples in one micro-batch                [M_r, reference batch size]
+ *   acc        a worker's running gradient accumulator   [G_t^i], fp32, P elements
+ *   count      samples accumulated so far in acc         [M_t^i], int64, exact
+ *   grad       MEAN gradient of one micro-batch, fp32 or bf16; the sum of its
+ *              per-sample gradients is n_samples * grad
+ *   params     x, fp32;  momentum  v, fp32
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE address memory of the current HIP device, owned by
+ *     the caller; the library never allocates, frees or keeps P-sized memory.
+ *     Pointers marked HOST are ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernels are enqueued on it and the call returns without waiting.
+ *   - fp32 buffers must be 4-byte aligned, bf16 buffers 2-byte aligned; 16-byte
+ *     aligned bases take the 128-bit path, others a slower element-wise path
+ *     with identical results.
+ *   - Return value: ABS_OK (0); ABS_EMPTY (1): nothing to apply, no memory
+ *     touched, not an error; ABS_EINVAL (-1): bad argument, nothing enqueued;
+ *     ABS_EHIP (-2): a HIP runtime call failed, abs_last_hip_error() has its code.
+ *     Nothing is thrown across this boundary.
+ *   - Arithmetic is fp32 in one fixed order (stated per call) so results are
+ *     reproducible bit for bit; sample counts are integers.
+ */
+#ifndef ABS_SGD_H
+#define ABS_SGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ABS_MAX_K 64 /* most workers one sync-update may combine */
+
+enum { ABS_OK = 0, ABS_EMPTY = 1, ABS_EINVAL = -1, ABS_EHIP = -2 };
+
+typedef enum { ABS_F32 = 0, ABS_BF16 = 1 } abs_dtype;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int abs_version(void);
+/* hipError_t of the last failed HIP call made by this thread through the library. */
+int abs_last_hip_error(void);
+/* Static, human-readable text for a return code. */
+const char *abs_error_string(int rc);
+/* Elements covered by one workgroup in every kernel (also the ragged chunk size). */
+int64_t abs_tile_elems(void);
+
+/* ------------------------------------------------------------------------
+ * (1) Gradient accumulation -- Algorithm 1, Step 2 (inner loop and its
+ *     initialisation G_t^i = 0, M_t^i = 0).
+ *
+ *   first = (*count == 0), i.e. first micro-batch since the accumulator was
+ *           reset (creation or swap).  Then, for every i < P,
+ *     acc[i] = first ? (float)n_samples * g[i]
+ *                    : fmaf((float)n_samples, g[i], acc[i])
+ *   with g[i] the fp32 value of grad[i] (bf16 widens exactly), and
+ *     *count += n_samples.
+ *   Overwriting on the first call is the paper's zero initialisation without a
+ *   separate pass over memory.
+ *
+ *   acc   DEVICE, P floats, read (unless first) and written
+ *   grad  DEVICE, P elements of grad_dtype, read only
+ *   count HOST, read and updated before the call returns
+ *   P = 0 is allowed (only the count moves).  EINVAL: null pointer, P < 0,
+ *   n_samples <= 0, *count < 0, count overflow, misaligned base, bad dtype.
+ * ---------------------------------------------------------------------- */
+int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
+                   int64_t n_samples, int64_t *count, void *stream);
+
+/* ------------------------------------------------------------------------
+ * (2)+(3) Weighted combination of the K delayed accumulators and the delayed
+ *     parameter update -- Algorithm 1, Step 1 (weighted gradient averaging)
+ *     and the update line; momentum and weight decay wrap the paper's plain
+ *     SGD step and vanish for mu = 0, wd = 0.
+ *
+ *   M = sum_k counts[k].  M == 0 -> ABS_EMPTY (the first iteration: G_{-1} = 0).
+ *   Workers with counts[k] == 0 are skipped; their buffers are never read (they
+ *   may hold stale data because accumulation overwrites instead of zeroing).
+ *   For every i < P, over the non-empty workers in ascending k:
+ *     s    = acc[k0][i];  s = s + acc[k][i] ...
+ *     Gbar = s / (float)M              (correctly rounded divide)
+ *     d    = fmaf(wd, x[i], Gbar)
+ *     v[i] = fmaf(mu, v[i], d)
+ *     x[i] = fmaf(-lr, v[i], x[i])
+ *   One read pass over the K buffers, fused with the reads and writes of x, v.
+ *
+ *   params, momentum  DEVICE, P floats, read and written
+ *   acc     HOST array of K DEVICE pointers (each P floats, read only)
+ *   counts  HOST array of K int64
+ *   EINVAL: null pointer, K < 1 or K > ABS_MAX_K, P < 0, a negative count,
+ *   misaligned base.
+ * ---------------------------------------------------------------------- */
+int abs_sync_update(float *params, float *momentum, const float *const *acc,
+                    const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                    void *stream);
+
+/* ------------------------------------------------------------------------
+ * Ragged (multi-tensor) layouts: the parameter vector of Section "Problem
+ * definition" split into T separately allocated tensors of arbitrary sizes.
+ * One launch covers all tensors.
+ *
+ * abs_layout    sizes only; built on the host (needs no GPU).  It cuts every
+ *               tensor into chunks of abs_tile_elems() elements, one per
+ *               workgroup; the chunk table is copied to the device the first
+ *               time a launch needs it.
+ * abs_tensorset T DEVICE base pointers for one logical vector (x, v, one
+ *               worker's accumulator, one gradient) laid out per the layout;
+ *               the pointer table is copied to device memory at creation.
+ *               The tensors stay owned by the caller and must outlive the set.
+ * ---------------------------------------------------------------------- */
+typedef struct abs_layout abs_layout;
+typedef struct abs_tensorset abs_tensorset;
+
+/* sizes: HOST array of T element counts (each >= 0; T >= 1). */
+int abs_layout_create(abs_layout **out, int T, const int64_t *sizes);
+int abs_layout_destroy(abs_layout *layout);
+int abs_layout_num_tensors(const abs_layout *layout);
+int64_t abs_layout_total(const abs_layout *layout);
+int64_t abs_layout_num_chunks(const abs_layout *layout);
+/* Chunk c covers elements [*offset, *offset + *len) of tensor *tensor. */
+int abs_layout_chunk(const abs_layout *layout, int64_t c, int *tensor, int64_t *offset,
+                     int64_t *len);
+
+/* ptrs: HOST array of T DEVICE pointers; elem: element type of the tensors.
+ * A tensor of size 0 may have a null pointer. */
+int abs_tensorset_create(abs_tensorset **out, const abs_layout *layout, void *const *ptrs,
+                         abs_dtype elem);
+int abs_tensorset_destroy(abs_tensorset *set);
+
+/* Same arithmetic as abs_accumulate over every tensor of the layout; one count
+ * for the whole vector.  acc must be an ABS_F32 set; grad may be F32 or BF16. */
+int abs_accumulate_mt(abs_layout *layout, const abs_tensorset *acc,
+                      const abs_tensorset *grad, int64_t n_samples, int64_t *count,
+                      void *stream);
+
+/* Same arithmetic as abs_sync_update over every tensor of the layout.
+ * acc: HOST array of K sets; counts: HOST array of K int64. */
+int abs_sync_update_mt(abs_layout *layout, const abs_tensorset *params,
+                       const abs_tensorset *momentum, const abs_tensorset *const *acc,
+                       const int64_t *counts, int K, float lr, float mu, float wd,
+                       void *stream);
+
+/* ------------------------------------------------------------------------
+ * (4) Double buffer -- Algorithm 1, "Run Step 1 and Step 2 in parallel": two
+ *     generations of (K accumulators, K counts).  Accumulation of batch t runs
+ *     on stream_acc into the CURRENT generation while the sync-update of batch
+ *     t-1 runs on stream_upd from the PREVIOUS one.
+ *
+ * The context owns only indices, the 2*K host counts and two HIP events; the
+ * accumulators stay the caller's.  All counts start at 0 (G_{-1} = 0).
+ * stream_acc == stream_upd gives the serial order on one stream.
+ * ---------------------------------------------------------------------- */
+typedef struct abs_ctx abs_ctx;
+
+/* acc_A, acc_B: HOST arrays of K DEVICE pointers, P floats each. */
+int abs_ctx_create(abs_ctx **out, int K, int64_t P, float *const *acc_A, float *const *acc_B,
+                   void *stream_acc, void *stream_upd);
+/* Ragged form: acc_A, acc_B are HOST arrays of K ABS_F32 sets over `layout`. */
+int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *layout,
+                      const abs_tensorset *const *acc_A, const abs_tensorset *const *acc_B,
+                      void *stream_acc, void *stream_upd);
+int abs_ctx_destroy(abs_ctx *ctx);
+
+/* abs_accumulate into worker k's CURRENT accumulator, on stream_acc. */
+int abs_ctx_accumulate(abs_ctx *ctx, int k, const void *grad, abs_dtype grad_dtype,
+                       int64_t n_samples);
+int abs_ctx_accumulate_mt(abs_ctx *ctx, int k, const abs_tensorset *grad, int64_t n_samples);
+
+/* abs_sync_update from the PREVIOUS generation, on stream_upd.  ABS_EMPTY in
+ * the first iteration. */
+int abs_ctx_sync_update(abs_ctx *ctx, float *params, float *momentum, float lr, float mu,
+                        float wd);
+int abs_ctx_sync_update_mt(abs_ctx *ctx, const abs_tensorset *params,
+                           const abs_tensorset *momentum, float lr, float mu, float wd);
+
+/* End of an iteration (Algorithm 1, t = t + 1): each stream waits for the work
+ * the other has enqueued so far (the next sync-update reads what accumulation
+ * wrote; the next accumulation overwrites what the sync-update read), the
+ * generations trade places, and the new current counts become 0.  No memory is
+ * cleared.  Does not block the host. */
+int abs_swap_buffers(abs_ctx *ctx);
+
+/* which: 0 = current generation, 1 = previous.  out: HOST, K int64. */
+int abs_ctx_counts(const abs_ctx *ctx, int which, int64_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABS_SGD_H */

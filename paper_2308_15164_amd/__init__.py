@@ -1,0 +1,324 @@
+"""MI355X-native ABS-SGD data-parallel hot path: thin Python binding.
+
+Every function here has the name and the meaning of the C entry point declared
+in ``include/abs_sgd.h`` and does argument marshalling only: tensors become
+device pointers, streams become ``hipStream_t`` handles, return codes become
+Python values or exceptions.  All arithmetic runs in the HIP kernels of
+``libabs_sgd.so``; there is no fallback path, and importing the module fails
+loudly when the library has not been built.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libabs_sgd.so")
+
+ABS_OK, ABS_EMPTY, ABS_EINVAL, ABS_EHIP = 0, 1, -1, -2
+ABS_F32, ABS_BF16 = 0, 1
+ABS_MAX_K = 64
+
+# name -> (restype, argtypes): every symbol include/abs_sgd.h declares
+_vp, _i64, _int, _f = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+_pi64 = ctypes.POINTER(ctypes.c_int64)
+_pvp = ctypes.POINTER(ctypes.c_void_p)
+SYMBOLS = {
+    "abs_version": (_int, []),
+    "abs_last_hip_error": (_int, []),
+    "abs_error_string": (ctypes.c_char_p, [_int]),
+    "abs_tile_elems": (_i64, []),
+    "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
+    "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
+    "abs_layout_create": (_int, [_pvp, _int, _pi64]),
+    "abs_layout_destroy": (_int, [_vp]),
+    "abs_layout_num_tensors": (_int, [_vp]),
+    "abs_layout_total": (_i64, [_vp]),
+    "abs_layout_num_chunks": (_i64, [_vp]),
+    "abs_layout_chunk": (_int, [_vp, _i64, ctypes.POINTER(_int), _pi64, _pi64]),
+    "abs_tensorset_create": (_int, [_pvp, _vp, _pvp, _int]),
+    "abs_tensorset_destroy": (_int, [_vp]),
+    "abs_accumulate_mt": (_int, [_vp, _vp, _vp, _i64, _pi64, _vp]),
+    "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
+    "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
+    "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
+    "abs_ctx_destroy": (_int, [_vp]),
+    "abs_ctx_accumulate": (_int, [_vp, _int, _vp, _int, _i64]),
+    "abs_ctx_accumulate_mt": (_int, [_vp, _int, _vp, _i64]),
+    "abs_ctx_sync_update": (_int, [_vp, _vp, _vp, _f, _f, _f]),
+    "abs_ctx_sync_update_mt": (_int, [_vp, _vp, _vp, _f, _f, _f]),
+    "abs_swap_buffers": (_int, [_vp]),
+    "abs_ctx_counts": (_int, [_vp, _int, _pi64]),
+}
+
+
+class AbsError(RuntimeError):
+    def __init__(self, fn, rc):
+        self.rc = rc
+        detail = ""
+        if rc == ABS_EHIP:
+            detail = f" (hipError_t {lib().abs_last_hip_error()})"
+        super().__init__(f"{fn}: {lib().abs_error_string(rc).decode()}{detail}")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library.  Raises if it has not been built: there is no
+    other implementation behind this package."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2308_15164_amd.build` "
+                "(hipcc, gfx950). This package has no CPU or PyTorch fallback.")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(fn, rc, allow_empty=False):
+    if rc == ABS_OK:
+        return True
+    if rc == ABS_EMPTY and allow_empty:
+        return False
+    raise AbsError(fn, rc)
+
+
+def _dev_ptr(t):
+    """Device address of a torch tensor (or a raw integer address)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise TypeError("expected a tensor in GPU memory")
+    if not t.is_contiguous():
+        raise TypeError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    """hipStream_t of a torch stream; None means torch's current stream."""
+    if isinstance(stream, int):
+        return stream
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def _dtype_of(t, dtype=None):
+    if dtype is not None:
+        return dtype
+    import torch
+    if t.dtype == torch.float32:
+        return ABS_F32
+    if t.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        return ABS_BF16
+    raise TypeError(f"gradient dtype {t.dtype} is neither fp32 nor bf16")
+
+
+def _ptr_array(ptrs):
+    return (ctypes.c_void_p * len(ptrs))(*ptrs)
+
+
+def _i64_array(vals):
+    return (ctypes.c_int64 * len(vals))(*[int(v) for v in vals])
+
+
+def abs_version():
+    return lib().abs_version()
+
+
+def abs_tile_elems():
+    return lib().abs_tile_elems()
+
+
+class Count:
+    """Host-side int64 sample counter handed to abs_accumulate by address."""
+
+    def __init__(self, value=0):
+        self._c = ctypes.c_int64(int(value))
+
+    @property
+    def value(self):
+        return self._c.value
+
+    @value.setter
+    def value(self, v):
+        self._c.value = int(v)
+
+
+def abs_accumulate(acc, grad, n_samples, count, stream=None, P=None, grad_dtype=None):
+    """acc (+)= n_samples * grad; count += n_samples.  See abs_accumulate in abs_sgd.h."""
+    n = acc.numel() if P is None else int(P)
+    rc = lib().abs_accumulate(_dev_ptr(acc), _dev_ptr(grad), _dtype_of(grad, grad_dtype), n,
+                              int(n_samples), ctypes.byref(count._c), _stream_handle(stream))
+    return _check("abs_accumulate", rc)
+
+
+def abs_sync_update(params, momentum, acc, counts, lr, mu, wd, stream=None, P=None):
+    """Fused weighted combine of acc[K] + delayed momentum-SGD update.
+    Returns False when the total count is zero (nothing applied)."""
+    n = params.numel() if P is None else int(P)
+    ptrs = _ptr_array([_dev_ptr(a) for a in acc])
+    rc = lib().abs_sync_update(_dev_ptr(params), _dev_ptr(momentum), ptrs, _i64_array(counts),
+                               len(acc), n, float(lr), float(mu), float(wd), _stream_handle(stream))
+    return _check("abs_sync_update", rc, allow_empty=True)
+
+
+class Layout:
+    """abs_layout: tensor sizes of a ragged parameter vector and its chunk table."""
+
+    def __init__(self, sizes):
+        self.sizes = [int(s) for s in sizes]
+        h = ctypes.c_void_p()
+        _check("abs_layout_create",
+               lib().abs_layout_create(ctypes.byref(h), len(self.sizes), _i64_array(self.sizes)))
+        self.handle = h
+
+    def num_tensors(self):
+        return lib().abs_layout_num_tensors(self.handle)
+
+    def total(self):
+        return lib().abs_layout_total(self.handle)
+
+    def num_chunks(self):
+        return lib().abs_layout_num_chunks(self.handle)
+
+    def chunk(self, c):
+        t, off, ln = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+        _check("abs_layout_chunk", lib().abs_layout_chunk(self.handle, c, ctypes.byref(t),
+                                                         ctypes.byref(off), ctypes.byref(ln)))
+        return t.value, off.value, ln.value
+
+    def close(self):
+        if self.handle is not None:
+            lib().abs_layout_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class TensorSet:
+    """abs_tensorset: the T base pointers of one logical vector over a Layout."""
+
+    def __init__(self, layout, tensors, dtype=None):
+        self.layout = layout
+        self.tensors = list(tensors)         # keeps the memory alive
+        if len(self.tensors) != len(layout.sizes):
+            raise ValueError("one tensor per layout entry expected")
+        for t, s in zip(self.tensors, layout.sizes):
+            if not isinstance(t, int) and t is not None and t.numel() != s:
+                raise ValueError("tensor size does not match the layout")
+        first = next((t for t in self.tensors if t is not None and not isinstance(t, int)), None)
+        self.dtype = _dtype_of(first, dtype) if (first is not None or dtype is not None) else ABS_F32
+        h = ctypes.c_void_p()
+        ptrs = _ptr_array([_dev_ptr(t) for t in self.tensors])
+        _check("abs_tensorset_create",
+               lib().abs_tensorset_create(ctypes.byref(h), layout.handle, ptrs, self.dtype))
+        self.handle = h
+
+    def close(self):
+        if self.handle is not None:
+            lib().abs_tensorset_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def abs_accumulate_mt(layout, acc, grad, n_samples, count, stream=None):
+    rc = lib().abs_accumulate_mt(layout.handle, acc.handle, grad.handle, int(n_samples),
+                                 ctypes.byref(count._c), _stream_handle(stream))
+    return _check("abs_accumulate_mt", rc)
+
+
+def abs_sync_update_mt(layout, params, momentum, acc, counts, lr, mu, wd, stream=None):
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_mt(layout.handle, params.handle, momentum.handle, sets,
+                                  _i64_array(counts), len(acc), float(lr), float(mu), float(wd),
+                                  _stream_handle(stream))
+    return _check("abs_sync_update_mt", rc, allow_empty=True)
+
+
+class Context:
+    """abs_ctx: the double buffer.  acc_A / acc_B are K tensors each (flat form)
+    or K TensorSets each over `layout` (ragged form)."""
+
+    def __init__(self, acc_A, acc_B, stream_acc, stream_upd, layout=None, P=None):
+        self.layout = layout
+        self.K = len(acc_A)
+        self._keep = (list(acc_A), list(acc_B), stream_acc, stream_upd)
+        h = ctypes.c_void_p()
+        sa, su = _stream_handle(stream_acc), _stream_handle(stream_upd)
+        if layout is None:
+            n = acc_A[0].numel() if P is None else int(P)
+            rc = lib().abs_ctx_create(ctypes.byref(h), self.K, n,
+                                      _ptr_array([_dev_ptr(a) for a in acc_A]),
+                                      _ptr_array([_dev_ptr(a) for a in acc_B]), sa, su)
+            _check("abs_ctx_create", rc)
+        else:
+            rc = lib().abs_ctx_create_mt(ctypes.byref(h), self.K, layout.handle,
+                                         _ptr_array([a.handle.value for a in acc_A]),
+                                         _ptr_array([a.handle.value for a in acc_B]), sa, su)
+            _check("abs_ctx_create_mt", rc)
+        self.handle = h
+
+    def abs_accumulate(self, k, grad, n_samples, grad_dtype=None):
+        if self.layout is None:
+            rc = lib().abs_ctx_accumulate(self.handle, int(k), _dev_ptr(grad),
+                                          _dtype_of(grad, grad_dtype), int(n_samples))
+            return _check("abs_ctx_accumulate", rc)
+        rc = lib().abs_ctx_accumulate_mt(self.handle, int(k), grad.handle, int(n_samples))
+        return _check("abs_ctx_accumulate_mt", rc)
+
+    def abs_sync_update(self, params, momentum, lr, mu, wd):
+        if self.layout is None:
+            rc = lib().abs_ctx_sync_update(self.handle, _dev_ptr(params), _dev_ptr(momentum),
+                                           float(lr), float(mu), float(wd))
+            return _check("abs_ctx_sync_update", rc, allow_empty=True)
+        rc = lib().abs_ctx_sync_update_mt(self.handle, params.handle, momentum.handle,
+                                          float(lr), float(mu), float(wd))
+        return _check("abs_ctx_sync_update_mt", rc, allow_empty=True)
+
+    def abs_swap_buffers(self):
+        return _check("abs_swap_buffers", lib().abs_swap_buffers(self.handle))
+
+    def counts(self, which=0):
+        out = (ctypes.c_int64 * self.K)()
+        _check("abs_ctx_counts", lib().abs_ctx_counts(self.handle, int(which), out))
+        return [int(v) for v in out]
+
+    def close(self):
+        if self.handle is not None:
+            lib().abs_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def abs_swap_buffers(ctx):
+    """End of an iteration: cross-stream joins, generations trade places."""
+    return ctx.abs_swap_buffers()
+
+
+__all__ = ["abs_swap_buffers", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
+           "abs_sync_update", "abs_accumulate_mt", "abs_sync_update_mt", "abs_version",
+           "abs_tile_elems", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
+           "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

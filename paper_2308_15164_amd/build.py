@@ -1,0 +1,32 @@
+"""Compile the HIP library for gfx950 into this package directory."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SOURCES = [os.path.join(HERE, "csrc", "abs_sgd.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "abs_kernels.hpp"), os.path.join(ROOT, "include", "abs_sgd.h")]
+LIB = os.path.join(HERE, "libabs_sgd.so")
+
+# Contraction is off so the fixed fp32 operation order survives; packed-fp32
+# instruction selection is disabled on this target.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-ffp-contract=off", "-fno-fast-math",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wextra", "-Wno-unused-parameter"]
+
+
+def build_library(force=True, extra_flags=(), out=LIB):
+    if not force and os.path.exists(out):
+        newest = max(os.path.getmtime(p) for p in SOURCES + HEADERS)
+        if os.path.getmtime(out) >= newest:
+            return out
+    cmd = (["hipcc"] + FLAGS + list(extra_flags) +
+           ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")] +
+           SOURCES + ["-o", out])
+    subprocess.run(cmd, check=True)
+    return out
+
+
+if __name__ == "__main__":
+    print(build_library())

@@ -1,0 +1,530 @@
+// Host side of the ABS-SGD hot-path library: argument checks, the ragged
+// layout's chunk table, the double-buffer context, and kernel launches.
+// The C ABI and the arithmetic contract are stated in include/abs_sgd.h.
+#include "abs_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+
+#include "abs_sgd.h"
+
+using namespace absk;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return ABS_EHIP;
+}
+
+#define ABS_HIP(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) return hip_fail(e_);      \
+    } while (0)
+
+inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline int launch_status()
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return ABS_OK;
+}
+
+// Number of workgroups for P elements; <0 when it does not fit the grid limit.
+inline int64_t tiles_for(int64_t P) { return (P + TILE - 1) / TILE; }
+constexpr int64_t kMaxGrid = 0x7fffffff;
+
+// counts -> compacted list of non-empty workers and their total.
+struct Combine {
+    int idx[ABS_MAX_K];
+    int n = 0;
+    int64_t M = 0;
+};
+
+int plan_combine(const int64_t *counts, int K, Combine &c)
+{
+    if (!counts || K < 1 || K > ABS_MAX_K) return ABS_EINVAL;
+    for (int k = 0; k < K; ++k) {
+        if (counts[k] < 0) return ABS_EINVAL;
+        if (counts[k] > 0) {
+            if (c.M > std::numeric_limits<int64_t>::max() - counts[k]) return ABS_EINVAL;
+            c.M += counts[k];
+            c.idx[c.n++] = k;
+        }
+    }
+    return c.M == 0 ? ABS_EMPTY : ABS_OK;
+}
+
+// ------------------------------------------------------------ flat launches
+
+template <bool FIRST>
+void launch_accumulate_flat(float *acc, const void *grad, abs_dtype dt, int64_t P, float nf,
+                            int vec_ok, hipStream_t s)
+{
+    const dim3 grid((unsigned)tiles_for(P)), block(BLOCK);
+    if (dt == ABS_BF16)
+        hipLaunchKernelGGL((accumulate_flat<FIRST, true>), grid, block, 0, s, acc, grad, P, nf, vec_ok);
+    else
+        hipLaunchKernelGGL((accumulate_flat<FIRST, false>), grid, block, 0, s, acc, grad, P, nf, vec_ok);
+}
+
+template <int K>
+void launch_sync_flat_k(float *x, float *v, const float *const *ptrs, int64_t P, Hyper h,
+                        int vec_ok, hipStream_t s)
+{
+    AccPtrs<K> A;
+    for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
+    hipLaunchKernelGGL((sync_update_flat<K>), dim3((unsigned)tiles_for(P)), dim3(BLOCK), 0, s, x, v,
+                       A, P, h, vec_ok);
+}
+
+void launch_sync_flat(float *x, float *v, const float *const *ptrs, int n, int64_t P, Hyper h,
+                      int vec_ok, hipStream_t s)
+{
+    switch (n) {
+#define ABS_CASE(K) case K: launch_sync_flat_k<K>(x, v, ptrs, P, h, vec_ok, s); break;
+        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
+        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
+        ABS_CASE(16)
+#undef ABS_CASE
+    default: {
+        AccPtrsAny A;
+        std::memset(&A, 0, sizeof A);
+        for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
+        hipLaunchKernelGGL(sync_update_flat_any, dim3((unsigned)tiles_for(P)), dim3(BLOCK), 0, s, x, v,
+                           A, n, P, h, vec_ok);
+    }
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- ragged types
+
+struct abs_layout {
+    std::vector<int64_t> sizes;
+    std::vector<Chunk> chunks;
+    int64_t total = 0;
+    // device copies, made on first use
+    Chunk *d_chunks = nullptr;
+    int64_t *d_sizes = nullptr;
+    int device = -1;
+};
+
+struct abs_tensorset {
+    const abs_layout *layout = nullptr;
+    abs_dtype elem = ABS_F32;
+    std::vector<void *> ptrs;
+    void **d_tab = nullptr;
+};
+
+struct abs_ctx {
+    int K = 0;
+    int64_t P = 0;                       // flat form
+    abs_layout *layout = nullptr;        // ragged form (else null)
+    std::vector<float *> acc[2];         // flat: [generation][k]
+    std::vector<const abs_tensorset *> set[2];
+    std::vector<int64_t> counts[2];
+    int cur = 0;
+    hipStream_t s_acc = nullptr, s_upd = nullptr;
+    hipEvent_t ev_acc = nullptr, ev_upd = nullptr;
+};
+
+namespace {
+
+int layout_to_device(abs_layout *L)
+{
+    int dev = 0;
+    ABS_HIP(hipGetDevice(&dev));
+    if (L->d_chunks) return L->device == dev ? ABS_OK : ABS_EINVAL;
+    if (L->chunks.empty()) { L->device = dev; return ABS_OK; }
+    Chunk *dc = nullptr;
+    int64_t *ds = nullptr;
+    ABS_HIP(hipMalloc(&dc, L->chunks.size() * sizeof(Chunk)));
+    hipError_t e = hipMalloc(&ds, L->sizes.size() * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMemcpy(dc, L->chunks.data(), L->chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ds, L->sizes.data(), L->sizes.size() * sizeof(int64_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dc);
+        if (ds) (void)hipFree(ds);
+        return hip_fail(e);
+    }
+    L->d_chunks = dc;
+    L->d_sizes = ds;
+    L->device = dev;
+    return ABS_OK;
+}
+
+template <int K>
+void launch_sync_ragged_k(const abs_layout *L, float *const *xt, float *const *vt,
+                          const float *const *const *tabs, Hyper h, hipStream_t s)
+{
+    TabPtrs<K> T;
+    for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
+    hipLaunchKernelGGL((sync_update_ragged<K>), dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
+                       L->d_chunks, L->d_sizes, xt, vt, T, h);
+}
+
+void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
+                        const float *const *const *tabs, int n, Hyper h, hipStream_t s)
+{
+    switch (n) {
+#define ABS_CASE(K) case K: launch_sync_ragged_k<K>(L, xt, vt, tabs, h, s); break;
+        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
+        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
+        ABS_CASE(16)
+#undef ABS_CASE
+    default: {
+        TabPtrsAny T;
+        std::memset(&T, 0, sizeof T);
+        for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
+        hipLaunchKernelGGL(sync_update_ragged_any, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
+                           L->d_chunks, L->d_sizes, xt, vt, T, n, h);
+    }
+    }
+}
+
+bool set_ok(const abs_tensorset *s, const abs_layout *L) { return s && s->layout == L; }
+
+}  // namespace
+
+// =========================================================================
+// C ABI
+// =========================================================================
+extern "C" {
+
+int abs_version(void) { return 100; }
+
+int abs_last_hip_error(void) { return g_last_hip_error; }
+
+const char *abs_error_string(int rc)
+{
+    switch (rc) {
+    case ABS_OK: return "ok";
+    case ABS_EMPTY: return "nothing to apply (total sample count is zero)";
+    case ABS_EINVAL: return "invalid argument";
+    case ABS_EHIP: return "HIP runtime call failed (see abs_last_hip_error)";
+    default: return "unknown return code";
+    }
+}
+
+int64_t abs_tile_elems(void) { return TILE; }
+
+// ------------------------------------------------------------------ flat
+
+int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
+                   int64_t n_samples, int64_t *count, void *stream)
+{
+    if (!count || P < 0 || n_samples <= 0 || *count < 0) return ABS_EINVAL;
+    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
+    if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
+    if (P > 0) {
+        if (!acc || !grad) return ABS_EINVAL;
+        const uintptr_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
+        if (!aligned_to(acc, 4) || !aligned_to(grad, gsz)) return ABS_EINVAL;
+        if (tiles_for(P) > kMaxGrid) return ABS_EINVAL;
+        const int vec_ok = aligned_to(acc, 16) && aligned_to(grad, grad_dtype == ABS_BF16 ? 8 : 16);
+        const float nf = (float)n_samples;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (*count == 0) launch_accumulate_flat<true>(acc, grad, grad_dtype, P, nf, vec_ok, s);
+        else launch_accumulate_flat<false>(acc, grad, grad_dtype, P, nf, vec_ok, s);
+        int rc = launch_status();
+        if (rc != ABS_OK) return rc;
+    }
+    *count += n_samples;
+    return ABS_OK;
+}
+
+int abs_sync_update(float *params, float *momentum, const float *const *acc,
+                    const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                    void *stream)
+{
+    if (!acc || P < 0) return ABS_EINVAL;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK) return rc;
+    if (P == 0) return ABS_OK;
+    if (!params || !momentum || params == momentum) return ABS_EINVAL;
+    if (!aligned_to(params, 4) || !aligned_to(momentum, 4)) return ABS_EINVAL;
+    if (tiles_for(P) > kMaxGrid) return ABS_EINVAL;
+    const float *ptrs[ABS_MAX_K];
+    bool vec = aligned_to(params, 16) && aligned_to(momentum, 16);
+    for (int j = 0; j < c.n; ++j) {
+        const float *p = acc[c.idx[j]];
+        if (!p || !aligned_to(p, 4)) return ABS_EINVAL;
+        vec = vec && aligned_to(p, 16);
+        ptrs[j] = p;
+    }
+    const Hyper h = {(float)c.M, lr, mu, wd};
+    launch_sync_flat(params, momentum, ptrs, c.n, P, h, vec ? 1 : 0, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+// ---------------------------------------------------------------- ragged
+
+int abs_layout_create(abs_layout **out, int T, const int64_t *sizes)
+{
+    if (!out || T < 1 || !sizes) return ABS_EINVAL;
+    abs_layout *L = new (std::nothrow) abs_layout;
+    if (!L) return ABS_EINVAL;
+    int64_t nchunks = 0;
+    for (int t = 0; t < T; ++t) {
+        if (sizes[t] < 0 || tiles_for(sizes[t]) > kMaxGrid ||
+            L->total > std::numeric_limits<int64_t>::max() - sizes[t]) {
+            delete L;
+            return ABS_EINVAL;
+        }
+        L->total += sizes[t];
+        nchunks += tiles_for(sizes[t]);
+    }
+    if (nchunks > kMaxGrid) { delete L; return ABS_EINVAL; }
+    L->sizes.assign(sizes, sizes + T);
+    L->chunks.reserve((size_t)nchunks);
+    // Tensor order, tile order within a tensor: consecutive workgroups stream
+    // consecutive memory of one tensor.
+    for (int t = 0; t < T; ++t)
+        for (int64_t i = 0, n = tiles_for(sizes[t]); i < n; ++i)
+            L->chunks.push_back(Chunk{(int32_t)t, (int32_t)i});
+    *out = L;
+    return ABS_OK;
+}
+
+int abs_layout_destroy(abs_layout *L)
+{
+    if (!L) return ABS_EINVAL;
+    if (L->d_chunks) (void)hipFree(L->d_chunks);
+    if (L->d_sizes) (void)hipFree(L->d_sizes);
+    delete L;
+    return ABS_OK;
+}
+
+int abs_layout_num_tensors(const abs_layout *L) { return L ? (int)L->sizes.size() : ABS_EINVAL; }
+int64_t abs_layout_total(const abs_layout *L) { return L ? L->total : ABS_EINVAL; }
+int64_t abs_layout_num_chunks(const abs_layout *L) { return L ? (int64_t)L->chunks.size() : ABS_EINVAL; }
+
+int abs_layout_chunk(const abs_layout *L, int64_t c, int *tensor, int64_t *offset, int64_t *len)
+{
+    if (!L || c < 0 || c >= (int64_t)L->chunks.size() || !tensor || !offset || !len) return ABS_EINVAL;
+    const Chunk ch = L->chunks[(size_t)c];
+    *tensor = ch.tensor;
+    *offset = (int64_t)ch.index * TILE;
+    const int64_t rest = L->sizes[(size_t)ch.tensor] - *offset;
+    *len = rest < TILE ? rest : TILE;
+    return ABS_OK;
+}
+
+int abs_tensorset_create(abs_tensorset **out, const abs_layout *L, void *const *ptrs, abs_dtype elem)
+{
+    if (!out || !L || !ptrs) return ABS_EINVAL;
+    if (elem != ABS_F32 && elem != ABS_BF16) return ABS_EINVAL;
+    const size_t T = L->sizes.size();
+    const uintptr_t esz = elem == ABS_BF16 ? 2 : 4;
+    for (size_t t = 0; t < T; ++t) {
+        if (L->sizes[t] > 0 && (!ptrs[t] || !aligned_to(ptrs[t], esz))) return ABS_EINVAL;
+    }
+    abs_tensorset *S = new (std::nothrow) abs_tensorset;
+    if (!S) return ABS_EINVAL;
+    S->layout = L;
+    S->elem = elem;
+    S->ptrs.assign(ptrs, ptrs + T);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&S->d_tab), T * sizeof(void *));
+    if (e == hipSuccess) e = hipMemcpy(S->d_tab, S->ptrs.data(), T * sizeof(void *), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (S->d_tab) (void)hipFree(S->d_tab);
+        delete S;
+        return hip_fail(e);
+    }
+    *out = S;
+    return ABS_OK;
+}
+
+int abs_tensorset_destroy(abs_tensorset *S)
+{
+    if (!S) return ABS_EINVAL;
+    if (S->d_tab) (void)hipFree(S->d_tab);
+    delete S;
+    return ABS_OK;
+}
+
+int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *grad,
+                      int64_t n_samples, int64_t *count, void *stream)
+{
+    if (!L || !set_ok(acc, L) || !set_ok(grad, L) || acc->elem != ABS_F32) return ABS_EINVAL;
+    if (!count || n_samples <= 0 || *count < 0) return ABS_EINVAL;
+    if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
+    if (!L->chunks.empty()) {
+        int rc = layout_to_device(L);
+        if (rc != ABS_OK) return rc;
+        const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
+        const float nf = (float)n_samples;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        float *const *at = reinterpret_cast<float *const *>(acc->d_tab);
+        const void *const *gt = reinterpret_cast<const void *const *>(grad->d_tab);
+        const bool first = *count == 0, bf = grad->elem == ABS_BF16;
+        if (first && bf) hipLaunchKernelGGL((accumulate_ragged<true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
+        else if (first) hipLaunchKernelGGL((accumulate_ragged<true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
+        else if (bf) hipLaunchKernelGGL((accumulate_ragged<false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
+        else hipLaunchKernelGGL((accumulate_ragged<false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
+        rc = launch_status();
+        if (rc != ABS_OK) return rc;
+    }
+    *count += n_samples;
+    return ABS_OK;
+}
+
+int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                       const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                       float mu, float wd, void *stream)
+{
+    if (!L || !acc) return ABS_EINVAL;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK) return rc;
+    if (!set_ok(params, L) || !set_ok(momentum, L) || params == momentum) return ABS_EINVAL;
+    if (params->elem != ABS_F32 || momentum->elem != ABS_F32) return ABS_EINVAL;
+    const float *const *tabs[ABS_MAX_K];
+    for (int j = 0; j < c.n; ++j) {
+        const abs_tensorset *s = acc[c.idx[j]];
+        if (!set_ok(s, L) || s->elem != ABS_F32) return ABS_EINVAL;
+        tabs[j] = reinterpret_cast<const float *const *>(s->d_tab);
+    }
+    if (L->chunks.empty()) return ABS_OK;
+    rc = layout_to_device(L);
+    if (rc != ABS_OK) return rc;
+    const Hyper h = {(float)c.M, lr, mu, wd};
+    launch_sync_ragged(L, reinterpret_cast<float *const *>(params->d_tab),
+                       reinterpret_cast<float *const *>(momentum->d_tab), tabs, c.n, h,
+                       static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+// --------------------------------------------------------- double buffer
+
+static int ctx_common(abs_ctx *C, int K, void *stream_acc, void *stream_upd)
+{
+    C->K = K;
+    C->counts[0].assign((size_t)K, 0);
+    C->counts[1].assign((size_t)K, 0);
+    C->s_acc = static_cast<hipStream_t>(stream_acc);
+    C->s_upd = static_cast<hipStream_t>(stream_upd);
+    if (C->s_acc != C->s_upd) {
+        ABS_HIP(hipEventCreateWithFlags(&C->ev_acc, hipEventDisableTiming));
+        ABS_HIP(hipEventCreateWithFlags(&C->ev_upd, hipEventDisableTiming));
+    }
+    return ABS_OK;
+}
+
+int abs_ctx_create(abs_ctx **out, int K, int64_t P, float *const *acc_A, float *const *acc_B,
+                   void *stream_acc, void *stream_upd)
+{
+    if (!out || K < 1 || K > ABS_MAX_K || P < 0 || !acc_A || !acc_B) return ABS_EINVAL;
+    for (int k = 0; k < K; ++k) {
+        if (P > 0 && (!acc_A[k] || !acc_B[k] || acc_A[k] == acc_B[k])) return ABS_EINVAL;
+        if (!aligned_to(acc_A[k], 4) || !aligned_to(acc_B[k], 4)) return ABS_EINVAL;
+    }
+    abs_ctx *C = new (std::nothrow) abs_ctx;
+    if (!C) return ABS_EINVAL;
+    C->P = P;
+    C->acc[0].assign(acc_A, acc_A + K);
+    C->acc[1].assign(acc_B, acc_B + K);
+    int rc = ctx_common(C, K, stream_acc, stream_upd);
+    if (rc != ABS_OK) { abs_ctx_destroy(C); return rc; }
+    *out = C;
+    return ABS_OK;
+}
+
+int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *L, const abs_tensorset *const *acc_A,
+                      const abs_tensorset *const *acc_B, void *stream_acc, void *stream_upd)
+{
+    if (!out || K < 1 || K > ABS_MAX_K || !L || !acc_A || !acc_B) return ABS_EINVAL;
+    for (int k = 0; k < K; ++k) {
+        if (!set_ok(acc_A[k], L) || !set_ok(acc_B[k], L) || acc_A[k] == acc_B[k]) return ABS_EINVAL;
+        if (acc_A[k]->elem != ABS_F32 || acc_B[k]->elem != ABS_F32) return ABS_EINVAL;
+    }
+    abs_ctx *C = new (std::nothrow) abs_ctx;
+    if (!C) return ABS_EINVAL;
+    C->layout = L;
+    C->P = L->total;
+    C->set[0].assign(acc_A, acc_A + K);
+    C->set[1].assign(acc_B, acc_B + K);
+    int rc = ctx_common(C, K, stream_acc, stream_upd);
+    if (rc != ABS_OK) { abs_ctx_destroy(C); return rc; }
+    *out = C;
+    return ABS_OK;
+}
+
+int abs_ctx_destroy(abs_ctx *C)
+{
+    if (!C) return ABS_EINVAL;
+    if (C->ev_acc) (void)hipEventDestroy(C->ev_acc);
+    if (C->ev_upd) (void)hipEventDestroy(C->ev_upd);
+    delete C;
+    return ABS_OK;
+}
+
+int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype, int64_t n_samples)
+{
+    if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    return abs_accumulate(C->acc[C->cur][(size_t)k], grad, grad_dtype, C->P, n_samples,
+                          &C->counts[C->cur][(size_t)k], C->s_acc);
+}
+
+int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
+{
+    if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    return abs_accumulate_mt(C->layout, C->set[C->cur][(size_t)k], grad, n_samples,
+                             &C->counts[C->cur][(size_t)k], C->s_acc);
+}
+
+int abs_ctx_sync_update(abs_ctx *C, float *params, float *momentum, float lr, float mu, float wd)
+{
+    if (!C || C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update(params, momentum, C->acc[prev].data(), C->counts[prev].data(), C->K, C->P,
+                           lr, mu, wd, C->s_upd);
+}
+
+int abs_ctx_sync_update_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *momentum,
+                           float lr, float mu, float wd)
+{
+    if (!C || !C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_mt(C->layout, params, momentum, C->set[prev].data(), C->counts[prev].data(),
+                              C->K, lr, mu, wd, C->s_upd);
+}
+
+int abs_swap_buffers(abs_ctx *C)
+{
+    if (!C) return ABS_EINVAL;
+    if (C->s_acc != C->s_upd) {
+        // next sync-update reads what accumulation has written so far
+        ABS_HIP(hipEventRecord(C->ev_acc, C->s_acc));
+        // next accumulation overwrites what the sync-update has been reading
+        ABS_HIP(hipEventRecord(C->ev_upd, C->s_upd));
+        ABS_HIP(hipStreamWaitEvent(C->s_upd, C->ev_acc, 0));
+        ABS_HIP(hipStreamWaitEvent(C->s_acc, C->ev_upd, 0));
+    }
+    C->cur ^= 1;
+    for (auto &c : C->counts[C->cur]) c = 0;
+    return ABS_OK;
+}
+
+int abs_ctx_counts(const abs_ctx *C, int which, int64_t *out)
+{
+    if (!C || !out || (which != 0 && which != 1)) return ABS_EINVAL;
+    const auto &c = C->counts[which == 0 ? C->cur : C->cur ^ 1];
+    for (int k = 0; k < C->K; ++k) out[k] = c[(size_t)k];
+    return ABS_OK;
+}
+
+}  // extern "C"

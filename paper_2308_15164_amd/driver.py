@@ -1,0 +1,136 @@
+"""Sequencing of the library calls for one workload: the loop of Algorithm 1 as
+seen from one GPU, where the K workers are K device-resident accumulators.
+
+This module allocates device memory through PyTorch, uploads host-generated
+inputs, and issues abs_accumulate / abs_sync_update / abs_swap_buffers in the
+order of Algorithm 1.  It computes nothing itself.
+"""
+import numpy as np
+import torch
+
+import abs_workloads as wl
+
+from . import ABS_BF16, ABS_F32, Context, Layout, TensorSet
+
+
+def _upload(a):
+    """numpy -> device tensor; uint16 bf16 bit patterns travel as int16."""
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+class DeviceRun:
+    """Device state and call sequence for one workload.
+
+    overlap=True : accumulation on one stream, sync-update on another (double
+                   buffer in use, the configuration the benchmark times);
+    overlap=False: both on one stream, in program order.
+    """
+
+    def __init__(self, w, x0, pool, schedule, overlap=True, P=None):
+        self.w = w
+        self.P = int(w.P if P is None else P)
+        self.K = w.K
+        self.m = np.asarray(schedule)
+        self.gdt = ABS_BF16 if w.grad_dtype == "bf16" else ABS_F32
+        self.ragged = w.tensor_sizes is not None
+        dev = torch.device("cuda:0")
+        self.s_acc = torch.cuda.Stream(device=dev)
+        self.s_upd = torch.cuda.Stream(device=dev) if overlap else self.s_acc
+        if not self.ragged:
+            self.x = _upload(np.ascontiguousarray(x0, dtype=np.float32))
+            self.v = torch.zeros_like(self.x)
+            self.acc = [[torch.empty_like(self.x) for _ in range(self.K)] for _ in range(2)]
+            # stale garbage on purpose: accumulation must overwrite, never rely on zeros
+            for gen in self.acc:
+                for a in gen:
+                    a.fill_(float("nan"))
+            self.pool = [_upload(g) for g in pool]
+            self.pool_ptr = [g.data_ptr() for g in self.pool]
+            torch.cuda.synchronize()
+            self.ctx = Context(self.acc[0], self.acc[1], self.s_acc, self.s_upd, P=self.P)
+            self.x_arg, self.v_arg = self.x.data_ptr(), self.v.data_ptr()
+        else:
+            sizes = list(w.tensor_sizes)
+            off = wl.tensor_offsets(sizes)
+            self.layout = Layout(sizes)
+
+            def split(a):
+                # one separate allocation per tensor, as a framework would hold them
+                return [_upload(np.ascontiguousarray(a[off[t]:off[t + 1]])) for t in range(len(sizes))]
+
+            self.x_t = split(np.ascontiguousarray(x0, dtype=np.float32))
+            self.v_t = [torch.zeros_like(t) for t in self.x_t]
+            self.acc_t = [[[torch.full_like(t, float("nan")) for t in self.x_t]
+                           for _ in range(self.K)] for _ in range(2)]
+            self.pool_t = [split(g) for g in pool]
+            torch.cuda.synchronize()
+            self.x_set = TensorSet(self.layout, self.x_t)
+            self.v_set = TensorSet(self.layout, self.v_t)
+            self.acc_sets = [[TensorSet(self.layout, self.acc_t[g][k]) for k in range(self.K)]
+                             for g in range(2)]
+            self.pool_sets = [TensorSet(self.layout, p, dtype=self.gdt) for p in self.pool_t]
+            self.ctx = Context(self.acc_sets[0], self.acc_sets[1], self.s_acc, self.s_upd,
+                               layout=self.layout)
+            self.x_arg, self.v_arg = self.x_set, self.v_set
+        self.lr, self.mu, self.wd = float(w.lr), float(w.mu), float(w.wd)
+        self.applied = []
+        self.count_history = []
+
+    def grad_arg(self, r):
+        return self.pool_sets[r] if self.ragged else self.pool_ptr[r]
+
+    def plan_step(self, t, pool_size=None):
+        """[(worker, gradient argument)] for step t, in issue order."""
+        R = len(self.pool_sets if self.ragged else self.pool) if pool_size is None else pool_size
+        calls = []
+        for k in range(self.K):
+            for j in range(int(self.m[t, k])):
+                calls.append((k, self.grad_arg(wl.pool_index(self.w, t, k, j, R))))
+        return calls
+
+    def step(self, t, calls=None):
+        """One iteration of Algorithm 1: Step 1 + update on the delayed generation,
+        Step 2 (accumulation) on the current one, then the swap."""
+        ctx, n, gdt = self.ctx, self.w.n, self.gdt
+        applied = ctx.abs_sync_update(self.x_arg, self.v_arg, self.lr, self.mu, self.wd)
+        for k, g in (self.plan_step(t) if calls is None else calls):
+            ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+        ctx.abs_swap_buffers()
+        return applied
+
+    def run(self, steps, record_counts=True):
+        for t in range(steps):
+            self.applied.append(self.step(t))
+            if record_counts:
+                self.count_history.append(self.ctx.counts(1))   # just-finished generation
+        torch.cuda.synchronize()
+
+    def read_state(self):
+        torch.cuda.synchronize()
+        if not self.ragged:
+            return self.x.cpu().numpy(), self.v.cpu().numpy()
+        return (np.concatenate([t.cpu().numpy() for t in self.x_t]),
+                np.concatenate([t.cpu().numpy() for t in self.v_t]))
+
+    def read_state_at(self, idx):
+        """x and v at flat element indices idx (ragged: indices into the concatenation)."""
+        torch.cuda.synchronize()
+        if not self.ragged:
+            i = torch.from_numpy(np.asarray(idx)).cuda()
+            return self.x[i].cpu().numpy(), self.v[i].cpu().numpy()
+        off = wl.tensor_offsets(self.w.tensor_sizes)
+        idx = np.asarray(idx)
+        tens = np.searchsorted(off, idx, side="right") - 1
+        xs = np.empty(idx.size, dtype=np.float32)
+        vs = np.empty(idx.size, dtype=np.float32)
+        for t in np.unique(tens):
+            sel = np.nonzero(tens == t)[0]
+            loc = torch.from_numpy(idx[sel] - off[t]).cuda()
+            xs[sel] = self.x_t[t][loc].cpu().numpy()
+            vs[sel] = self.v_t[t][loc].cpu().numpy()
+        return xs, vs
+
+    def close(self):
+        self.ctx.close()

@@ -1,0 +1,116 @@
+"""CPU tests of the boundary: the C-ABI library loads, exports every symbol the
+header declares, and its host-side logic (argument checks, ragged chunk table,
+empty-step detection) behaves as the header states.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2308_15164_amd as absgd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "abs_sgd.h")
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(abs_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = absgd.lib()
+    declared = _declared_symbols()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in abs_sgd.h but not exported"
+    # and the binding marshals exactly that set
+    assert sorted(absgd.SYMBOLS) == declared
+
+
+def test_version_tile_and_error_strings():
+    assert absgd.abs_version() >= 100
+    tile = absgd.abs_tile_elems()
+    assert tile > 0 and tile % 1024 == 0
+    L = absgd.lib()
+    assert b"invalid" in L.abs_error_string(absgd.ABS_EINVAL)
+    assert L.abs_error_string(absgd.ABS_OK) == b"ok"
+
+
+def _rc_accumulate(acc, grad, dtype, P, n, count):
+    c = ctypes.c_int64(count)
+    rc = absgd.lib().abs_accumulate(acc, grad, dtype, P, n, ctypes.byref(c), None)
+    return rc, c.value
+
+
+def test_accumulate_rejects_bad_arguments_before_touching_the_gpu():
+    assert _rc_accumulate(None, 16, absgd.ABS_F32, 8, 32, 0)[0] == absgd.ABS_EINVAL     # null acc
+    assert _rc_accumulate(16, None, absgd.ABS_F32, 8, 32, 0)[0] == absgd.ABS_EINVAL     # null grad
+    assert _rc_accumulate(16, 32, absgd.ABS_F32, -1, 32, 0)[0] == absgd.ABS_EINVAL      # P < 0
+    assert _rc_accumulate(16, 32, absgd.ABS_F32, 8, 0, 0)[0] == absgd.ABS_EINVAL        # n <= 0
+    assert _rc_accumulate(16, 32, absgd.ABS_F32, 8, 32, -5)[0] == absgd.ABS_EINVAL      # count < 0
+    assert _rc_accumulate(18, 32, absgd.ABS_F32, 8, 32, 0)[0] == absgd.ABS_EINVAL       # acc not 4-aligned
+    assert _rc_accumulate(16, 33, absgd.ABS_BF16, 8, 32, 0)[0] == absgd.ABS_EINVAL      # bf16 not 2-aligned
+    assert _rc_accumulate(16, 32, 7, 8, 32, 0)[0] == absgd.ABS_EINVAL                   # dtype
+    assert _rc_accumulate(16, 32, absgd.ABS_F32, 8, 2, 2**63 - 2)[0] == absgd.ABS_EINVAL  # overflow
+    # failed calls leave the count alone
+    assert _rc_accumulate(None, 16, absgd.ABS_F32, 8, 32, 64)[1] == 64
+    # P == 0: nothing to launch, only the integer moves (bit-exact counts)
+    rc, cnt = _rc_accumulate(None, None, absgd.ABS_F32, 0, 32, 64)
+    assert rc == absgd.ABS_OK and cnt == 96
+
+
+def _rc_sync(x, v, ptrs, counts, P, K=None):
+    K = len(ptrs) if K is None else K
+    arr = (ctypes.c_void_p * max(1, len(ptrs)))(*ptrs)
+    cnt = (ctypes.c_int64 * max(1, len(counts)))(*counts)
+    return absgd.lib().abs_sync_update(x, v, arr, cnt, K, P, 0.1, 0.9, 5e-4, None)
+
+
+def test_sync_update_empty_and_bad_arguments():
+    # total count zero: the first iteration applies nothing, whatever the pointers are
+    assert _rc_sync(16, 32, [48, 64], [0, 0], 8) == absgd.ABS_EMPTY
+    assert _rc_sync(16, 32, [48, 64], [32, -1], 8) == absgd.ABS_EINVAL
+    assert _rc_sync(16, 32, [48], [32], 8, K=0) == absgd.ABS_EINVAL
+    assert _rc_sync(16, 32, [48] * 65, [32] * 65, 8) == absgd.ABS_EINVAL      # K > ABS_MAX_K
+    assert _rc_sync(None, 32, [48], [32], 8) == absgd.ABS_EINVAL
+    assert _rc_sync(16, 16, [48], [32], 8) == absgd.ABS_EINVAL                 # x aliases v
+    assert _rc_sync(16, 32, [None], [32], 8) == absgd.ABS_EINVAL               # non-empty worker, null buffer
+    assert _rc_sync(16, 32, [48], [32], -3) == absgd.ABS_EINVAL
+    assert _rc_sync(16, 32, [48], [32], 0) == absgd.ABS_OK                     # P == 0
+
+
+@pytest.mark.parametrize("sizes", [[1], [0, 5, 0], [4096], [4097, 1, 8192, 3], [12289, 768, 100000]])
+def test_layout_chunk_table_partitions_every_tensor(sizes):
+    tile = absgd.abs_tile_elems()
+    lay = absgd.Layout(sizes)
+    assert lay.num_tensors() == len(sizes)
+    assert lay.total() == sum(sizes)
+    expected = sum((s + tile - 1) // tile for s in sizes)
+    assert lay.num_chunks() == expected
+    covered = [np.zeros(s, dtype=np.int32) for s in sizes]
+    for c in range(lay.num_chunks()):
+        t, off, ln = lay.chunk(c)
+        assert 0 < ln <= tile and off % tile == 0 and off + ln <= sizes[t]
+        covered[t][off:off + ln] += 1
+    for cov in covered:
+        assert np.all(cov == 1)          # every element in exactly one chunk
+    assert absgd.lib().abs_layout_chunk(lay.handle, lay.num_chunks(), None, None, None) == absgd.ABS_EINVAL
+    lay.close()
+
+
+def test_layout_rejects_bad_sizes():
+    h = ctypes.c_void_p()
+    L = absgd.lib()
+    assert L.abs_layout_create(ctypes.byref(h), 0, (ctypes.c_int64 * 1)(1)) == absgd.ABS_EINVAL
+    assert L.abs_layout_create(ctypes.byref(h), 2, (ctypes.c_int64 * 2)(5, -1)) == absgd.ABS_EINVAL
+    assert L.abs_layout_create(None, 1, (ctypes.c_int64 * 1)(1)) == absgd.ABS_EINVAL
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(absgd, "_lib", None)
+    monkeypatch.setattr(absgd, "LIB_PATH", "/nonexistent/libabs_sgd.so")
+    with pytest.raises(ImportError, match="no CPU or PyTorch fallback"):
+        absgd.lib()

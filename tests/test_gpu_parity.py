@@ -1,0 +1,349 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars (written out here, derived in the design doc):
+  * sample counts: exact integers;
+  * against the fixed-order fp32 oracle: bit for bit;
+  * against the double oracle (the judge of accuracy):
+      - norm-wise   max|d| <= 1e-5 * max|ref|,
+      - element-wise |d_i| <= 1e-5 * (magnitude of the operands that formed element i),
+        which is the relative-error bar wherever no cancellation occurs.
+    The naive element-wise relative error is printed for information: where
+    x - lr*v cancels to ~0 it is unbounded for ANY fp32 implementation.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+import abs_workloads as wl
+from oracle import abs_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+F32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def absgd():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2308_15164_amd as m
+    m.lib()                      # fails loudly if the HIP library is missing
+    return m
+
+
+def _up(a):
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _bits(a):
+    return np.ascontiguousarray(a, dtype=F32).view(np.uint32)
+
+
+def _assert_bitexact(got, want, what):
+    gb, wb = _bits(got), _bits(want)
+    bad = np.nonzero(gb != wb)[0]
+    assert bad.size == 0, (f"{what}: {bad.size} of {gb.size} elements differ in bits; first at {bad[0]}: "
+                           f"got {got[bad[0]]!r} want {want[bad[0]]!r}")
+
+
+def _assert_close64(got, ref, scale, what):
+    """got fp32, ref float64, scale = per-element operand magnitude (float64)."""
+    d = np.abs(got.astype(np.float64) - ref)
+    assert np.max(d) <= RTOL * max(np.max(np.abs(ref)), 1e-300), f"{what}: norm-wise bar missed"
+    bad = np.nonzero(d > RTOL * scale + 1e-300)[0]
+    assert bad.size == 0, f"{what}: {bad.size} elements beyond 1e-5 of their operands; first {bad[0]}"
+    with np.errstate(divide="ignore", invalid="ignore"):
+        naive = np.where(ref != 0, d / np.abs(ref), 0.0)
+    return float(np.max(naive)), int(np.count_nonzero(naive > RTOL))
+
+
+def _grad(rng, P, dtype, sigma=0.01):
+    g = (rng.standard_normal(P) * sigma).astype(F32)
+    return wl.to_bf16_bits(g) if dtype == "bf16" else g
+
+
+# ---------------------------------------------------------------------------
+# abs_accumulate, call by call
+# ---------------------------------------------------------------------------
+
+SIZES = [1, 3, 4, 7, 255, 1024, 4095, 4096, 4097, 3 * 4096 + 5, 8 * 4096, 100_003, 1_048_576 + 13]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("P", SIZES)
+def test_accumulate_matches_oracle(absgd, dtype, P):
+    print(f"[case] accumulate dtype={dtype} P={P}", flush=True)
+    rng = np.random.default_rng(P * 2 + (dtype == "bf16"))
+    grads = [_grad(rng, P, dtype) for _ in range(3)]
+    n_list = [32, 64, 7]
+    acc_d = torch.full((P,), float("nan"), device="cuda")       # stale garbage before the first call
+    cnt = absgd.Count(0)
+    G64 = np.zeros(P)
+    G32 = np.zeros(P, dtype=F32)
+    M = 0
+    for j, (g, n) in enumerate(zip(grads, n_list)):
+        g_d = _up(g)
+        absgd.abs_accumulate(acc_d, g_d, n, cnt)
+        orc.accumulate(G64, g, n)
+        orc.accumulate32(G32, g, n, first=(M == 0))
+        M += n
+        assert cnt.value == M
+        got = acc_d.cpu().numpy()
+        _assert_bitexact(got, G32, f"accumulate call {j}")
+        gf = (g.astype(np.uint32) << 16).view(F32) if dtype == "bf16" else g
+        scale = np.abs(G64) + n * np.abs(gf.astype(np.float64))
+        _assert_close64(got, G64, scale, f"accumulate call {j}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_accumulate_unaligned_views(absgd, dtype, shift):
+    """Bases that are element-aligned but not 16-byte aligned take the
+    element-wise path and must give the same bits."""
+    print(f"[case] accumulate unaligned dtype={dtype} shift={shift}", flush=True)
+    P = 2 * 4096 + 37
+    rng = np.random.default_rng(77 + shift)
+    g1, g2 = _grad(rng, P, dtype), _grad(rng, P, dtype)
+    acc_buf = torch.full((P + 8,), float("nan"), device="cuda")
+    acc_d = acc_buf[shift:shift + P]
+    cnt = absgd.Count(0)
+    G32 = np.zeros(P, dtype=F32)
+    for j, g in enumerate((g1, g2)):
+        pad = np.zeros(P + 8, dtype=g.dtype)
+        pad[shift:shift + P] = g
+        g_d = _up(pad)[shift:shift + P]
+        absgd.abs_accumulate(acc_d, g_d, 32, cnt)
+        orc.accumulate32(G32, g, 32, first=(j == 0))
+    _assert_bitexact(acc_d.cpu().numpy(), G32, "unaligned accumulate")
+    guard = acc_buf.cpu().numpy()
+    assert np.all(np.isnan(guard[:shift])) and np.all(np.isnan(guard[shift + P:]))   # nothing written outside
+
+
+def test_accumulate_zero_length_and_large_count(absgd):
+    cnt = absgd.Count(2**40)
+    acc_d = torch.zeros(4, device="cuda")
+    absgd.abs_accumulate(acc_d, acc_d, 32, cnt, P=0)
+    assert cnt.value == 2**40 + 32
+
+
+# ---------------------------------------------------------------------------
+# abs_sync_update, call by call
+# ---------------------------------------------------------------------------
+
+def _sync_case(absgd, K, P, counts, seed, lr=0.1, mu=0.9, wd=5e-4):
+    rng = np.random.default_rng(seed)
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    v0 = (rng.standard_normal(P) * 0.02).astype(F32)
+    accs = [(rng.standard_normal(P) * 0.3 * max(c, 1) / 32).astype(F32) for c in counts]
+    x_d, v_d = _up(x0), _up(v0)
+    acc_d = [_up(a) if c > 0 else torch.full((P,), float("nan"), device="cuda")
+             for a, c in zip(accs, counts)]
+    applied = absgd.abs_sync_update(x_d, v_d, acc_d, counts, lr, mu, wd)
+    x32, v32 = x0.copy(), v0.copy()
+    ok32 = orc.sync_update32(x32, v32, accs, counts, lr, mu, wd)
+    x64, v64 = x0.astype(np.float64), v0.astype(np.float64)
+    # the double oracle sums every worker: idle workers hold zeros there (Step 2 initialisation)
+    G64 = [a.astype(np.float64) if c > 0 else np.zeros(P) for a, c in zip(accs, counts)]
+    lr32, mu32, wd32 = (float(F32(t)) for t in (lr, mu, wd))
+    ok64 = orc.sync_update(x64, v64, G64, counts, lr32, mu32, wd32)
+    assert applied == ok32 == ok64
+    gx, gv = x_d.cpu().numpy(), v_d.cpu().numpy()
+    _assert_bitexact(gx, x32, f"sync x K={K} P={P}")
+    _assert_bitexact(gv, v32, f"sync v K={K} P={P}")
+    if applied:
+        M = float(sum(counts))
+        gbar_mag = sum(np.abs(g) for g in G64) / M
+        v_scale = mu32 * np.abs(v0.astype(np.float64)) + gbar_mag + wd32 * np.abs(x0.astype(np.float64))
+        x_scale = np.abs(x0.astype(np.float64)) + lr32 * v_scale
+        _assert_close64(gv, v64, v_scale, "sync v")
+        _assert_close64(gx, x64, x_scale, "sync x")
+    else:
+        _assert_bitexact(gx, x0, "untouched x")
+        _assert_bitexact(gv, v0, "untouched v")
+
+
+@pytest.mark.parametrize("K", list(range(1, 18)) + [33, 64])
+def test_sync_update_every_worker_count(absgd, K):
+    print(f"[case] sync_update K={K}", flush=True)
+    counts = [32 * (1 + (3 * k) % 5) for k in range(K)]
+    _sync_case(absgd, K, 3 * 4096 + 1029, counts, seed=K)
+
+
+@pytest.mark.parametrize("P", [1, 5, 4096, 4097, 100_003, 1_048_576])
+def test_sync_update_sizes(absgd, P):
+    print(f"[case] sync_update P={P}", flush=True)
+    _sync_case(absgd, 4, P, [64, 64, 128, 256], seed=P)
+
+
+def test_sync_update_idle_workers_and_empty_step(absgd):
+    print("[case] sync_update idle workers", flush=True)
+    _sync_case(absgd, 5, 9001, [0, 96, 0, 32, 0], seed=5)        # stale NaN buffers must not be read
+    _sync_case(absgd, 3, 9001, [0, 0, 0], seed=6)                # first iteration: nothing applied
+    _sync_case(absgd, 20, 9001, [0] * 3 + [32] * 17, seed=7)     # 17 non-empty: the run-time-K kernel
+
+
+def test_sync_update_paper_rule_plain_sgd(absgd):
+    print("[case] sync_update plain SGD", flush=True)
+    _sync_case(absgd, 4, 50_000, [384, 192, 128, 96], seed=8, lr=0.01, mu=0.0, wd=0.0)
+
+
+def test_sync_update_huge_total_count(absgd):
+    print("[case] sync_update huge counts", flush=True)
+    _sync_case(absgd, 2, 5000, [2**33 + 1, 2**31 + 7], seed=9)   # (float)M rounds; both sides round alike
+
+
+def test_sync_update_unaligned_views(absgd):
+    print("[case] sync_update unaligned", flush=True)
+    P, K = 4096 + 11, 3
+    rng = np.random.default_rng(11)
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    v0 = (rng.standard_normal(P) * 0.02).astype(F32)
+    accs = [(rng.standard_normal(P)).astype(F32) for _ in range(K)]
+
+    def shifted(a, s):
+        pad = np.zeros(P + 8, dtype=F32)
+        pad[s:s + P] = a
+        return _up(pad)[s:s + P]
+
+    x_d, v_d = shifted(x0, 1), shifted(v0, 0)
+    acc_d = [shifted(a, s) for a, s in zip(accs, (0, 3, 2))]
+    absgd.abs_sync_update(x_d, v_d, acc_d, [32, 64, 32], 0.1, 0.9, 5e-4)
+    x32, v32 = x0.copy(), v0.copy()
+    orc.sync_update32(x32, v32, accs, [32, 64, 32], 0.1, 0.9, 5e-4)
+    _assert_bitexact(x_d.cpu().numpy(), x32, "unaligned sync x")
+    _assert_bitexact(v_d.cpu().numpy(), v32, "unaligned sync v")
+
+
+# ---------------------------------------------------------------------------
+# whole trajectories through the double-buffered context (Algorithm 1 loop)
+# ---------------------------------------------------------------------------
+
+def _oracle_trajectory(w, x0, pool, sched, steps, precision, R=None):
+    R = len(pool) if R is None else R
+
+    def batches(t, i):
+        return [pool[wl.pool_index(w, t, i, j, R)] for j in range(int(sched[t, i]))]
+
+    return orc.run(x0, w.K, steps, w.n, float(F32(w.lr)), float(F32(w.mu)), float(F32(w.wd)), batches,
+                   precision=precision)
+
+
+def _trajectory_case(absgd, name, steps=None, P=None):
+    from paper_2308_15164_amd.driver import DeviceRun
+    w = wl.WORKLOADS[name]
+    steps = w.steps if steps is None else steps
+    size = w.P if P is None else P
+    x0 = wl.initial_params(w, size)
+    pool = wl.gradient_pool(w, size)
+    sched = wl.schedule(w, steps)
+    out = {}
+    for overlap in (False, True):
+        print(f"[case] trajectory {name} overlap={overlap}", flush=True)
+        run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size)
+        run.run(steps)
+        out[overlap] = run.read_state() + (run.count_history, run.applied)
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+    (xs, vs, cs, aps), (xo, vo, co, apo) = out[False], out[True]
+    # serial == overlapped, bit for bit: the double buffer has no race
+    _assert_bitexact(xo, xs, "overlap vs serial x")
+    _assert_bitexact(vo, vs, "overlap vs serial v")
+    assert cs == co and aps == apo
+    assert aps == [False] + [True] * (steps - 1)       # one-iteration delay: step 0 applies nothing
+
+    x32, v32, h32 = _oracle_trajectory(w, x0, pool, sched, steps, "f32")
+    x64, v64, h64 = _oracle_trajectory(w, x0, pool, sched, steps, "f64")
+    assert cs == h32 == h64                            # sample counts: exact
+    _assert_bitexact(xo, x32, f"{name} x vs fp32 oracle")
+    _assert_bitexact(vo, v32, f"{name} v vs fp32 oracle")
+    scale_x = np.abs(x0.astype(np.float64)) + np.abs(x64) + w.lr * np.abs(v64) * steps
+    scale_v = np.abs(v64) + 10 * w.sigma_g
+    nx = _assert_close64(xo, x64, scale_x, f"{name} x vs double oracle")
+    nv = _assert_close64(vo, v64, scale_v, f"{name} v vs double oracle")
+    print(f"[info] {name}: naive max rel err x={nx[0]:.3e} ({nx[1]} elems > 1e-5), "
+          f"v={nv[0]:.3e} ({nv[1]} elems > 1e-5)", flush=True)
+
+
+def test_trajectory_cfg1(absgd):
+    _trajectory_case(absgd, "cfg1_small")
+
+
+@pytest.mark.parametrize("name", ["tiny_tail_f32", "tiny_tail_bf16", "ragged_odd_f32", "ragged_odd_bf16"])
+def test_trajectory_tails_and_ragged(absgd, name):
+    _trajectory_case(absgd, name)
+
+
+def test_trajectory_paper_rule(absgd):
+    """The paper's own setting (plain SGD, 12:6:4:3 micro-batches) on a short vector."""
+    _trajectory_case(absgd, "paper_static", steps=6, P=300_007)
+
+
+def test_trajectory_delay_invariant_on_gpu(absgd):
+    """x after step t does not depend on step t's gradients."""
+    from paper_2308_15164_amd.driver import DeviceRun
+    print("[case] delay invariant", flush=True)
+    w = wl.WORKLOADS["tiny_tail_f32"]
+    x0 = wl.initial_params(w)
+    pool = wl.gradient_pool(w)
+    sched = wl.schedule(w, 4)
+    res = []
+    for bump in (1, 5):
+        s2 = sched.copy()
+        s2[3] = bump                                        # only the LAST step's accumulation differs
+        run = DeviceRun(w, x0, pool, s2, overlap=True)
+        run.run(4)
+        res.append(run.read_state())
+        run.close()
+    _assert_bitexact(res[0][0], res[1][0], "delay invariant x")
+    _assert_bitexact(res[0][1], res[1][1], "delay invariant v")
+
+
+# ---------------------------------------------------------------------------
+# full BASELINE sizes in the benchmark's launch configuration, sampled outputs
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["cfg2_resnet18", "cfg3_resnet50_bf16", "cfg4_vgg16", "cfg5_gpt2_ragged_bf16"])
+def test_full_size_sampled(absgd, name):
+    """Every output element depends only on the same index of the inputs, so the
+    oracle runs on a sample of indices gathered from the very same host arrays."""
+    from paper_2308_15164_amd.driver import DeviceRun
+    w = wl.WORKLOADS[name]
+    print(f"[case] full size {name}: generating inputs", flush=True)
+    x0 = wl.initial_params(w)
+    R = 4
+    pool = wl.gradient_pool(w, pool=R)
+    sched = wl.schedule(w)
+    print(f"[case] full size {name}: device run, two streams", flush=True)
+    run = DeviceRun(w, x0, pool, sched, overlap=True)
+    run.run(w.steps)
+    idx = wl.sample_indices(w.P, 200_000, w.seed)
+    if w.tensor_sizes is not None:       # both sides of every tensor boundary
+        off = wl.tensor_offsets(w.tensor_sizes)
+        extra = np.concatenate([off[:-1], off[1:] - 1, np.minimum(off[:-1] + 1, w.P - 1)])
+        idx = np.unique(np.concatenate([idx, extra]))
+    gx, gv = run.read_state_at(idx)
+    counts = run.count_history
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+    print(f"[case] full size {name}: oracle on {idx.size} sampled elements", flush=True)
+    x0s = np.ascontiguousarray(x0[idx])
+    pools = [np.ascontiguousarray(g[idx]) for g in pool]
+    x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R)
+    x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R)
+    assert counts == h32 == h64
+    _assert_bitexact(gx, x32, f"{name} sampled x")
+    _assert_bitexact(gv, v32, f"{name} sampled v")
+    scale_x = np.abs(x0s.astype(np.float64)) + np.abs(x64) + w.lr * np.abs(v64) * w.steps
+    scale_v = np.abs(v64) + 10 * w.sigma_g
+    nx = _assert_close64(gx, x64, scale_x, f"{name} x vs double oracle")
+    nv = _assert_close64(gv, v64, scale_v, f"{name} v vs double oracle")
+    print(f"[info] {name}: naive max rel err x={nx[0]:.3e} ({nx[1]} > 1e-5), v={nv[0]:.3e} ({nv[1]} > 1e-5)",
+          flush=True)
