@@ -1,0 +1,304 @@
+#!/usr/bin/env python3
+"""Benchmark of the ABS-SGD hot path on one MI355X.
+
+A step is one iteration of Algorithm 1 as one GPU sees it: the fused
+sync-update of the delayed generation (K accumulators -> x, v) on one stream,
+sum_k m_k accumulate calls into the current generation on another, and the
+swap.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line; see the design doc for the meaning of every field.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+METRIC = "sync-update+accumulate GB/s and % of HBM peak; params/s per step"
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this same command, scaled by what the same counters read
+# for a plain copy of known size (summaries under profiles/).  None = not measured.
+MEASURED_TRAFFIC = {
+    # FETCH_SIZE x 2.000 = 81.88 MB, WRITE_SIZE x 1.000 = 46.75 MB per launch (average over
+    # the 12 read-modify-write and 4 overwrite launches of a step)
+    ("cfg2_resnet18", "absk::accumulate_flat<false, *>"): 128.63e6,
+}
+
+
+def bytes_per_param(w, m_row):
+    """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
+    an accumulate reads one gradient element and reads+writes one fp32
+    accumulator element (the first call of a step only writes it); the
+    sync-update reads K accumulators and reads+writes x and v."""
+    gb = 4 if w.grad_dtype == "f32" else 2
+    acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
+    return acc, 4 * w.K + 16
+
+
+def dominant_kernel(w):
+    """The accumulate kernel: it moves most of a step's bytes in every workload."""
+    bf = "true" if w.grad_dtype == "bf16" else "false"
+    kind = "ragged" if w.tensor_sizes is not None else "flat"
+    return f"absk::accumulate_{kind}<{bf}, *>"
+
+
+def time_steps(run, plans, t0, steps, torch):
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for t in range(t0, t0 + steps):
+        run.step(t, plans[t])
+    torch.cuda.synchronize()
+    return time.perf_counter() - t_start
+
+
+def kernel_event_pass(run, plans, t0, steps, torch):
+    """Replay the timed steps with ONE HIP event pair per step around that step's
+    whole sequence of accumulate launches, recorded on the stream they run on
+    (launches on one stream run back to back, so the bracket divided by the
+    number of launches is the average launch duration; one pair per ~16
+    launches keeps the events' own cost below 1 %).  The sync-update of the
+    step runs concurrently on the other stream, as in the timed region."""
+    ctx, n, gdt = run.ctx, run.w.n, run.gdt
+    pairs, launches = [], 0
+    torch.cuda.synchronize()
+    for t in range(t0, t0 + steps):
+        ctx.abs_sync_update(run.x_arg, run.v_arg, run.lr, run.mu, run.wd)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(run.s_acc)
+        for k, g in plans[t]:
+            ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+        e1.record(run.s_acc)
+        pairs.append((e0, e1))
+        launches += len(plans[t])
+        ctx.abs_swap_buffers()
+    torch.cuda.synchronize()
+    total_ms = sum(a.elapsed_time(b) for a, b in pairs)
+    return total_ms / launches, launches
+
+
+def probe_ceilings(torch, nbytes=1 << 30, reps=20):
+    """Copy / read / write rates of plain streaming kernels on this machine (context
+    for the roofline fraction; not part of the method)."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2308_15164_amd", "libabs_probe.so")
+    if not os.path.exists(path):
+        return None
+    L = ctypes.CDLL(path)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    L.probe_copy.argtypes = [vp, vp, i64, vp]
+    L.probe_read.argtypes = [vp, i64, vp, vp]
+    L.probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
+    a = torch.ones(nbytes // 4, device="cuda")
+    b = torch.ones(nbytes // 4, device="cuda")
+    sink = torch.zeros(4, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for name, fn, moved in (("copy", lambda: L.probe_copy(a.data_ptr(), b.data_ptr(), nbytes, st), 2 * nbytes),
+                            ("read", lambda: L.probe_read(a.data_ptr(), nbytes, sink.data_ptr(), st), nbytes),
+                            ("write", lambda: L.probe_write(a.data_ptr(), nbytes, 1.0, st), nbytes)):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBs"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return out
+
+
+def calibrate_copy(torch, nbytes=1 << 30, reps=10):
+    """Only a plain copy of known size, for scaling the profiler's byte counters."""
+    import ctypes
+    L = ctypes.CDLL(os.path.join(ROOT, "paper_2308_15164_amd", "libabs_probe.so"))
+    L.probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    a = torch.ones(nbytes // 4, device="cuda")
+    b = torch.ones(nbytes // 4, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        L.probe_copy(a.data_ptr(), b.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibration": "probe_copy_kernel", "bytes_read_per_launch": nbytes,
+                      "bytes_written_per_launch": nbytes, "launches": reps}))
+
+
+def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
+    """The oracle as it stands, on the host cores, on a bounded run of the same
+    workload: whole steps at full P until about budget_s of wall time is spent."""
+    import numpy as np
+    import abs_workloads as wl
+    from oracle import abs_oracle as orc
+
+    threads = orc.max_threads()
+    P, K = x0.size, w.K
+    x = x0.astype(np.float64)
+    v = np.zeros(P)
+    G = [[np.zeros(P) for _ in range(K)] for _ in range(2)]
+    M = [[0] * K for _ in range(2)]
+    cur, prev = 0, 1
+    R = len(pool)
+    done_bytes, done_steps = 0, 0
+    t_start = time.perf_counter()
+    t = -1
+    while True:
+        t = (t + 1) % sched.shape[0]
+        for i in range(K):
+            orc.zero(G[cur][i])
+            M[cur][i] = 0
+            for j in range(int(sched[t, i])):
+                orc.accumulate(G[cur][i], pool[wl.pool_index(w, t, i, j, R)], w.n)
+                M[cur][i] += w.n
+        orc.sync_update(x, v, G[prev], M[prev], w.lr, w.mu, w.wd)
+        cur, prev = prev, cur
+        a, s = bytes_per_param(w, sched[t])
+        done_bytes += (a + s) * P
+        done_steps += 1
+        if time.perf_counter() - t_start > budget_s:
+            break
+    dt = time.perf_counter() - t_start
+    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{done_steps} whole steps of {w.name} at full P={P} (same inputs and m_k), "
+                      f"{dt:.1f} s wall, OpenMP over the parameter index",
+            "ms_per_step": dt / done_steps * 1e3, "params_per_s": P * done_steps / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2_resnet18")
+    ap.add_argument("--pool", type=int, default=8, help="distinct gradient vectors resident in HBM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache-policy", default="-1,-1",
+                    help="accumulate,update: -1 auto, 0 cached, 1 streaming (see abs_set_cache_policy)")
+    ap.add_argument("--launch-tuning", default=None,
+                    help="blocks_per_cu,max_rows_per_tile (see abs_set_launch_tuning); default: the library's")
+    ap.add_argument("--acc-streams", type=int, default=1,
+                    help="streams the K workers' accumulations are spread over")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB copy kernel (profiler counter calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU: the K workers are K device-resident buffers and "
+              "there are no collectives; --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import abs_workloads as wl
+    import paper_2308_15164_amd as absgd
+    from paper_2308_15164_amd.driver import DeviceRun
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    absgd.lib()
+    if args.calibrate_copy:
+        calibrate_copy(torch)
+        return 0
+    absgd.abs_set_cache_policy(*[int(v) for v in args.cache_policy.split(",")])
+    if args.launch_tuning:
+        absgd.abs_set_launch_tuning(*[int(v) for v in args.launch_tuning.split(",")])
+
+    w = wl.WORKLOADS[args.workload]
+    W, K_steps = args.warmup, args.steps
+    total = W + K_steps
+    x0 = wl.initial_params(w)
+    pool = wl.gradient_pool(w, pool=args.pool)
+    sched = wl.schedule(w, total)
+
+    # Stream plans.  The double buffer is in use in all of them; they differ in which
+    # HIP streams carry the work.  Each plan is warmed up and timed over the same K
+    # steps; the fastest one is the library's configuration for this workload and
+    # gives `value`.
+    plans_wanted = [("one stream", False, 1), ("accumulate | sync-update", True, 1)]
+    for n in (2, 4):
+        if n <= w.K:
+            plans_wanted.append((f"{n} accumulate streams (workers spread) | sync-update", True, n))
+    if args.acc_streams > 1:
+        plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
+    run = DeviceRun(w, x0, pool, sched, overlap=False)
+    calls = [run.plan_step(t) for t in range(total)]
+    timings = {}
+    for name, overlap, n_acc in plans_wanted:
+        run.configure_streams(overlap, n_acc)
+        time_steps(run, calls, 0, max(W, 1), torch)        # also refills the delayed generation
+        timings[name] = time_steps(run, calls, W, K_steps, torch)
+    best = min(timings, key=timings.get)
+    dt = timings[best]
+    dt_serial = timings["one stream"]
+    dt_overlap = min(v for k, v in timings.items() if k != "one stream")
+
+    # Dominant kernel (accumulate) alone on the GPU: the one-stream plan, same steps.
+    run.configure_streams(False, 1)
+    time_steps(run, calls, 0, max(W, 1), torch)
+    kern_ms, launches = kernel_event_pass(run, calls, W, K_steps, torch)
+    run.close()
+    del run, calls
+    torch.cuda.empty_cache()
+
+    step_bytes = 0
+    for t in range(W, total):
+        a, s_ = bytes_per_param(w, sched[t])
+        step_bytes += (a + s_) * w.P
+    gbs = step_bytes / dt / 1e9
+    # Algorithmic bytes per accumulate launch = the step's accumulate bytes
+    # (sum_k [m_k (g_b + 8) - 4] per parameter) averaged over its sum_k m_k launches.
+    acc_bytes = sum(bytes_per_param(w, sched[t])[0] for t in range(W, total)) * w.P
+    kern_bytes = acc_bytes / launches
+    achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+    kname = dominant_kernel(w)
+    traffic = MEASURED_TRAFFIC.get((w.name, kname))
+
+    out = {
+        "metric": METRIC,
+        "value": gbs,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K_steps,
+        "warmup": W,
+        "ms_per_step": dt / K_steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "P": w.P, "K": w.K, "grad_dtype": w.grad_dtype,
+            "samples_per_microbatch": w.n, "m_k": w.schedule + (str(list(w.ratio)) if w.ratio else ""),
+            "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
+            "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
+            "streams": best + ", double-buffered",
+            "algorithmic_bytes_per_step": step_bytes // K_steps,
+        },
+        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "params_per_s": w.P * K_steps / dt,
+        "overlap_speedup": dt_serial / dt_overlap,
+        "ms_per_step_by_stream_plan": {k: v / K_steps * 1e3 for k, v in timings.items()},
+        "roofline": {
+            "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "algorithmic_bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms,
+            "launches_timed": launches,
+            "measured": "HIP events around each step's accumulate launches, one-stream plan "
+                        "(the kernel alone on the GPU), same steps as the timed region",
+        },
+        "box_ceilings": probe_ceilings(torch),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:])
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -49,8 +49,26 @@ int abs_version(void);
 int abs_last_hip_error(void);
 /* Static, human-readable text for a return code. */
 const char *abs_error_string(int rc);
-/* Elements covered by one workgroup in every kernel (also the ragged chunk size). */
-int64_t abs_tile_elems(void);
+/* Elements in one workgroup row (threads per workgroup x 4); every tile, and every
+ * ragged chunk, is a whole number of rows. */
+int64_t abs_row_elems(void);
+
+/* Launch shape.  A launch gives each workgroup one tile of consecutive rows,
+ * sized so the grid fills the GPU in whole rounds of resident workgroups.
+ * blocks_per_cu: resident workgroups per CU to plan for (0 = default: what the
+ * kernel's register use allows).  max_rows_per_tile: cap on the tile (default 4;
+ * 0 = none: one round, each workgroup walks one long run).  Affects later launches and
+ * later abs_layout_create calls; results never change.  Process-wide. */
+int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile);
+
+/* Cache policy of the kernels.  Accumulators, x and v are re-read soon after a
+ * launch (next micro-batch, next iteration).  Each kernel has a cached flavour
+ * and a streaming one (non-temporal accesses to those buffers); results are
+ * identical.  Mode -1 (default) picks per launch from the buffer sizes: cached
+ * while the working set fits the GPU's memory-side cache, streaming beyond.
+ * 0 forces cached, 1 forces streaming.  Process-wide; not thread-safe against
+ * concurrent launches.  EINVAL for other values. */
+int abs_set_cache_policy(int accumulate_mode, int update_mode);
 
 /* ------------------------------------------------------------------------
  * (1) Gradient accumulation -- Algorithm 1, Step 2 (inner loop and its
@@ -107,7 +125,7 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
  * One launch covers all tensors.
  *
  * abs_layout    sizes only; built on the host (needs no GPU).  It cuts every
- *               tensor into chunks of abs_tile_elems() elements, one per
+ *               tensor into chunks of abs_layout_tile() elements, one per
  *               workgroup; the chunk table is copied to the device the first
  *               time a launch needs it.
  * abs_tensorset T DEVICE base pointers for one logical vector (x, v, one
@@ -124,6 +142,8 @@ int abs_layout_destroy(abs_layout *layout);
 int abs_layout_num_tensors(const abs_layout *layout);
 int64_t abs_layout_total(const abs_layout *layout);
 int64_t abs_layout_num_chunks(const abs_layout *layout);
+/* Elements per chunk of this layout (a multiple of abs_row_elems()). */
+int64_t abs_layout_tile(const abs_layout *layout);
 /* Chunk c covers elements [*offset, *offset + *len) of tensor *tensor. */
 int abs_layout_chunk(const abs_layout *layout, int64_t c, int *tensor, int64_t *offset,
                      int64_t *len);
@@ -168,7 +188,16 @@ int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *layout,
                       void *stream_acc, void *stream_upd);
 int abs_ctx_destroy(abs_ctx *ctx);
 
-/* abs_accumulate into worker k's CURRENT accumulator, on stream_acc. */
+/* Optional: spread accumulation over n streams, worker k on streams[k % n]
+ * (replaces stream_acc).  The K workers of Algorithm 1 compute at the same
+ * time; their accumulators are independent, so their launches may overlap,
+ * which hides launch ramp-up and drain when P is small.  A worker's own
+ * launches stay ordered on its stream.  Only before the first accumulate;
+ * EINVAL afterwards, or for n < 1, n > ABS_MAX_K.  streams: HOST array. */
+int abs_ctx_set_accumulate_streams(abs_ctx *ctx, void *const *streams, int n);
+
+/* abs_accumulate into worker k's CURRENT accumulator, on that worker's
+ * accumulate stream. */
 int abs_ctx_accumulate(abs_ctx *ctx, int k, const void *grad, abs_dtype grad_dtype,
                        int64_t n_samples);
 int abs_ctx_accumulate_mt(abs_ctx *ctx, int k, const abs_tensorset *grad, int64_t n_samples);
@@ -180,8 +209,8 @@ int abs_ctx_sync_update(abs_ctx *ctx, float *params, float *momentum, float lr, 
 int abs_ctx_sync_update_mt(abs_ctx *ctx, const abs_tensorset *params,
                            const abs_tensorset *momentum, float lr, float mu, float wd);
 
-/* End of an iteration (Algorithm 1, t = t + 1): each stream waits for the work
- * the other has enqueued so far (the next sync-update reads what accumulation
+/* End of an iteration (Algorithm 1, t = t + 1): stream_upd and every accumulate
+ * stream wait for the work the other side has enqueued so far (the next sync-update reads what accumulation
  * wrote; the next accumulation overwrites what the sync-update read), the
  * generations trade places, and the new current counts become 0.  No memory is
  * cleared.  Does not block the host. */

@@ -11,7 +11,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libabs_sgd.so")
+# ABS_SGD_LIB points the binding at another build of the same library (tuning variants)
+LIB_PATH = os.environ.get("ABS_SGD_LIB") or os.path.join(_HERE, "libabs_sgd.so")
 
 ABS_OK, ABS_EMPTY, ABS_EINVAL, ABS_EHIP = 0, 1, -1, -2
 ABS_F32, ABS_BF16 = 0, 1
@@ -25,7 +26,9 @@ SYMBOLS = {
     "abs_version": (_int, []),
     "abs_last_hip_error": (_int, []),
     "abs_error_string": (ctypes.c_char_p, [_int]),
-    "abs_tile_elems": (_i64, []),
+    "abs_row_elems": (_i64, []),
+    "abs_set_launch_tuning": (_int, [_int, _int]),
+    "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
     "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
     "abs_layout_create": (_int, [_pvp, _int, _pi64]),
@@ -33,6 +36,7 @@ SYMBOLS = {
     "abs_layout_num_tensors": (_int, [_vp]),
     "abs_layout_total": (_i64, [_vp]),
     "abs_layout_num_chunks": (_i64, [_vp]),
+    "abs_layout_tile": (_i64, [_vp]),
     "abs_layout_chunk": (_int, [_vp, _i64, ctypes.POINTER(_int), _pi64, _pi64]),
     "abs_tensorset_create": (_int, [_pvp, _vp, _pvp, _int]),
     "abs_tensorset_destroy": (_int, [_vp]),
@@ -41,6 +45,7 @@ SYMBOLS = {
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_destroy": (_int, [_vp]),
+    "abs_ctx_set_accumulate_streams": (_int, [_vp, _pvp, _int]),
     "abs_ctx_accumulate": (_int, [_vp, _int, _vp, _int, _i64]),
     "abs_ctx_accumulate_mt": (_int, [_vp, _int, _vp, _i64]),
     "abs_ctx_sync_update": (_int, [_vp, _vp, _vp, _f, _f, _f]),
@@ -134,8 +139,19 @@ def abs_version():
     return lib().abs_version()
 
 
-def abs_tile_elems():
-    return lib().abs_tile_elems()
+def abs_row_elems():
+    return lib().abs_row_elems()
+
+
+def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=0):
+    """See abs_set_launch_tuning in abs_sgd.h."""
+    return _check("abs_set_launch_tuning",
+                  lib().abs_set_launch_tuning(int(blocks_per_cu), int(max_rows_per_tile)))
+
+
+def abs_set_cache_policy(accumulate_mode=-1, update_mode=-1):
+    """-1 auto, 0 cached, 1 streaming; see abs_set_cache_policy in abs_sgd.h."""
+    return _check("abs_set_cache_policy", lib().abs_set_cache_policy(int(accumulate_mode), int(update_mode)))
 
 
 class Count:
@@ -189,6 +205,9 @@ class Layout:
 
     def num_chunks(self):
         return lib().abs_layout_num_chunks(self.handle)
+
+    def tile(self):
+        return lib().abs_layout_tile(self.handle)
 
     def chunk(self, c):
         t, off, ln = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
@@ -276,6 +295,12 @@ class Context:
             _check("abs_ctx_create_mt", rc)
         self.handle = h
 
+    def abs_set_accumulate_streams(self, streams):
+        self._keep = self._keep + (list(streams),)
+        arr = _ptr_array([_stream_handle(s) for s in streams])
+        return _check("abs_ctx_set_accumulate_streams",
+                      lib().abs_ctx_set_accumulate_streams(self.handle, arr, len(streams)))
+
     def abs_accumulate(self, k, grad, n_samples, grad_dtype=None):
         if self.layout is None:
             rc = lib().abs_ctx_accumulate(self.handle, int(k), _dev_ptr(grad),
@@ -318,7 +343,7 @@ def abs_swap_buffers(ctx):
     return ctx.abs_swap_buffers()
 
 
-__all__ = ["abs_swap_buffers", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
+__all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
            "abs_sync_update", "abs_accumulate_mt", "abs_sync_update_mt", "abs_version",
-           "abs_tile_elems", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
+           "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

@@ -7,6 +7,8 @@ ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "abs_sgd.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "abs_kernels.hpp"), os.path.join(ROOT, "include", "abs_sgd.h")]
 LIB = os.path.join(HERE, "libabs_sgd.so")
+PROBE_SRC = os.path.join(HERE, "csrc", "copy_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libabs_probe.so")
 
 # Contraction is off so the fixed fp32 operation order survives; packed-fp32
 # instruction selection is disabled on this target.
@@ -28,5 +30,12 @@ def build_library(force=True, extra_flags=(), out=LIB):
     return out
 
 
+def build_probe():
+    """Plain copy/read/write kernels the benchmark uses for calibration only."""
+    subprocess.run(["hipcc"] + FLAGS + [PROBE_SRC, "-o", PROBE_LIB], check=True)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     print(build_library())
+    print(build_probe())

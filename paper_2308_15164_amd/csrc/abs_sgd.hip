@@ -13,6 +13,16 @@
 
 #include "abs_sgd.h"
 
+#ifndef ABS_ACC_STREAM_BYTES
+#define ABS_ACC_STREAM_BYTES (int64_t(160) << 20)
+#endif
+#ifndef ABS_MAX_ROWS
+#define ABS_MAX_ROWS 4
+#endif
+#ifndef ABS_UPD_STREAM_BYTES
+#define ABS_UPD_STREAM_BYTES (int64_t(256) << 20)
+#endif
+
 using namespace absk;
 
 namespace {
@@ -40,9 +50,51 @@ inline int launch_status()
     return ABS_OK;
 }
 
-// Number of workgroups for P elements; <0 when it does not fit the grid limit.
-inline int64_t tiles_for(int64_t P) { return (P + TILE - 1) / TILE; }
 constexpr int64_t kMaxGrid = 0x7fffffff;
+constexpr int64_t kMaxTile = int64_t(1) << 30;   // tile sizes travel as int
+
+// ------------------------------------------------------------ launch shape
+//
+// A launch should fill the chip in whole rounds: with `resident` workgroups
+// able to run at once, the tile is the smallest whole number of rows that
+// covers n rows in `rounds` rounds, rounds being the fewest that keep a tile
+// within g_max_rows rows (0 = no limit: always one round, every workgroup
+// walks one long run of memory).  Measured on MI355X: short tiles (<= 4 rows,
+// many rounds) beat long per-workgroup runs by 5-20 % once P exceeds ~30 M,
+// because all resident workgroups then sweep one compact window of memory.
+constexpr int kCUs = 256;                 // MI355X
+int g_blocks_per_cu = 0;                  // 0 = ask the runtime per kernel
+int g_max_rows = ABS_MAX_ROWS;
+
+inline int64_t rows_of(int64_t P) { return (P + ROW - 1) / ROW; }
+
+int64_t choose_tile(int64_t rows, int resident)
+{
+    if (rows <= resident) return ROW;
+    int64_t rounds = 1;
+    if (g_max_rows > 0) rounds = (rows + (int64_t)resident * g_max_rows - 1) / ((int64_t)resident * g_max_rows);
+    const int64_t slots = (int64_t)resident * rounds;
+    return ((rows + slots - 1) / slots) * ROW;
+}
+
+inline int64_t tiles_for(int64_t P, int64_t tile) { return (P + tile - 1) / tile; }
+
+// Workgroups of `kernel` that fit on the chip at once.
+template <class Kernel>
+int resident_blocks(Kernel kernel, int fallback_per_cu)
+{
+    int per_cu = g_blocks_per_cu;
+    if (per_cu <= 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, BLOCK, 0) == hipSuccess && n > 0) per_cu = n;
+        else { (void)hipGetLastError(); per_cu = fallback_per_cu; }
+    }
+    return per_cu * kCUs;
+}
+
+// The accumulate kernels need few registers: 8 workgroups of 4 wavefronts per CU.
+constexpr int kAccBlocksPerCU = 8;
+inline int acc_resident() { return (g_blocks_per_cu > 0 ? g_blocks_per_cu : kAccBlocksPerCU) * kCUs; }
 
 // counts -> compacted list of non-empty workers and their total.
 struct Combine {
@@ -65,44 +117,70 @@ int plan_combine(const int64_t *counts, int K, Combine &c)
     return c.M == 0 ? ABS_EMPTY : ABS_OK;
 }
 
+// ------------------------------------------------------------ cache policy
+//
+// Accumulators, x and v are touched again soon after a kernel ends.  When they
+// fit the memory-side cache (256 MiB on this part) keeping them cached pays;
+// when they do not, streaming (non-temporal) accesses avoid allocating lines
+// that are evicted before their reuse.  -1 = decide from the sizes.
+int g_policy_acc = -1, g_policy_upd = -1;
+constexpr int64_t kAccStreamBytes = ABS_ACC_STREAM_BYTES;   // accumulator bytes above which accumulate streams
+constexpr int64_t kUpdStreamBytes = ABS_UPD_STREAM_BYTES;   // bytes of x + v above which sync-update streams
+
+inline bool stream_acc(int64_t P) { return g_policy_acc < 0 ? 4 * P > kAccStreamBytes : g_policy_acc != 0; }
+inline bool stream_upd(int64_t P) { return g_policy_upd < 0 ? 8 * P > kUpdStreamBytes : g_policy_upd != 0; }
+
 // ------------------------------------------------------------ flat launches
 
-template <bool FIRST>
-void launch_accumulate_flat(float *acc, const void *grad, abs_dtype dt, int64_t P, float nf,
-                            int vec_ok, hipStream_t s)
+int launch_accumulate_flat(float *acc, const void *grad, abs_dtype dt, int64_t P, float nf,
+                           int first, int vec_ok, hipStream_t s)
 {
-    const dim3 grid((unsigned)tiles_for(P)), block(BLOCK);
-    if (dt == ABS_BF16)
-        hipLaunchKernelGGL((accumulate_flat<FIRST, true>), grid, block, 0, s, acc, grad, P, nf, vec_ok);
-    else
-        hipLaunchKernelGGL((accumulate_flat<FIRST, false>), grid, block, 0, s, acc, grad, P, nf, vec_ok);
+    const int64_t tile64 = choose_tile(rows_of(P), acc_resident());
+    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
+    const int tile = (int)tile64;
+    const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
+    const bool bf = dt == ABS_BF16, nta = stream_acc(P);
+    if (bf && nta) hipLaunchKernelGGL((accumulate_flat<true, true>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
+    else if (bf) hipLaunchKernelGGL((accumulate_flat<true, false>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
+    else if (nta) hipLaunchKernelGGL((accumulate_flat<false, true>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
+    else hipLaunchKernelGGL((accumulate_flat<false, false>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
+    return ABS_OK;
 }
 
 template <int K>
-void launch_sync_flat_k(float *x, float *v, const float *const *ptrs, int64_t P, Hyper h,
-                        int vec_ok, hipStream_t s)
+int launch_sync_flat_k(float *x, float *v, const float *const *ptrs, int64_t P, Hyper h,
+                       int vec_ok, hipStream_t s)
 {
+    static const int resident = resident_blocks(sync_update_flat<K, false>, 4);
+    const int64_t tile64 = choose_tile(rows_of(P), g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : resident);
+    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
+    const int tile = (int)tile64;
     AccPtrs<K> A;
     for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
-    hipLaunchKernelGGL((sync_update_flat<K>), dim3((unsigned)tiles_for(P)), dim3(BLOCK), 0, s, x, v,
-                       A, P, h, vec_ok);
+    const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
+    if (stream_upd(P)) hipLaunchKernelGGL((sync_update_flat<K, true>), grid, block, 0, s, x, v, A, P, tile, h, vec_ok);
+    else hipLaunchKernelGGL((sync_update_flat<K, false>), grid, block, 0, s, x, v, A, P, tile, h, vec_ok);
+    return ABS_OK;
 }
 
-void launch_sync_flat(float *x, float *v, const float *const *ptrs, int n, int64_t P, Hyper h,
-                      int vec_ok, hipStream_t s)
+int launch_sync_flat(float *x, float *v, const float *const *ptrs, int n, int64_t P, Hyper h,
+                     int vec_ok, hipStream_t s)
 {
     switch (n) {
-#define ABS_CASE(K) case K: launch_sync_flat_k<K>(x, v, ptrs, P, h, vec_ok, s); break;
+#define ABS_CASE(K) case K: return launch_sync_flat_k<K>(x, v, ptrs, P, h, vec_ok, s);
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
         ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
         ABS_CASE(16)
 #undef ABS_CASE
     default: {
+        const int64_t tile64 = choose_tile(rows_of(P), 4 * kCUs);
+        if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
         AccPtrsAny A;
         std::memset(&A, 0, sizeof A);
         for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
-        hipLaunchKernelGGL(sync_update_flat_any, dim3((unsigned)tiles_for(P)), dim3(BLOCK), 0, s, x, v,
-                           A, n, P, h, vec_ok);
+        hipLaunchKernelGGL(sync_update_flat_any, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s,
+                           x, v, A, n, P, (int)tile64, h, vec_ok);
+        return ABS_OK;
     }
     }
 }
@@ -115,6 +193,7 @@ struct abs_layout {
     std::vector<int64_t> sizes;
     std::vector<Chunk> chunks;
     int64_t total = 0;
+    int tile = ROW;                      // elements per chunk, a multiple of ROW
     // device copies, made on first use
     Chunk *d_chunks = nullptr;
     int64_t *d_sizes = nullptr;
@@ -136,8 +215,13 @@ struct abs_ctx {
     std::vector<const abs_tensorset *> set[2];
     std::vector<int64_t> counts[2];
     int cur = 0;
-    hipStream_t s_acc = nullptr, s_upd = nullptr;
-    hipEvent_t ev_acc = nullptr, ev_upd = nullptr;
+    std::vector<hipStream_t> s_acc;      // worker k accumulates on s_acc[k % size]
+    hipStream_t s_upd = nullptr;
+    std::vector<hipEvent_t> ev_acc;      // one per accumulate stream
+    hipEvent_t ev_upd = nullptr;
+    bool joins = false;                  // more than one distinct stream in use
+
+    hipStream_t stream_of(int k) const { return s_acc[(size_t)k % s_acc.size()]; }
 };
 
 namespace {
@@ -171,8 +255,11 @@ void launch_sync_ragged_k(const abs_layout *L, float *const *xt, float *const *v
 {
     TabPtrs<K> T;
     for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
-    hipLaunchKernelGGL((sync_update_ragged<K>), dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
-                       L->d_chunks, L->d_sizes, xt, vt, T, h);
+    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
+    if (stream_upd(L->total))
+        hipLaunchKernelGGL((sync_update_ragged<K, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, T, L->tile, h);
+    else
+        hipLaunchKernelGGL((sync_update_ragged<K, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, T, L->tile, h);
 }
 
 void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
@@ -189,7 +276,7 @@ void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
         std::memset(&T, 0, sizeof T);
         for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
         hipLaunchKernelGGL(sync_update_ragged_any, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
-                           L->d_chunks, L->d_sizes, xt, vt, T, n, h);
+                           L->d_chunks, L->d_sizes, xt, vt, T, n, L->tile, h);
     }
     }
 }
@@ -218,7 +305,23 @@ const char *abs_error_string(int rc)
     }
 }
 
-int64_t abs_tile_elems(void) { return TILE; }
+int64_t abs_row_elems(void) { return ROW; }
+
+int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile)
+{
+    if (blocks_per_cu < 0 || blocks_per_cu > 32 || max_rows_per_tile < 0) return ABS_EINVAL;
+    g_blocks_per_cu = blocks_per_cu;
+    g_max_rows = max_rows_per_tile;
+    return ABS_OK;
+}
+
+int abs_set_cache_policy(int accumulate_mode, int update_mode)
+{
+    if (accumulate_mode < -1 || accumulate_mode > 1 || update_mode < -1 || update_mode > 1) return ABS_EINVAL;
+    g_policy_acc = accumulate_mode;
+    g_policy_upd = update_mode;
+    return ABS_OK;
+}
 
 // ------------------------------------------------------------------ flat
 
@@ -232,13 +335,12 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
         if (!acc || !grad) return ABS_EINVAL;
         const uintptr_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
         if (!aligned_to(acc, 4) || !aligned_to(grad, gsz)) return ABS_EINVAL;
-        if (tiles_for(P) > kMaxGrid) return ABS_EINVAL;
         const int vec_ok = aligned_to(acc, 16) && aligned_to(grad, grad_dtype == ABS_BF16 ? 8 : 16);
         const float nf = (float)n_samples;
         hipStream_t s = static_cast<hipStream_t>(stream);
-        if (*count == 0) launch_accumulate_flat<true>(acc, grad, grad_dtype, P, nf, vec_ok, s);
-        else launch_accumulate_flat<false>(acc, grad, grad_dtype, P, nf, vec_ok, s);
-        int rc = launch_status();
+        int rc = launch_accumulate_flat(acc, grad, grad_dtype, P, nf, *count == 0 ? 1 : 0, vec_ok, s);
+        if (rc != ABS_OK) return rc;
+        rc = launch_status();
         if (rc != ABS_OK) return rc;
     }
     *count += n_samples;
@@ -256,7 +358,6 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
     if (P == 0) return ABS_OK;
     if (!params || !momentum || params == momentum) return ABS_EINVAL;
     if (!aligned_to(params, 4) || !aligned_to(momentum, 4)) return ABS_EINVAL;
-    if (tiles_for(P) > kMaxGrid) return ABS_EINVAL;
     const float *ptrs[ABS_MAX_K];
     bool vec = aligned_to(params, 16) && aligned_to(momentum, 16);
     for (int j = 0; j < c.n; ++j) {
@@ -266,7 +367,8 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
         ptrs[j] = p;
     }
     const Hyper h = {(float)c.M, lr, mu, wd};
-    launch_sync_flat(params, momentum, ptrs, c.n, P, h, vec ? 1 : 0, static_cast<hipStream_t>(stream));
+    rc = launch_sync_flat(params, momentum, ptrs, c.n, P, h, vec ? 1 : 0, static_cast<hipStream_t>(stream));
+    if (rc != ABS_OK) return rc;
     return launch_status();
 }
 
@@ -277,23 +379,27 @@ int abs_layout_create(abs_layout **out, int T, const int64_t *sizes)
     if (!out || T < 1 || !sizes) return ABS_EINVAL;
     abs_layout *L = new (std::nothrow) abs_layout;
     if (!L) return ABS_EINVAL;
-    int64_t nchunks = 0;
+    int64_t rows = 0;
     for (int t = 0; t < T; ++t) {
-        if (sizes[t] < 0 || tiles_for(sizes[t]) > kMaxGrid ||
-            L->total > std::numeric_limits<int64_t>::max() - sizes[t]) {
+        if (sizes[t] < 0 || L->total > std::numeric_limits<int64_t>::max() - sizes[t]) {
             delete L;
             return ABS_EINVAL;
         }
         L->total += sizes[t];
-        nchunks += tiles_for(sizes[t]);
+        rows += rows_of(sizes[t]);
     }
-    if (nchunks > kMaxGrid) { delete L; return ABS_EINVAL; }
+    // one tile size for the whole layout, from the accumulate kernel's residency
+    const int64_t tile = choose_tile(rows, acc_resident());
+    int64_t nchunks = 0;
+    for (int t = 0; t < T; ++t) nchunks += tiles_for(sizes[t], tile);
+    if (tile > kMaxTile || nchunks > kMaxGrid) { delete L; return ABS_EINVAL; }
+    L->tile = (int)tile;
     L->sizes.assign(sizes, sizes + T);
     L->chunks.reserve((size_t)nchunks);
     // Tensor order, tile order within a tensor: consecutive workgroups stream
     // consecutive memory of one tensor.
     for (int t = 0; t < T; ++t)
-        for (int64_t i = 0, n = tiles_for(sizes[t]); i < n; ++i)
+        for (int64_t i = 0, n = tiles_for(sizes[t], tile); i < n; ++i)
             L->chunks.push_back(Chunk{(int32_t)t, (int32_t)i});
     *out = L;
     return ABS_OK;
@@ -311,15 +417,16 @@ int abs_layout_destroy(abs_layout *L)
 int abs_layout_num_tensors(const abs_layout *L) { return L ? (int)L->sizes.size() : ABS_EINVAL; }
 int64_t abs_layout_total(const abs_layout *L) { return L ? L->total : ABS_EINVAL; }
 int64_t abs_layout_num_chunks(const abs_layout *L) { return L ? (int64_t)L->chunks.size() : ABS_EINVAL; }
+int64_t abs_layout_tile(const abs_layout *L) { return L ? L->tile : ABS_EINVAL; }
 
 int abs_layout_chunk(const abs_layout *L, int64_t c, int *tensor, int64_t *offset, int64_t *len)
 {
     if (!L || c < 0 || c >= (int64_t)L->chunks.size() || !tensor || !offset || !len) return ABS_EINVAL;
     const Chunk ch = L->chunks[(size_t)c];
     *tensor = ch.tensor;
-    *offset = (int64_t)ch.index * TILE;
+    *offset = (int64_t)ch.index * L->tile;
     const int64_t rest = L->sizes[(size_t)ch.tensor] - *offset;
-    *len = rest < TILE ? rest : TILE;
+    *len = rest < L->tile ? rest : L->tile;
     return ABS_OK;
 }
 
@@ -370,11 +477,12 @@ int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensors
         hipStream_t s = static_cast<hipStream_t>(stream);
         float *const *at = reinterpret_cast<float *const *>(acc->d_tab);
         const void *const *gt = reinterpret_cast<const void *const *>(grad->d_tab);
-        const bool first = *count == 0, bf = grad->elem == ABS_BF16;
-        if (first && bf) hipLaunchKernelGGL((accumulate_ragged<true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
-        else if (first) hipLaunchKernelGGL((accumulate_ragged<true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
-        else if (bf) hipLaunchKernelGGL((accumulate_ragged<false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
-        else hipLaunchKernelGGL((accumulate_ragged<false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, nf);
+        const int first = *count == 0 ? 1 : 0;
+        const bool bf = grad->elem == ABS_BF16, nta = stream_acc(L->total);
+        if (bf && nta) hipLaunchKernelGGL((accumulate_ragged<true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
+        else if (bf) hipLaunchKernelGGL((accumulate_ragged<true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
+        else if (nta) hipLaunchKernelGGL((accumulate_ragged<false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
+        else hipLaunchKernelGGL((accumulate_ragged<false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
         rc = launch_status();
         if (rc != ABS_OK) return rc;
     }
@@ -410,18 +518,32 @@ int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_ten
 
 // --------------------------------------------------------- double buffer
 
+static int ctx_set_streams(abs_ctx *C, const hipStream_t *streams, int n)
+{
+    for (hipEvent_t e : C->ev_acc) (void)hipEventDestroy(e);
+    C->ev_acc.clear();
+    C->s_acc.assign(streams, streams + n);
+    C->joins = false;
+    for (hipStream_t s : C->s_acc) C->joins = C->joins || s != C->s_upd;
+    if (C->joins) {
+        if (!C->ev_upd) ABS_HIP(hipEventCreateWithFlags(&C->ev_upd, hipEventDisableTiming));
+        for (int i = 0; i < n; ++i) {
+            hipEvent_t e = nullptr;
+            ABS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            C->ev_acc.push_back(e);
+        }
+    }
+    return ABS_OK;
+}
+
 static int ctx_common(abs_ctx *C, int K, void *stream_acc, void *stream_upd)
 {
     C->K = K;
     C->counts[0].assign((size_t)K, 0);
     C->counts[1].assign((size_t)K, 0);
-    C->s_acc = static_cast<hipStream_t>(stream_acc);
     C->s_upd = static_cast<hipStream_t>(stream_upd);
-    if (C->s_acc != C->s_upd) {
-        ABS_HIP(hipEventCreateWithFlags(&C->ev_acc, hipEventDisableTiming));
-        ABS_HIP(hipEventCreateWithFlags(&C->ev_upd, hipEventDisableTiming));
-    }
-    return ABS_OK;
+    hipStream_t sa = static_cast<hipStream_t>(stream_acc);
+    return ctx_set_streams(C, &sa, 1);
 }
 
 int abs_ctx_create(abs_ctx **out, int K, int64_t P, float *const *acc_A, float *const *acc_B,
@@ -466,7 +588,7 @@ int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *L, const abs_tensorset *
 int abs_ctx_destroy(abs_ctx *C)
 {
     if (!C) return ABS_EINVAL;
-    if (C->ev_acc) (void)hipEventDestroy(C->ev_acc);
+    for (hipEvent_t e : C->ev_acc) (void)hipEventDestroy(e);
     if (C->ev_upd) (void)hipEventDestroy(C->ev_upd);
     delete C;
     return ABS_OK;
@@ -476,14 +598,25 @@ int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype
 {
     if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
     return abs_accumulate(C->acc[C->cur][(size_t)k], grad, grad_dtype, C->P, n_samples,
-                          &C->counts[C->cur][(size_t)k], C->s_acc);
+                          &C->counts[C->cur][(size_t)k], C->stream_of(k));
+}
+
+int abs_ctx_set_accumulate_streams(abs_ctx *C, void *const *streams, int n)
+{
+    if (!C || !streams || n < 1 || n > ABS_MAX_K) return ABS_EINVAL;
+    for (const auto &gen : C->counts)
+        for (int64_t c : gen)
+            if (c != 0) return ABS_EINVAL;   // only between creation and the first accumulate
+    std::vector<hipStream_t> s((size_t)n);
+    for (int i = 0; i < n; ++i) s[(size_t)i] = static_cast<hipStream_t>(streams[i]);
+    return ctx_set_streams(C, s.data(), n);
 }
 
 int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
 {
     if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
     return abs_accumulate_mt(C->layout, C->set[C->cur][(size_t)k], grad, n_samples,
-                             &C->counts[C->cur][(size_t)k], C->s_acc);
+                             &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
 
 int abs_ctx_sync_update(abs_ctx *C, float *params, float *momentum, float lr, float mu, float wd)
@@ -506,13 +639,16 @@ int abs_ctx_sync_update_mt(abs_ctx *C, const abs_tensorset *params, const abs_te
 int abs_swap_buffers(abs_ctx *C)
 {
     if (!C) return ABS_EINVAL;
-    if (C->s_acc != C->s_upd) {
-        // next sync-update reads what accumulation has written so far
-        ABS_HIP(hipEventRecord(C->ev_acc, C->s_acc));
+    if (C->joins) {
         // next accumulation overwrites what the sync-update has been reading
         ABS_HIP(hipEventRecord(C->ev_upd, C->s_upd));
-        ABS_HIP(hipStreamWaitEvent(C->s_upd, C->ev_acc, 0));
-        ABS_HIP(hipStreamWaitEvent(C->s_acc, C->ev_upd, 0));
+        for (size_t i = 0; i < C->s_acc.size(); ++i) {
+            if (C->s_acc[i] == C->s_upd) continue;
+            // next sync-update reads what accumulation has written so far
+            ABS_HIP(hipEventRecord(C->ev_acc[i], C->s_acc[i]));
+            ABS_HIP(hipStreamWaitEvent(C->s_upd, C->ev_acc[i], 0));
+            ABS_HIP(hipStreamWaitEvent(C->s_acc[i], C->ev_upd, 0));
+        }
     }
     C->cur ^= 1;
     for (auto &c : C->counts[C->cur]) c = 0;

@@ -1,0 +1,89 @@
+// Plain streaming kernels of known size, separate from the method's library.
+// They serve two purposes in the benchmark: (1) calibrating the profiler's
+// HBM byte counters against a transfer whose size is known, and (2) measuring
+// the copy / read / write ceilings of the box the benchmark runs on, to put the
+// method's kernels in context.  Nothing in the method calls them.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int BLOCK = 256;
+constexpr int VPT = 4;   // 128-bit vectors per lane, all loads issued before the stores
+
+__global__ __launch_bounds__(BLOCK) void probe_copy_kernel(f32x4 *__restrict__ dst,
+                                                          const f32x4 *__restrict__ src, int64_t nvec)
+{
+    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+    f32x4 r[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) r[u] = __builtin_nontemporal_load(src + i);
+    }
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) __builtin_nontemporal_store(r[u], dst + i);
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void probe_read_kernel(const f32x4 *__restrict__ src, int64_t nvec,
+                                                          float *__restrict__ sink)
+{
+    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) acc += __builtin_nontemporal_load(src + i);
+    }
+    // never true for finite data: keeps the loads alive without a store stream
+    if (acc.x + acc.y + acc.z + acc.w == 1.2345678e38f) *sink = acc.x;
+}
+
+__global__ __launch_bounds__(BLOCK) void probe_write_kernel(f32x4 *__restrict__ dst, int64_t nvec, float val)
+{
+    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+    const f32x4 r = {val, val, val, val};
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) __builtin_nontemporal_store(r, dst + i);
+    }
+}
+
+inline unsigned grid_for(int64_t nvec) { return (unsigned)((nvec + BLOCK * VPT - 1) / (BLOCK * VPT)); }
+}  // namespace
+
+extern "C" {
+
+// dst, src: DEVICE, 16-byte aligned, nbytes a multiple of 16.  Returns 0 or -1.
+int probe_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes <= 0 || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return -1;
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
+                       (f32x4 *)dst, (const f32x4 *)src, nvec);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int probe_read(const void *src, int64_t nbytes, float *sink, void *stream)
+{
+    if (!src || !sink || nbytes <= 0 || (nbytes & 15) || ((uintptr_t)src & 15)) return -1;
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
+                       (const f32x4 *)src, nvec, sink);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int probe_write(void *dst, int64_t nbytes, float val, void *stream)
+{
+    if (!dst || nbytes <= 0 || (nbytes & 15) || ((uintptr_t)dst & 15)) return -1;
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(probe_write_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
+                       (f32x4 *)dst, nvec, val);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // extern "C"

@@ -23,21 +23,20 @@ def _upload(a):
 class DeviceRun:
     """Device state and call sequence for one workload.
 
-    overlap=True : accumulation on one stream, sync-update on another (double
-                   buffer in use, the configuration the benchmark times);
-    overlap=False: both on one stream, in program order.
+    overlap=True : accumulation and sync-update on different streams;
+    overlap=False: both on one stream, in program order;
+    acc_streams=n: the K workers' accumulations spread over n streams.
     """
 
-    def __init__(self, w, x0, pool, schedule, overlap=True, P=None):
+    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
         self.m = np.asarray(schedule)
         self.gdt = ABS_BF16 if w.grad_dtype == "bf16" else ABS_F32
         self.ragged = w.tensor_sizes is not None
-        dev = torch.device("cuda:0")
-        self.s_acc = torch.cuda.Stream(device=dev)
-        self.s_upd = torch.cuda.Stream(device=dev) if overlap else self.s_acc
+        self._streams = [torch.cuda.Stream(device=torch.device("cuda:0")) for _ in range(9)]
+        self.ctx = None
         if not self.ragged:
             self.x = _upload(np.ascontiguousarray(x0, dtype=np.float32))
             self.v = torch.zeros_like(self.x)
@@ -49,7 +48,6 @@ class DeviceRun:
             self.pool = [_upload(g) for g in pool]
             self.pool_ptr = [g.data_ptr() for g in self.pool]
             torch.cuda.synchronize()
-            self.ctx = Context(self.acc[0], self.acc[1], self.s_acc, self.s_upd, P=self.P)
             self.x_arg, self.v_arg = self.x.data_ptr(), self.v.data_ptr()
         else:
             sizes = list(w.tensor_sizes)
@@ -71,12 +69,31 @@ class DeviceRun:
             self.acc_sets = [[TensorSet(self.layout, self.acc_t[g][k]) for k in range(self.K)]
                              for g in range(2)]
             self.pool_sets = [TensorSet(self.layout, p, dtype=self.gdt) for p in self.pool_t]
-            self.ctx = Context(self.acc_sets[0], self.acc_sets[1], self.s_acc, self.s_upd,
-                               layout=self.layout)
             self.x_arg, self.v_arg = self.x_set, self.v_set
+        self.configure_streams(overlap, acc_streams)
         self.lr, self.mu, self.wd = float(w.lr), float(w.mu), float(w.wd)
         self.applied = []
         self.count_history = []
+
+    def configure_streams(self, overlap, acc_streams=1):
+        """(Re)build the double-buffer context over the same device buffers with
+        another stream plan.  Counts restart at zero (as at creation), so the
+        next step applies nothing; parameters and momentum carry on."""
+        torch.cuda.synchronize()
+        if self.ctx is not None:
+            self.ctx.close()
+        acc_streams = max(1, min(int(acc_streams), 8))
+        self.s_acc = self._streams[0]
+        self.s_upd = self._streams[8] if overlap else self.s_acc
+        self.acc_streams = self._streams[:acc_streams]
+        self.stream_plan = {"overlap": bool(overlap), "acc_streams": acc_streams}
+        if not self.ragged:
+            self.ctx = Context(self.acc[0], self.acc[1], self.s_acc, self.s_upd, P=self.P)
+        else:
+            self.ctx = Context(self.acc_sets[0], self.acc_sets[1], self.s_acc, self.s_upd,
+                               layout=self.layout)
+        if acc_streams > 1:
+            self.ctx.abs_set_accumulate_streams(self.acc_streams)
 
     def grad_arg(self, r):
         return self.pool_sets[r] if self.ragged else self.pool_ptr[r]

@@ -32,8 +32,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_tile_and_error_strings():
     assert absgd.abs_version() >= 100
-    tile = absgd.abs_tile_elems()
-    assert tile > 0 and tile % 1024 == 0
+    row = absgd.abs_row_elems()
+    assert row > 0 and row % 256 == 0
     L = absgd.lib()
     assert b"invalid" in L.abs_error_string(absgd.ABS_EINVAL)
     assert L.abs_error_string(absgd.ABS_OK) == b"ok"
@@ -82,10 +82,12 @@ def test_sync_update_empty_and_bad_arguments():
     assert _rc_sync(16, 32, [48], [32], 0) == absgd.ABS_OK                     # P == 0
 
 
-@pytest.mark.parametrize("sizes", [[1], [0, 5, 0], [4096], [4097, 1, 8192, 3], [12289, 768, 100000]])
+@pytest.mark.parametrize("sizes", [[1], [0, 5, 0], [4096], [4097, 1, 8192, 3], [12289, 768, 100000],
+                                   [5_000_000, 1, 1023, 1025, 3_000_001]])
 def test_layout_chunk_table_partitions_every_tensor(sizes):
-    tile = absgd.abs_tile_elems()
     lay = absgd.Layout(sizes)
+    tile = lay.tile()
+    assert tile > 0 and tile % absgd.abs_row_elems() == 0
     assert lay.num_tensors() == len(sizes)
     assert lay.total() == sum(sizes)
     expected = sum((s + tile - 1) // tile for s in sizes)
@@ -99,6 +101,21 @@ def test_layout_chunk_table_partitions_every_tensor(sizes):
         assert np.all(cov == 1)          # every element in exactly one chunk
     assert absgd.lib().abs_layout_chunk(lay.handle, lay.num_chunks(), None, None, None) == absgd.ABS_EINVAL
     lay.close()
+
+
+def test_layout_tile_fills_whole_rounds():
+    """Large layouts get one chunk per resident workgroup (about), small ones one row per chunk."""
+    row = absgd.abs_row_elems()
+    small = absgd.Layout([row * 10, 5])
+    assert small.tile() == row
+    absgd.abs_set_launch_tuning(0, 0)              # no cap: one round
+    big = absgd.Layout([row * 2048 * 7 + 3])
+    assert big.tile() == 8 * row and big.num_chunks() <= 2048
+    absgd.abs_set_launch_tuning(0, 4)              # the default cap of 4 rows: two rounds of 2048
+    capped = absgd.Layout([row * 2048 * 7 + 3])
+    assert capped.tile() == 4 * row and 2048 < capped.num_chunks() <= 4096
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_set_launch_tuning(-1, 0)
 
 
 def test_layout_rejects_bad_sizes():

@@ -11,8 +11,6 @@ Bars (written out here, derived in the design doc):
     The naive element-wise relative error is printed for information: where
     x - lr*v cancels to ~0 it is unbounded for ANY fp32 implementation.
 """
-import ctypes
-
 import numpy as np
 import pytest
 
@@ -73,6 +71,35 @@ def _grad(rng, P, dtype, sigma=0.01):
 # ---------------------------------------------------------------------------
 
 SIZES = [1, 3, 4, 7, 255, 1024, 4095, 4096, 4097, 3 * 4096 + 5, 8 * 4096, 100_003, 1_048_576 + 13]
+
+
+@pytest.fixture
+def tuned(absgd, request):
+    """Launch shapes that force multi-row tiles (whole groups + a partial group +
+    a vector tail) already at small sizes."""
+    blocks_per_cu, max_rows = request.param
+    absgd.abs_set_launch_tuning(blocks_per_cu, max_rows)
+    yield request.param
+    absgd.abs_set_launch_tuning(0, 4)      # the defaults
+
+
+MULTI_ROW_SIZES = [700_001, 1_048_576, 1_048_576 + 13, 2_500_007]
+TUNINGS = [(1, 0), (1, 3), (2, 5)]
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("P", MULTI_ROW_SIZES)
+def test_accumulate_multi_row_tiles(absgd, tuned, dtype, P):
+    test_accumulate_matches_oracle(absgd, dtype, P)
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+@pytest.mark.parametrize("K", [3, 9, 16, 19])
+@pytest.mark.parametrize("P", MULTI_ROW_SIZES[:3])
+def test_sync_update_multi_row_tiles(absgd, tuned, K, P):
+    print(f"[case] sync_update multi-row K={K} P={P} tuning={tuned}", flush=True)
+    _sync_case(absgd, K, P, [32 * (1 + k % 3) for k in range(K)], seed=K + P)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -273,6 +300,30 @@ def _trajectory_case(absgd, name, steps=None, P=None):
 
 def test_trajectory_cfg1(absgd):
     _trajectory_case(absgd, "cfg1_small")
+
+
+@pytest.mark.parametrize("tuned", [(1, 0), (1, 2)], indirect=True)
+@pytest.mark.parametrize("name", ["cfg1_small", "ragged_odd_bf16"])
+def test_trajectory_multi_row_tiles(absgd, tuned, name):
+    _trajectory_case(absgd, name)
+
+
+def test_trajectory_worker_streams(absgd):
+    """The K workers' accumulations spread over several streams give the same bits."""
+    from paper_2308_15164_amd.driver import DeviceRun
+    w = wl.WORKLOADS["cfg1_small"]
+    x0, pool, sched = wl.initial_params(w), wl.gradient_pool(w), wl.schedule(w)
+    res = []
+    for n_streams in (1, 2, 4):
+        print(f"[case] worker streams n={n_streams}", flush=True)
+        run = DeviceRun(w, x0, pool, sched, overlap=True, acc_streams=n_streams)
+        run.run(w.steps)
+        res.append(run.read_state() + (run.count_history,))
+        run.close()
+    for r in res[1:]:
+        _assert_bitexact(r[0], res[0][0], "worker streams x")
+        _assert_bitexact(r[1], res[0][1], "worker streams v")
+        assert r[2] == res[0][2]
 
 
 @pytest.mark.parametrize("name", ["tiny_tail_f32", "tiny_tail_bf16", "ragged_odd_f32", "ragged_odd_bf16"])
