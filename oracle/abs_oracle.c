@@ -26,6 +26,15 @@
  * M_r samples of a mean-reduced loss yields), so the sum of its per-sample
  * gradients is M_r * g.
  *
+ * Delayed gradient compensation (Section "Algorithm", third mechanism; the
+ * "Compensate delayed gradients" line of Algorithm 1):
+ *       Gtilde_t = Gbar_{t-1} + lambda * Gbar_{t-1} (.) Gbar_{t-1} (.) (x_t - x_{t-1})
+ * element-wise, applied in place of Gbar in the update.  The paper states it for
+ * plain SGD; with momentum and weight decay the compensated gradient takes
+ * Gbar's place (compensate first, then weight decay, then momentum).  The
+ * functions with the suffix _dc keep x_{t-1} in a buffer of their own, as the
+ * paper's remark on memory overhead implies.
+ *
  * Precision: everything in IEEE double.  Inputs (fp32 or bf16 gradients, fp32
  * hyper-parameters) are widened exactly before use.
  *
@@ -126,6 +135,36 @@ int oracle_sync_update(double *x, double *v, const double *const *G, const int64
     return 0;
 }
 
+/* Same with the delayed gradient compensation.  x_prev holds x_{t-1} on entry
+ * (equal to x when no update has been applied yet, so the correction vanishes
+ * at the first applied step) and x_t on return -- also when sum(M) == 0, in
+ * which case x_{t+1} = x_t and the function returns 1. */
+int oracle_sync_update_dc(double *x, double *x_prev, double *v, const double *const *G,
+                          const int64_t *M, int N, int64_t n_params, double gamma, double mu,
+                          double wd, double lambda)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) {
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n_params; ++j) x_prev[j] = x[j];
+        return 1;
+    }
+    const double Mt = (double)M_total;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < N; ++i) s += G[i][j];
+        const double Gbar = s / Mt;
+        const double Gtilde = Gbar + lambda * Gbar * Gbar * (x[j] - x_prev[j]);
+        const double d = Gtilde + wd * x[j];
+        v[j] = mu * v[j] + d;
+        x_prev[j] = x[j];
+        x[j] = x[j] - gamma * v[j];
+    }
+    return 0;
+}
+
 /* ---- fp32 family with a fixed operation order -------------------------- */
 
 /* first != 0: this is the first reference batch since the accumulator was
@@ -174,6 +213,44 @@ int oracle32_sync_update(float *x, float *v, const float *const *G, const int64_
         const float d = fmaf(wd, x[j], Gbar);
         const float vn = fmaf(mu, v[j], d);
         v[j] = vn;
+        x[j] = fmaf(-gamma, vn, x[j]);
+    }
+    return 0;
+}
+
+/* With compensation.  Order: Gbar as above; q = Gbar * Gbar; c = lambda * q;
+ * diff = x - x_prev; Gtilde = fma(c, diff, Gbar); d = fma(wd, x, Gtilde);
+ * v = fma(mu, v, d); x_prev = x; x = fma(-gamma, v, x). */
+int oracle32_sync_update_dc(float *x, float *x_prev, float *v, const float *const *G,
+                            const int64_t *M, int N, int64_t n_params, float gamma, float mu,
+                            float wd, float lambda)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) {
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n_params; ++j) x_prev[j] = x[j];
+        return 1;
+    }
+    const float Mt = (float)M_total;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        float s = 0.0f;
+        int seen = 0;
+        for (int i = 0; i < N; ++i) {
+            if (M[i] <= 0) continue;
+            s = seen ? s + G[i][j] : G[i][j];
+            seen = 1;
+        }
+        const float Gbar = s / Mt;
+        const float q = Gbar * Gbar;
+        const float c = lambda * q;
+        const float diff = x[j] - x_prev[j];
+        const float Gtilde = fmaf(c, diff, Gbar);
+        const float d = fmaf(wd, x[j], Gtilde);
+        const float vn = fmaf(mu, v[j], d);
+        v[j] = vn;
+        x_prev[j] = x[j];
         x[j] = fmaf(-gamma, vn, x[j]);
     }
     return 0;

@@ -54,6 +54,12 @@ def lib():
         _lib.oracle_sync_update.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
                                             _c_dbl, _c_dbl, _c_dbl]
         _lib.oracle_sync_update.restype = ctypes.c_int
+        _lib.oracle_sync_update_dc.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
+                                               _c_dbl, _c_dbl, _c_dbl, _c_dbl]
+        _lib.oracle_sync_update_dc.restype = ctypes.c_int
+        _lib.oracle32_sync_update_dc.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
+                                                 _c_flt, _c_flt, _c_flt, _c_flt]
+        _lib.oracle32_sync_update_dc.restype = ctypes.c_int
         _lib.oracle32_accumulate_f32.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_accumulate_bf16.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_sync_update.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
@@ -126,6 +132,27 @@ def sync_update(x, v, G_list, M_list, gamma, mu, wd):
     return rc == 0
 
 
+def sync_update_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
+    """sync_update with the delayed gradient compensation of Algorithm 1:
+    Gtilde = Gbar + lam * Gbar (.) Gbar (.) (x_t - x_{t-1}); x_prev holds x_{t-1}
+    on entry and x_t on return."""
+    _check(x, np.float64)
+    _check(x_prev, np.float64)
+    _check(v, np.float64)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float64)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    if x_prev.size != x.size:
+        raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    rc = lib().oracle_sync_update_dc(_ptr(x), _ptr(x_prev), _ptr(v), ptrs, _ptr(M), N, x.size,
+                                     float(gamma), float(mu), float(wd), float(lam))
+    return rc == 0
+
+
 # ---- fp32 family with the fixed operation order ------------------------------
 
 def accumulate32(G, g, M_r, first):
@@ -153,9 +180,26 @@ def sync_update32(x, v, G_list, M_list, gamma, mu, wd):
     return rc == 0
 
 
+def sync_update32_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
+    _check(x, np.float32)
+    _check(x_prev, np.float32)
+    _check(v, np.float32)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float32)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    f = lambda t: float(np.float32(t))
+    rc = lib().oracle32_sync_update_dc(_ptr(x), _ptr(x_prev), _ptr(v), ptrs, _ptr(M), N, x.size,
+                                       f(gamma), f(mu), f(wd), f(lam))
+    return rc == 0
+
+
 # ---- Algorithm 1, whole loop --------------------------------------------------
 
-def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None):
+def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None):
     """Run T iterations of Algorithm 1 on the flat parameter vector x0.
 
     batches(t, i) -> list of mean-gradient vectors (float32 or bf16 bits), one
@@ -169,8 +213,10 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None):
     The last generation is accumulated and never applied (the loop returns x_T).
 
     precision "f64": the definition in double.  "f32": the fixed-order fp32
-    restatement.  Returns (x_T, v_T, M_history[T][N]).  record(t, x, v) is
-    called after each iteration when given.
+    restatement.  lam: compensation coefficient lambda; None leaves the
+    compensation line of Algorithm 1 out (then no x_{t-1} is kept).
+    Returns (x_T, v_T, M_history[T][N]).  record(t, x, v) is called after each
+    iteration when given.
     """
     if precision == "f64":
         ft, upd_fn = np.float64, sync_update
@@ -180,6 +226,7 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None):
         raise ValueError(precision)
     P = x0.size
     x = np.array(x0, dtype=ft)
+    x_prev = x.copy()                  # no update applied yet: x_t - x_{t-1} = 0
     v = np.zeros(P, dtype=ft)
     G = [[np.zeros(P, dtype=ft) for _ in range(N)] for _ in range(2)]
     M = [[0] * N for _ in range(2)]   # G_{-1} = 0; its batch sizes are 0
@@ -197,7 +244,12 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None):
                     accumulate32(G[cur][i], g, M_r, first=(M[cur][i] == 0))
                 M[cur][i] += M_r
         # Step 1 + update: apply generation t-1 to x_t
-        upd_fn(x, v, G[prev], M[prev], gamma, mu, wd)
+        if lam is None:
+            upd_fn(x, v, G[prev], M[prev], gamma, mu, wd)
+        elif precision == "f64":
+            sync_update_dc(x, x_prev, v, G[prev], M[prev], gamma, mu, wd, lam)
+        else:
+            sync_update32_dc(x, x_prev, v, G[prev], M[prev], gamma, mu, wd, lam)
         history.append(list(M[cur]))
         if record is not None:
             record(t, x, v)

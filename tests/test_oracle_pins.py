@@ -359,3 +359,142 @@ def test_fp32_family_skips_idle_workers():
     assert orc.sync_update32(x, v, [stale, Ga], [0, 32], 1.0, 0.0, 0.0)
     np.testing.assert_array_equal(x, _f32(-1.0, -2.0))
     assert orc.sync_update32(x, v, [stale, Ga], [0, 0], 1.0, 0.0, 0.0) is False
+
+
+# ---------------------------------------------------------------------------
+# 10. delayed gradient compensation (third mechanism of Section "Algorithm")
+# ---------------------------------------------------------------------------
+
+def test_compensation_worked_example():
+    gold = _read_golden("worked_example.txt")
+    x = np.array([0.9, -1.9])
+    x_prev = np.array([1.0, -2.0])
+    v = np.zeros(2)
+    G = [np.array([0.5, -0.25]) * 64]
+    assert orc.sync_update_dc(x, x_prev, v, G, [64], 0.1, 0.0, 0.0, 0.5)
+    np.testing.assert_allclose(v, [float(f) for f in gold["dc_gtilde"]], rtol=1e-15)   # mu = wd = 0: v is Gtilde
+    np.testing.assert_allclose(x, [float(f) for f in gold["dc_x_next"]], rtol=1e-15)
+    np.testing.assert_array_equal(x_prev, [0.9, -1.9])                                  # now holds x_t
+
+
+def test_compensation_vanishes_for_lambda_zero_and_for_equal_iterates():
+    rng = np.random.default_rng(10)
+    P = 31
+    G = [rng.standard_normal(P) * 10, rng.standard_normal(P) * 10]
+    M = [32, 64]
+    x0 = rng.standard_normal(P)
+    xp = rng.standard_normal(P)
+    v0 = rng.standard_normal(P)
+    xa, va = x0.copy(), v0.copy()
+    orc.sync_update(xa, va, G, M, 0.1, 0.9, 5e-4)
+    # lambda = 0: any x_prev gives the uncompensated update
+    xb, vb, xpb = x0.copy(), v0.copy(), xp.copy()
+    orc.sync_update_dc(xb, xpb, vb, G, M, 0.1, 0.9, 5e-4, 0.0)
+    np.testing.assert_array_equal(xb, xa)
+    np.testing.assert_array_equal(vb, va)
+    np.testing.assert_array_equal(xpb, x0)
+    # x_prev == x (first applied step): any lambda gives the uncompensated update
+    xc, vc, xpc = x0.copy(), v0.copy(), x0.copy()
+    orc.sync_update_dc(xc, xpc, vc, G, M, 0.1, 0.9, 5e-4, 0.5)
+    np.testing.assert_array_equal(xc, xa)
+    np.testing.assert_array_equal(vc, va)
+    # and a non-trivial case really differs
+    xd, vd, xpd = x0.copy(), v0.copy(), xp.copy()
+    orc.sync_update_dc(xd, xpd, vd, G, M, 0.1, 0.9, 5e-4, 0.5)
+    assert np.max(np.abs(xd - xa)) > 1e-4
+
+
+def test_compensation_constant_gradient_closed_form():
+    """Plain SGD with constant Gbar = g: the increments d_t = x_t - x_{t-1} obey
+    d_{t+1} = -gamma*g + r*d_t with r = -gamma*lambda*g^2, a geometric series."""
+    g, gamma, lam, steps = 1.5, 0.1, 0.5, 15
+    r = -gamma * lam * g * g
+    G = [np.full(1, 32 * g)]
+    x, xp, v = np.array([2.0]), np.array([2.0]), np.zeros(1)
+    for n in range(1, steps + 1):
+        orc.sync_update_dc(x, xp, v, G, [32], gamma, 0.0, 0.0, lam)
+        d_n = -gamma * g * (1 - r ** n) / (1 - r)
+        np.testing.assert_allclose(x - xp, d_n, rtol=1e-12)
+    x_n = 2.0 - gamma * g * (steps - r * (1 - r ** steps) / (1 - r)) / (1 - r)
+    np.testing.assert_allclose(x, x_n, rtol=1e-12)
+
+
+def test_compensation_is_elementwise():
+    rng = np.random.default_rng(12)
+    P = 9
+    G = [rng.standard_normal(P) * 32]
+    x0, xp0 = rng.standard_normal(P), rng.standard_normal(P)
+    xa, xpa, va = x0.copy(), xp0.copy(), np.zeros(P)
+    orc.sync_update_dc(xa, xpa, va, G, [32], 0.1, 0.9, 1e-3, 0.5)
+    G2 = [G[0].copy()]
+    G2[0][4] += 100.0
+    xp2 = xp0.copy()
+    xp2[4] -= 3.0
+    xb, vb = x0.copy(), np.zeros(P)
+    orc.sync_update_dc(xb, xp2, vb, G2, [32], 0.1, 0.9, 1e-3, 0.5)
+    others = np.arange(P) != 4
+    np.testing.assert_array_equal(xb[others], xa[others])
+    assert xb[4] != xa[4]
+
+
+def test_compensation_empty_step_still_advances_previous_iterate():
+    x = np.array([1.0, 2.0])
+    xp = np.array([0.0, 0.0])
+    v = np.array([0.5, 0.5])
+    assert orc.sync_update_dc(x, xp, v, [np.zeros(2)], [0], 0.1, 0.9, 0.0, 0.5) is False
+    assert x.tolist() == [1.0, 2.0] and v.tolist() == [0.5, 0.5] and xp.tolist() == [1.0, 2.0]
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_compensation_brute_force_rational(seed):
+    """Whole loop with compensation against exact rationals from per-sample gradients."""
+    rng = np.random.default_rng(200 + seed)
+    P, N, T, M_r = 4, 2, 5, 4
+    gamma, mu, wd, lam = F32(0.1), F32(0.9), F32(5e-4), F32(0.5)
+    fg, fm, fw, fl = (Fraction(float(t)) for t in (gamma, mu, wd, lam))
+    m = rng.integers(1, 3, size=(T, N))
+    samples = {(t, i, j): rng.integers(-512, 513, size=(M_r, P))
+               for t in range(T) for i in range(N) for j in range(int(m[t, i]))}
+    x0 = (rng.integers(-1024, 1025, size=P) / 512.0).astype(F32)
+
+    def batches(t, i):
+        return [(samples[(t, i, j)].sum(axis=0) / (256.0 * M_r)).astype(F32)
+                for j in range(int(m[t, i]))]
+
+    x_o, v_o, _ = orc.run(x0, N, T, M_r, gamma, mu, wd, batches, lam=lam)
+
+    x = [Fraction(float(a)) for a in x0]
+    xprev = list(x)
+    v = [Fraction(0)] * P
+    for t in range(T):
+        if t >= 1:
+            alls = [samples[(t - 1, i, j)][s]
+                    for i in range(N) for j in range(int(m[t - 1, i])) for s in range(M_r)]
+            for p in range(P):
+                gbar = Fraction(int(sum(int(s[p]) for s in alls)), 256 * len(alls))
+                gt = gbar + fl * gbar * gbar * (x[p] - xprev[p])
+                d = gt + fw * x[p]
+                v[p] = fm * v[p] + d
+                xprev[p] = x[p]
+                x[p] = x[p] - fg * v[p]
+    np.testing.assert_allclose(x_o, [float(a) for a in x], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(v_o, [float(a) for a in v], rtol=1e-13, atol=1e-15)
+
+
+def test_compensation_fp32_family_tracks_double_family():
+    rng = np.random.default_rng(13)
+    P, N, T, M_r = 2051, 3, 6, 32
+    m = rng.integers(1, 4, size=(T, N))
+    pool = [(rng.standard_normal(P) * 0.5).astype(F32) for _ in range(8)]   # large gradients: a visible correction
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+
+    def batches(t, i):
+        return [pool[(3 * t + 5 * i + j) % 8] for j in range(int(m[t, i]))]
+
+    args = (x0, N, T, M_r, F32(0.1), F32(0.9), F32(5e-4), batches)
+    x64, v64, _ = orc.run(*args, precision="f64", lam=F32(0.5))
+    x32, v32, _ = orc.run(*args, precision="f32", lam=F32(0.5))
+    xb, _, _ = orc.run(*args, precision="f64")
+    assert np.max(np.abs(x64 - xb)) > 1e-4                       # the compensation is active here
+    assert np.max(np.abs(x32 - x64)) <= 2e-6 * np.max(np.abs(x64))
+    assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
