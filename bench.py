@@ -32,14 +32,15 @@ MEASURED_TRAFFIC = {
 }
 
 
-def bytes_per_param(w, m_row):
+def bytes_per_param(w, m_row, compensated=False):
     """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
     an accumulate reads one gradient element and reads+writes one fp32
     accumulator element (the first call of a step only writes it); the
-    sync-update reads K accumulators and reads+writes x and v."""
+    sync-update reads K accumulators and reads+writes x and v (and the previous
+    iterate when the delayed gradient compensation is on)."""
     gb = 4 if w.grad_dtype == "f32" else 2
     acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
-    return acc, 4 * w.K + 16
+    return acc, 4 * w.K + 16 + (8 if compensated else 0)
 
 
 def dominant_kernel(w):
@@ -69,7 +70,7 @@ def kernel_event_pass(run, plans, t0, steps, torch):
     pairs, launches = [], 0
     torch.cuda.synchronize()
     for t in range(t0, t0 + steps):
-        ctx.abs_sync_update(run.x_arg, run.v_arg, run.lr, run.mu, run.wd)
+        run.sync_update()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(run.s_acc)
@@ -185,6 +186,9 @@ def main():
                     help="blocks_per_cu,max_rows_per_tile (see abs_set_launch_tuning); default: the library's")
     ap.add_argument("--acc-streams", type=int, default=1,
                     help="streams the K workers' accumulations are spread over")
+    ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
+                    help="also apply the delayed gradient compensation with this coefficient "
+                         "(abs_sync_update_dc; +8 B/param); default: off, the BASELINE metric's path")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB copy kernel (profiler counter calibration)")
     args = ap.parse_args()
@@ -226,7 +230,8 @@ def main():
             plans_wanted.append((f"{n} accumulate streams (workers spread) | sync-update", True, n))
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
-    run = DeviceRun(w, x0, pool, sched, overlap=False)
+    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation)
+    comp = args.compensation is not None
     calls = [run.plan_step(t) for t in range(total)]
     timings = {}
     for name, overlap, n_acc in plans_wanted:
@@ -248,7 +253,7 @@ def main():
 
     step_bytes = 0
     for t in range(W, total):
-        a, s_ = bytes_per_param(w, sched[t])
+        a, s_ = bytes_per_param(w, sched[t], comp)
         step_bytes += (a + s_) * w.P
     gbs = step_bytes / dt / 1e9
     # Algorithmic bytes per accumulate launch = the step's accumulate bytes
@@ -277,6 +282,7 @@ def main():
             "samples_per_microbatch": w.n, "m_k": w.schedule + (str(list(w.ratio)) if w.ratio else ""),
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
             "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
+            "compensation_lambda": args.compensation,
             "streams": best + ", double-buffered",
             "algorithmic_bytes_per_step": step_bytes // K_steps,
         },

@@ -120,6 +120,30 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
                     void *stream);
 
 /* ------------------------------------------------------------------------
+ * (3') The same with delayed gradient compensation -- Algorithm 1, "Compensate
+ *     delayed gradients" (third mechanism of Section "Algorithm"):
+ *       Gtilde = Gbar + lambda * Gbar (.) Gbar (.) (x_t - x_{t-1})   element-wise,
+ *     used in place of Gbar.  The previous iterate x_{t-1} lives in a caller-owned
+ *     buffer (the memory overhead the paper mentions): +8 B/param of traffic.
+ *
+ *   Order after Gbar: q = Gbar*Gbar; c = lambda*q; diff = x[i] - xp[i];
+ *     Gtilde = fmaf(c, diff, Gbar); d = fmaf(wd, x[i], Gtilde); v[i] = fmaf(mu, v[i], d);
+ *     xp[i] = x[i] (the value on entry); x[i] = fmaf(-lr, v[i], x[i]).
+ *
+ *   params_prev  DEVICE, P floats, read and written.  The caller initialises it
+ *     to a copy of params before the first call (then x_t - x_{t-1} = 0 and the
+ *     first applied step is uncompensated, as in the paper where x_{-1} does not
+ *     exist).  When the total count is 0 the call copies params into params_prev
+ *     (x_{t+1} = x_t, so the next difference is 0) and returns ABS_EMPTY; this is
+ *     the one case in which ABS_EMPTY touches memory.
+ *   Other arguments, errors: as abs_sync_update; params_prev must differ from
+ *   params and momentum.
+ * ---------------------------------------------------------------------- */
+int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const float *const *acc,
+                       const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                       float lambda, void *stream);
+
+/* ------------------------------------------------------------------------
  * Ragged (multi-tensor) layouts: the parameter vector of Section "Problem
  * definition" split into T separately allocated tensors of arbitrary sizes.
  * One launch covers all tensors.
@@ -167,6 +191,12 @@ int abs_sync_update_mt(abs_layout *layout, const abs_tensorset *params,
                        const int64_t *counts, int K, float lr, float mu, float wd,
                        void *stream);
 
+/* abs_sync_update_dc over every tensor of the layout; params_prev an ABS_F32 set. */
+int abs_sync_update_dc_mt(abs_layout *layout, const abs_tensorset *params,
+                          const abs_tensorset *params_prev, const abs_tensorset *momentum,
+                          const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                          float mu, float wd, float lambda, void *stream);
+
 /* ------------------------------------------------------------------------
  * (4) Double buffer -- Algorithm 1, "Run Step 1 and Step 2 in parallel": two
  *     generations of (K accumulators, K counts).  Accumulation of batch t runs
@@ -208,6 +238,13 @@ int abs_ctx_sync_update(abs_ctx *ctx, float *params, float *momentum, float lr, 
                         float wd);
 int abs_ctx_sync_update_mt(abs_ctx *ctx, const abs_tensorset *params,
                            const abs_tensorset *momentum, float lr, float mu, float wd);
+
+/* The same with delayed gradient compensation (abs_sync_update_dc). */
+int abs_ctx_sync_update_dc(abs_ctx *ctx, float *params, float *params_prev, float *momentum,
+                           float lr, float mu, float wd, float lambda);
+int abs_ctx_sync_update_dc_mt(abs_ctx *ctx, const abs_tensorset *params,
+                              const abs_tensorset *params_prev, const abs_tensorset *momentum,
+                              float lr, float mu, float wd, float lambda);
 
 /* End of an iteration (Algorithm 1, t = t + 1): stream_upd and every accumulate
  * stream wait for the work the other side has enqueued so far (the next sync-update reads what accumulation

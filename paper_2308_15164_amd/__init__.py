@@ -31,6 +31,7 @@ SYMBOLS = {
     "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
     "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
+    "abs_sync_update_dc": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _vp]),
     "abs_layout_create": (_int, [_pvp, _int, _pi64]),
     "abs_layout_destroy": (_int, [_vp]),
     "abs_layout_num_tensors": (_int, [_vp]),
@@ -42,6 +43,7 @@ SYMBOLS = {
     "abs_tensorset_destroy": (_int, [_vp]),
     "abs_accumulate_mt": (_int, [_vp, _vp, _vp, _i64, _pi64, _vp]),
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
+    "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_destroy": (_int, [_vp]),
@@ -50,6 +52,8 @@ SYMBOLS = {
     "abs_ctx_accumulate_mt": (_int, [_vp, _int, _vp, _i64]),
     "abs_ctx_sync_update": (_int, [_vp, _vp, _vp, _f, _f, _f]),
     "abs_ctx_sync_update_mt": (_int, [_vp, _vp, _vp, _f, _f, _f]),
+    "abs_ctx_sync_update_dc": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
+    "abs_ctx_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
     "abs_swap_buffers": (_int, [_vp]),
     "abs_ctx_counts": (_int, [_vp, _int, _pi64]),
 }
@@ -187,6 +191,16 @@ def abs_sync_update(params, momentum, acc, counts, lr, mu, wd, stream=None, P=No
     return _check("abs_sync_update", rc, allow_empty=True)
 
 
+def abs_sync_update_dc(params, params_prev, momentum, acc, counts, lr, mu, wd, lam, stream=None, P=None):
+    """abs_sync_update with delayed gradient compensation; params_prev holds x_{t-1}."""
+    n = params.numel() if P is None else int(P)
+    ptrs = _ptr_array([_dev_ptr(a) for a in acc])
+    rc = lib().abs_sync_update_dc(_dev_ptr(params), _dev_ptr(params_prev), _dev_ptr(momentum), ptrs,
+                                  _i64_array(counts), len(acc), n, float(lr), float(mu), float(wd),
+                                  float(lam), _stream_handle(stream))
+    return _check("abs_sync_update_dc", rc, allow_empty=True)
+
+
 class Layout:
     """abs_layout: tensor sizes of a ragged parameter vector and its chunk table."""
 
@@ -272,6 +286,15 @@ def abs_sync_update_mt(layout, params, momentum, acc, counts, lr, mu, wd, stream
     return _check("abs_sync_update_mt", rc, allow_empty=True)
 
 
+def abs_sync_update_dc_mt(layout, params, params_prev, momentum, acc, counts, lr, mu, wd, lam,
+                          stream=None):
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_dc_mt(layout.handle, params.handle, params_prev.handle, momentum.handle,
+                                     sets, _i64_array(counts), len(acc), float(lr), float(mu),
+                                     float(wd), float(lam), _stream_handle(stream))
+    return _check("abs_sync_update_dc_mt", rc, allow_empty=True)
+
+
 class Context:
     """abs_ctx: the double buffer.  acc_A / acc_B are K tensors each (flat form)
     or K TensorSets each over `layout` (ragged form)."""
@@ -318,6 +341,16 @@ class Context:
                                           float(lr), float(mu), float(wd))
         return _check("abs_ctx_sync_update_mt", rc, allow_empty=True)
 
+    def abs_sync_update_dc(self, params, params_prev, momentum, lr, mu, wd, lam):
+        if self.layout is None:
+            rc = lib().abs_ctx_sync_update_dc(self.handle, _dev_ptr(params), _dev_ptr(params_prev),
+                                              _dev_ptr(momentum), float(lr), float(mu), float(wd),
+                                              float(lam))
+            return _check("abs_ctx_sync_update_dc", rc, allow_empty=True)
+        rc = lib().abs_ctx_sync_update_dc_mt(self.handle, params.handle, params_prev.handle,
+                                             momentum.handle, float(lr), float(mu), float(wd), float(lam))
+        return _check("abs_ctx_sync_update_dc_mt", rc, allow_empty=True)
+
     def abs_swap_buffers(self):
         return _check("abs_swap_buffers", lib().abs_swap_buffers(self.handle))
 
@@ -344,6 +377,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_sync_update", "abs_accumulate_mt", "abs_sync_update_mt", "abs_version",
+           "abs_sync_update", "abs_sync_update_dc", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

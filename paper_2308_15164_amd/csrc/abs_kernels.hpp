@@ -173,60 +173,76 @@ __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc,
 
 // --------------------------------------------------------------- sync-update
 
-struct Hyper { float M, lr, mu, wd; };
+struct Hyper { float M, lr, mu, wd, lambda; };
 
-__device__ __forceinline__ void update_one(float s, float &x, float &v, const Hyper &h)
+// DC: delayed gradient compensation, Gtilde = Gbar + lambda*Gbar*Gbar*(x - xp)
+// with xp the previous iterate; xp then takes the value x had on entry.
+template <bool DC>
+__device__ __forceinline__ void update_one(float s, float &x, float &v, float &xp, const Hyper &h)
 {
-    const float gbar = s / h.M;
-    const float d = __builtin_fmaf(h.wd, x, gbar);
+    float g = s / h.M;
+    if constexpr (DC) {
+        const float q = g * g;
+        const float c = h.lambda * q;
+        const float diff = x - xp;
+        g = __builtin_fmaf(c, diff, g);
+        xp = x;
+    }
+    const float d = __builtin_fmaf(h.wd, x, g);
     v = __builtin_fmaf(h.mu, v, d);
     x = __builtin_fmaf(-h.lr, v, x);
 }
 
-__device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &v, const Hyper &h)
+template <bool DC>
+__device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &v, f32x4 &xp, const Hyper &h)
 {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        float xs = x[c], vs = v[c];
-        update_one(s[c], xs, vs, h);
+        float xs = x[c], vs = v[c], ps = xp[c];
+        update_one<DC>(s[c], xs, vs, ps, h);
         x[c] = xs;
         v[c] = vs;
+        xp[c] = ps;
     }
 }
 
 template <int K> struct AccPtrs { const float *p[K]; };
 
 // rows per group so that about ABS_SYNC_INFLIGHT loads are outstanding per lane
-template <int K>
+template <int K, bool DC>
 constexpr int sync_unroll()
 {
-    int u = ABS_SYNC_INFLIGHT / (K + 2);
+    int u = ABS_SYNC_INFLIGHT / (K + 2 + (DC ? 1 : 0));
     return u < 1 ? 1 : (u > 4 ? 4 : u);
 }
 
 // One workgroup, one tile of the fused combine + update; K compile-time.
-// NTX: x / v traffic is streaming.
-template <int K, bool NTX>
+// NTX: x / v (/ xp) traffic is streaming.  xp is only touched when DC.
+template <int K, bool NTX, bool DC>
 __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restrict__ v,
-                                          const AccPtrs<K> &A, int len, const Hyper &h, bool vec_ok)
+                                          float *__restrict__ xp, const AccPtrs<K> &A, int len,
+                                          const Hyper &h, bool vec_ok)
 {
-    constexpr int U = sync_unroll<K>();
+    constexpr int U = sync_unroll<K, DC>();
     const int tid = threadIdx.x;
     if (!vec_ok) {
         for (int i = tid; i < len; i += BLOCK) {
             float s = A.p[0][i];
 #pragma unroll
             for (int k = 1; k < K; ++k) s = s + A.p[k][i];
-            update_one(s, x[i], v[i], h);
+            float ps = DC ? xp[i] : 0.f;
+            update_one<DC>(s, x[i], v[i], ps, h);
+            if constexpr (DC) xp[i] = ps;
         }
         return;
     }
     f32x4 *xv = reinterpret_cast<f32x4 *>(x);
     f32x4 *vv = reinterpret_cast<f32x4 *>(v);
+    f32x4 *pv = reinterpret_cast<f32x4 *>(xp);
     const int nvec = len / VEC;
     int g0 = 0;
     for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) {
-        f32x4 a[U][K], xr[U], vr[U];
+        f32x4 a[U][K], xr[U], vr[U], pr[U] = {};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = g0 + u * BLOCK + tid;
@@ -235,6 +251,7 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
                 a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
             xr[u] = ld<NTX>(xv + i);
             vr[u] = ld<NTX>(vv + i);
+            if constexpr (DC) pr[u] = ld<NTX>(pv + i);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -242,8 +259,9 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
             f32x4 s = a[u][0];
 #pragma unroll
             for (int k = 1; k < K; ++k) s = s + a[u][k];
-            update_vec(s, xr[u], vr[u], h);
+            update_vec<DC>(s, xr[u], vr[u], pr[u], h);
             st<NTX>(vv + i, vr[u]);
+            if constexpr (DC) st<NTX>(pv + i, pr[u]);
             st<NTX>(xv + i, xr[u]);
         }
     }
@@ -252,9 +270,11 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
 #pragma unroll
         for (int k = 1; k < K; ++k)
             s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
-        f32x4 xr = ld<NTX>(xv + i), vr = ld<NTX>(vv + i);
-        update_vec(s, xr, vr, h);
+        f32x4 xr = ld<NTX>(xv + i), vr = ld<NTX>(vv + i), pr = {};
+        if constexpr (DC) pr = ld<NTX>(pv + i);
+        update_vec<DC>(s, xr, vr, pr, h);
         st<NTX>(vv + i, vr);
+        if constexpr (DC) st<NTX>(pv + i, pr);
         st<NTX>(xv + i, xr);
     }
     const int i = nvec * VEC + tid;
@@ -262,30 +282,40 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
         float s = A.p[0][i];
 #pragma unroll
         for (int k = 1; k < K; ++k) s = s + A.p[k][i];
-        update_one(s, x[i], v[i], h);
+        float ps = DC ? xp[i] : 0.f;
+        update_one<DC>(s, x[i], v[i], ps, h);
+        if constexpr (DC) xp[i] = ps;
     }
 }
 
 // K known only at run time (K above the specialised range).  get(k) yields
 // worker k's accumulator pointer for this tile; it is uniform across the
-// workgroup, so it costs scalar loads only.
+// workgroup, so it costs scalar loads only.  xp == nullptr: no compensation.
 template <class GetPtr>
 __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__restrict__ v,
-                                              GetPtr get, int K, int len, const Hyper &h,
-                                              bool vec_ok)
+                                              float *__restrict__ xp, GetPtr get, int K, int len,
+                                              const Hyper &h, bool vec_ok)
 {
     const int tid = threadIdx.x;
+    const bool dc = xp != nullptr;
     if (vec_ok) {
         f32x4 *xv = reinterpret_cast<f32x4 *>(x);
         f32x4 *vv = reinterpret_cast<f32x4 *>(v);
+        f32x4 *pv = reinterpret_cast<f32x4 *>(xp);
         const int nvec = len / VEC;
         for (int i = tid; i < nvec; i += BLOCK) {
             f32x4 s = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(get(0)) + i);
 #pragma unroll 8
             for (int k = 1; k < K; ++k)
                 s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(get(k)) + i);
-            f32x4 xr = xv[i], vr = vv[i];
-            update_vec(s, xr, vr, h);
+            f32x4 xr = xv[i], vr = vv[i], pr = {};
+            if (dc) {
+                pr = pv[i];
+                update_vec<true>(s, xr, vr, pr, h);
+                pv[i] = pr;
+            } else {
+                update_vec<false>(s, xr, vr, pr, h);
+            }
             vv[i] = vr;
             xv[i] = xr;
         }
@@ -293,15 +323,36 @@ __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__re
         if (i < len) {
             float s = get(0)[i];
             for (int k = 1; k < K; ++k) s = s + get(k)[i];
-            update_one(s, x[i], v[i], h);
+            float ps = 0.f;
+            if (dc) { ps = xp[i]; update_one<true>(s, x[i], v[i], ps, h); xp[i] = ps; }
+            else update_one<false>(s, x[i], v[i], ps, h);
         }
         return;
     }
     for (int i = tid; i < len; i += BLOCK) {
         float s = get(0)[i];
         for (int k = 1; k < K; ++k) s = s + get(k)[i];
-        update_one(s, x[i], v[i], h);
+        float ps = 0.f;
+        if (dc) { ps = xp[i]; update_one<true>(s, x[i], v[i], ps, h); xp[i] = ps; }
+        else update_one<false>(s, x[i], v[i], ps, h);
     }
+}
+
+// dst[0..len) = src[0..len): keeps the previous-iterate buffer current on a step
+// that applies nothing.
+__device__ __forceinline__ void copy_tile(float *__restrict__ dst, const float *__restrict__ src, int len,
+                                          bool vec_ok)
+{
+    const int tid = threadIdx.x;
+    if (vec_ok) {
+        const int nvec = len / VEC;
+        for (int i = tid; i < nvec; i += BLOCK)
+            reinterpret_cast<f32x4 *>(dst)[i] = reinterpret_cast<const f32x4 *>(src)[i];
+        const int i = nvec * VEC + tid;
+        if (i < len) dst[i] = src[i];
+        return;
+    }
+    for (int i = tid; i < len; i += BLOCK) dst[i] = src[i];
 }
 
 struct AccPtrsAny { const float *p[64]; };
@@ -331,26 +382,37 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_flat(float *__restrict__
                                tile_len(P, base, tile), nf, first != 0, vec_ok != 0);
 }
 
-template <int K, bool NTX>
+template <int K, bool NTX, bool DC>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat(float *__restrict__ x,
-                                                             float *__restrict__ v, AccPtrs<K> A,
+                                                             float *__restrict__ v,
+                                                             float *__restrict__ xp, AccPtrs<K> A,
                                                              int64_t P, int tile, Hyper h, int vec_ok)
 {
     const int64_t base = (int64_t)blockIdx.x * tile;
     AccPtrs<K> B;
 #pragma unroll
     for (int k = 0; k < K; ++k) B.p[k] = A.p[k] + base;
-    sync_tile<K, NTX>(x + base, v + base, B, tile_len(P, base, tile), h, vec_ok != 0);
+    sync_tile<K, NTX, DC>(x + base, v + base, DC ? xp + base : nullptr, B, tile_len(P, base, tile), h,
+                          vec_ok != 0);
 }
 
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restrict__ x,
                                                                  float *__restrict__ v,
+                                                                 float *__restrict__ xp,
                                                                  AccPtrsAny A, int K, int64_t P,
                                                                  int tile, Hyper h, int vec_ok)
 {
     const int64_t base = (int64_t)blockIdx.x * tile;
-    sync_tile_any(x + base, v + base, [&](int k) { return A.p[k] + base; }, K,
+    sync_tile_any(x + base, v + base, xp ? xp + base : nullptr, [&](int k) { return A.p[k] + base; }, K,
                   tile_len(P, base, tile), h, vec_ok != 0);
+}
+
+__global__ __launch_bounds__(ABS_BLOCK) void copy_flat(float *__restrict__ dst,
+                                                      const float *__restrict__ src, int64_t P,
+                                                      int tile, int vec_ok)
+{
+    const int64_t base = (int64_t)blockIdx.x * tile;
+    copy_tile(dst + base, src + base, tile_len(P, base, tile), vec_ok != 0);
 }
 
 // Ragged layout: workgroup b looks its (tensor, tile index) up in a table; the
@@ -377,31 +439,38 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__re
 template <int K> struct TabPtrs { const float *const *t[K]; };
 struct TabPtrsAny { const float *const *t[64]; };
 
-template <int K, bool NTX>
+template <int K, bool NTX, bool DC>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__restrict__ chunks,
                                                                const int64_t *__restrict__ sizes,
                                                                float *const *__restrict__ x_tab,
                                                                float *const *__restrict__ v_tab,
+                                                               float *const *__restrict__ p_tab,
                                                                TabPtrs<K> tabs, int tile, Hyper h)
 {
     const Chunk c = chunks[blockIdx.x];
     const int64_t base = (int64_t)c.index * tile;
     float *x = x_tab[c.tensor] + base;
     float *v = v_tab[c.tensor] + base;
+    float *xp = nullptr;
     bool vec_ok = aligned16(x) && aligned16(v);
+    if constexpr (DC) {
+        xp = p_tab[c.tensor] + base;
+        vec_ok = vec_ok && aligned16(xp);
+    }
     AccPtrs<K> A;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         A.p[k] = tabs.t[k][c.tensor] + base;
         vec_ok = vec_ok && aligned16(A.p[k]);
     }
-    sync_tile<K, NTX>(x, v, A, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
+    sync_tile<K, NTX, DC>(x, v, xp, A, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
 }
 
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk *__restrict__ chunks,
                                                                    const int64_t *__restrict__ sizes,
                                                                    float *const *__restrict__ x_tab,
                                                                    float *const *__restrict__ v_tab,
+                                                                   float *const *__restrict__ p_tab,
                                                                    TabPtrsAny tabs, int K, int tile,
                                                                    Hyper h)
 {
@@ -409,10 +478,23 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk 
     const int64_t base = (int64_t)c.index * tile;
     float *x = x_tab[c.tensor] + base;
     float *v = v_tab[c.tensor] + base;
-    bool vec_ok = aligned16(x) && aligned16(v);
+    float *xp = p_tab ? p_tab[c.tensor] + base : nullptr;
+    bool vec_ok = aligned16(x) && aligned16(v) && aligned16(xp);
     for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned16(tabs.t[k][c.tensor] + base);
-    sync_tile_any(x, v, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
+    sync_tile_any(x, v, xp, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
                   tile_len(sizes[c.tensor], base, tile), h, vec_ok);
+}
+
+__global__ __launch_bounds__(ABS_BLOCK) void copy_ragged(const Chunk *__restrict__ chunks,
+                                                        const int64_t *__restrict__ sizes,
+                                                        float *const *__restrict__ dst_tab,
+                                                        float *const *__restrict__ src_tab, int tile)
+{
+    const Chunk c = chunks[blockIdx.x];
+    const int64_t base = (int64_t)c.index * tile;
+    float *dst = dst_tab[c.tensor] + base;
+    const float *src = src_tab[c.tensor] + base;
+    copy_tile(dst, src, tile_len(sizes[c.tensor], base, tile), aligned16(dst) && aligned16(src));
 }
 
 }  // namespace absk

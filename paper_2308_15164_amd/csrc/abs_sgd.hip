@@ -125,10 +125,10 @@ int plan_combine(const int64_t *counts, int K, Combine &c)
 // that are evicted before their reuse.  -1 = decide from the sizes.
 int g_policy_acc = -1, g_policy_upd = -1;
 constexpr int64_t kAccStreamBytes = ABS_ACC_STREAM_BYTES;   // accumulator bytes above which accumulate streams
-constexpr int64_t kUpdStreamBytes = ABS_UPD_STREAM_BYTES;   // bytes of x + v above which sync-update streams
+constexpr int64_t kUpdStreamBytes = ABS_UPD_STREAM_BYTES;   // bytes of x + v (+ previous x) above which sync-update streams
 
 inline bool stream_acc(int64_t P) { return g_policy_acc < 0 ? 4 * P > kAccStreamBytes : g_policy_acc != 0; }
-inline bool stream_upd(int64_t P) { return g_policy_upd < 0 ? 8 * P > kUpdStreamBytes : g_policy_upd != 0; }
+inline bool stream_upd(int64_t P, int vectors = 2) { return g_policy_upd < 0 ? 4 * vectors * P > kUpdStreamBytes : g_policy_upd != 0; }
 
 // ------------------------------------------------------------ flat launches
 
@@ -148,26 +148,32 @@ int launch_accumulate_flat(float *acc, const void *grad, abs_dtype dt, int64_t P
 }
 
 template <int K>
-int launch_sync_flat_k(float *x, float *v, const float *const *ptrs, int64_t P, Hyper h,
+int launch_sync_flat_k(float *x, float *v, float *xp, const float *const *ptrs, int64_t P, Hyper h,
                        int vec_ok, hipStream_t s)
 {
-    static const int resident = resident_blocks(sync_update_flat<K, false>, 4);
-    const int64_t tile64 = choose_tile(rows_of(P), g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : resident);
+    static const int resident = resident_blocks(sync_update_flat<K, false, false>, 4);
+    static const int resident_dc = resident_blocks(sync_update_flat<K, false, true>, 4);
+    const int res = g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : (xp ? resident_dc : resident);
+    const int64_t tile64 = choose_tile(rows_of(P), res);
     if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
     const int tile = (int)tile64;
     AccPtrs<K> A;
     for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
     const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
-    if (stream_upd(P)) hipLaunchKernelGGL((sync_update_flat<K, true>), grid, block, 0, s, x, v, A, P, tile, h, vec_ok);
-    else hipLaunchKernelGGL((sync_update_flat<K, false>), grid, block, 0, s, x, v, A, P, tile, h, vec_ok);
+    // x, v and the previous iterate are each re-read one iteration later
+    const bool ntx = stream_upd(P, xp ? 3 : 2);
+    if (xp && ntx) hipLaunchKernelGGL((sync_update_flat<K, true, true>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    else if (xp) hipLaunchKernelGGL((sync_update_flat<K, false, true>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    else if (ntx) hipLaunchKernelGGL((sync_update_flat<K, true, false>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    else hipLaunchKernelGGL((sync_update_flat<K, false, false>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
     return ABS_OK;
 }
 
-int launch_sync_flat(float *x, float *v, const float *const *ptrs, int n, int64_t P, Hyper h,
+int launch_sync_flat(float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P, Hyper h,
                      int vec_ok, hipStream_t s)
 {
     switch (n) {
-#define ABS_CASE(K) case K: return launch_sync_flat_k<K>(x, v, ptrs, P, h, vec_ok, s);
+#define ABS_CASE(K) case K: return launch_sync_flat_k<K>(x, v, xp, ptrs, P, h, vec_ok, s);
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
         ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
         ABS_CASE(16)
@@ -179,10 +185,20 @@ int launch_sync_flat(float *x, float *v, const float *const *ptrs, int n, int64_
         std::memset(&A, 0, sizeof A);
         for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
         hipLaunchKernelGGL(sync_update_flat_any, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s,
-                           x, v, A, n, P, (int)tile64, h, vec_ok);
+                           x, v, xp, A, n, P, (int)tile64, h, vec_ok);
         return ABS_OK;
     }
     }
+}
+
+int launch_copy_flat(float *dst, const float *src, int64_t P, hipStream_t s)
+{
+    const int64_t tile64 = choose_tile(rows_of(P), acc_resident());
+    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
+    const int vec_ok = aligned_to(dst, 16) && aligned_to(src, 16);
+    hipLaunchKernelGGL(copy_flat, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s, dst, src, P,
+                       (int)tile64, vec_ok);
+    return ABS_OK;
 }
 
 }  // namespace
@@ -250,23 +266,24 @@ int layout_to_device(abs_layout *L)
 }
 
 template <int K>
-void launch_sync_ragged_k(const abs_layout *L, float *const *xt, float *const *vt,
+void launch_sync_ragged_k(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
                           const float *const *const *tabs, Hyper h, hipStream_t s)
 {
     TabPtrs<K> T;
     for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
     const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-    if (stream_upd(L->total))
-        hipLaunchKernelGGL((sync_update_ragged<K, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, T, L->tile, h);
-    else
-        hipLaunchKernelGGL((sync_update_ragged<K, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, T, L->tile, h);
+    const bool ntx = stream_upd(L->total, pt ? 3 : 2);
+    if (pt && ntx) hipLaunchKernelGGL((sync_update_ragged<K, true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
+    else if (pt) hipLaunchKernelGGL((sync_update_ragged<K, false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
+    else if (ntx) hipLaunchKernelGGL((sync_update_ragged<K, true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
+    else hipLaunchKernelGGL((sync_update_ragged<K, false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
 }
 
-void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
+void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
                         const float *const *const *tabs, int n, Hyper h, hipStream_t s)
 {
     switch (n) {
-#define ABS_CASE(K) case K: launch_sync_ragged_k<K>(L, xt, vt, tabs, h, s); break;
+#define ABS_CASE(K) case K: launch_sync_ragged_k<K>(L, xt, vt, pt, tabs, h, s); break;
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
         ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
         ABS_CASE(16)
@@ -276,7 +293,7 @@ void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
         std::memset(&T, 0, sizeof T);
         for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
         hipLaunchKernelGGL(sync_update_ragged_any, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
-                           L->d_chunks, L->d_sizes, xt, vt, T, n, L->tile, h);
+                           L->d_chunks, L->d_sizes, xt, vt, pt, T, n, L->tile, h);
     }
     }
 }
@@ -347,29 +364,57 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
     return ABS_OK;
 }
 
-int abs_sync_update(float *params, float *momentum, const float *const *acc,
-                    const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
-                    void *stream)
+// params_prev == nullptr: no compensation.
+static int sync_update_flat_impl(float *params, float *params_prev, bool dc, float *momentum,
+                                 const float *const *acc, const int64_t *counts, int K, int64_t P,
+                                 float lr, float mu, float wd, float lambda, void *stream)
 {
     if (!acc || P < 0) return ABS_EINVAL;
     Combine c;
     int rc = plan_combine(counts, K, c);
-    if (rc != ABS_OK) return rc;
-    if (P == 0) return ABS_OK;
+    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
+    const bool empty = rc == ABS_EMPTY;
+    if (empty && !dc) return ABS_EMPTY;
+    if (P == 0) return empty ? ABS_EMPTY : ABS_OK;
     if (!params || !momentum || params == momentum) return ABS_EINVAL;
     if (!aligned_to(params, 4) || !aligned_to(momentum, 4)) return ABS_EINVAL;
+    if (dc && (!params_prev || params_prev == params || params_prev == momentum || !aligned_to(params_prev, 4)))
+        return ABS_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (empty) {
+        // x_{t+1} = x_t: the previous-iterate buffer must still advance
+        rc = launch_copy_flat(params_prev, params, P, s);
+        if (rc != ABS_OK) return rc;
+        rc = launch_status();
+        return rc == ABS_OK ? ABS_EMPTY : rc;
+    }
     const float *ptrs[ABS_MAX_K];
-    bool vec = aligned_to(params, 16) && aligned_to(momentum, 16);
+    bool vec = aligned_to(params, 16) && aligned_to(momentum, 16) && (!dc || aligned_to(params_prev, 16));
     for (int j = 0; j < c.n; ++j) {
         const float *p = acc[c.idx[j]];
         if (!p || !aligned_to(p, 4)) return ABS_EINVAL;
         vec = vec && aligned_to(p, 16);
         ptrs[j] = p;
     }
-    const Hyper h = {(float)c.M, lr, mu, wd};
-    rc = launch_sync_flat(params, momentum, ptrs, c.n, P, h, vec ? 1 : 0, static_cast<hipStream_t>(stream));
+    const Hyper h = {(float)c.M, lr, mu, wd, lambda};
+    rc = launch_sync_flat(params, momentum, dc ? params_prev : nullptr, ptrs, c.n, P, h, vec ? 1 : 0, s);
     if (rc != ABS_OK) return rc;
     return launch_status();
+}
+
+int abs_sync_update(float *params, float *momentum, const float *const *acc,
+                    const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                    void *stream)
+{
+    return sync_update_flat_impl(params, nullptr, false, momentum, acc, counts, K, P, lr, mu, wd, 0.f, stream);
+}
+
+int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const float *const *acc,
+                       const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                       float lambda, void *stream)
+{
+    return sync_update_flat_impl(params, params_prev, true, momentum, acc, counts, K, P, lr, mu, wd, lambda,
+                                 stream);
 }
 
 // ---------------------------------------------------------------- ragged
@@ -490,30 +535,57 @@ int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensors
     return ABS_OK;
 }
 
-int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
-                       const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
-                       float mu, float wd, void *stream)
+static int sync_update_mt_impl(abs_layout *L, const abs_tensorset *params, const abs_tensorset *prev,
+                               bool dc, const abs_tensorset *momentum, const abs_tensorset *const *acc,
+                               const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
+                               void *stream)
 {
     if (!L || !acc) return ABS_EINVAL;
     Combine c;
     int rc = plan_combine(counts, K, c);
-    if (rc != ABS_OK) return rc;
+    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
+    const bool empty = rc == ABS_EMPTY;
+    if (empty && !dc) return ABS_EMPTY;
     if (!set_ok(params, L) || !set_ok(momentum, L) || params == momentum) return ABS_EINVAL;
     if (params->elem != ABS_F32 || momentum->elem != ABS_F32) return ABS_EINVAL;
+    if (dc && (!set_ok(prev, L) || prev == params || prev == momentum || prev->elem != ABS_F32)) return ABS_EINVAL;
     const float *const *tabs[ABS_MAX_K];
     for (int j = 0; j < c.n; ++j) {
         const abs_tensorset *s = acc[c.idx[j]];
         if (!set_ok(s, L) || s->elem != ABS_F32) return ABS_EINVAL;
         tabs[j] = reinterpret_cast<const float *const *>(s->d_tab);
     }
-    if (L->chunks.empty()) return ABS_OK;
+    if (L->chunks.empty()) return empty ? ABS_EMPTY : ABS_OK;
     rc = layout_to_device(L);
     if (rc != ABS_OK) return rc;
-    const Hyper h = {(float)c.M, lr, mu, wd};
-    launch_sync_ragged(L, reinterpret_cast<float *const *>(params->d_tab),
-                       reinterpret_cast<float *const *>(momentum->d_tab), tabs, c.n, h,
-                       static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
+    float *const *pt = dc ? reinterpret_cast<float *const *>(prev->d_tab) : nullptr;
+    if (empty) {
+        hipLaunchKernelGGL(copy_ragged, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s, L->d_chunks,
+                           L->d_sizes, pt, xt, L->tile);
+        rc = launch_status();
+        return rc == ABS_OK ? ABS_EMPTY : rc;
+    }
+    const Hyper h = {(float)c.M, lr, mu, wd, lambda};
+    launch_sync_ragged(L, xt, reinterpret_cast<float *const *>(momentum->d_tab), pt, tabs, c.n, h, s);
     return launch_status();
+}
+
+int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                       const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                       float mu, float wd, void *stream)
+{
+    return sync_update_mt_impl(L, params, nullptr, false, momentum, acc, counts, K, lr, mu, wd, 0.f, stream);
+}
+
+int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *params_prev,
+                          const abs_tensorset *momentum, const abs_tensorset *const *acc,
+                          const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
+                          void *stream)
+{
+    return sync_update_mt_impl(L, params, params_prev, true, momentum, acc, counts, K, lr, mu, wd, lambda,
+                               stream);
 }
 
 // --------------------------------------------------------- double buffer
@@ -634,6 +706,24 @@ int abs_ctx_sync_update_mt(abs_ctx *C, const abs_tensorset *params, const abs_te
     const int prev = C->cur ^ 1;
     return abs_sync_update_mt(C->layout, params, momentum, C->set[prev].data(), C->counts[prev].data(),
                               C->K, lr, mu, wd, C->s_upd);
+}
+
+int abs_ctx_sync_update_dc(abs_ctx *C, float *params, float *params_prev, float *momentum, float lr,
+                           float mu, float wd, float lambda)
+{
+    if (!C || C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_dc(params, params_prev, momentum, C->acc[prev].data(), C->counts[prev].data(),
+                              C->K, C->P, lr, mu, wd, lambda, C->s_upd);
+}
+
+int abs_ctx_sync_update_dc_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *params_prev,
+                              const abs_tensorset *momentum, float lr, float mu, float wd, float lambda)
+{
+    if (!C || !C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_dc_mt(C->layout, params, params_prev, momentum, C->set[prev].data(),
+                                 C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->s_upd);
 }
 
 int abs_swap_buffers(abs_ctx *C)

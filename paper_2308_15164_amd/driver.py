@@ -28,13 +28,14 @@ class DeviceRun:
     acc_streams=n: the K workers' accumulations spread over n streams.
     """
 
-    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1):
+    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
         self.m = np.asarray(schedule)
         self.gdt = ABS_BF16 if w.grad_dtype == "bf16" else ABS_F32
         self.ragged = w.tensor_sizes is not None
+        self.lam = None if lam is None else float(lam)   # delayed gradient compensation coefficient
         self._streams = [torch.cuda.Stream(device=torch.device("cuda:0")) for _ in range(9)]
         self.ctx = None
         if not self.ragged:
@@ -47,8 +48,10 @@ class DeviceRun:
                     a.fill_(float("nan"))
             self.pool = [_upload(g) for g in pool]
             self.pool_ptr = [g.data_ptr() for g in self.pool]
+            self.xp = self.x.clone() if self.lam is not None else None    # x_{t-1}; starts equal to x_0
             torch.cuda.synchronize()
             self.x_arg, self.v_arg = self.x.data_ptr(), self.v.data_ptr()
+            self.xp_arg = self.xp.data_ptr() if self.xp is not None else None
         else:
             sizes = list(w.tensor_sizes)
             off = wl.tensor_offsets(sizes)
@@ -70,6 +73,11 @@ class DeviceRun:
                              for g in range(2)]
             self.pool_sets = [TensorSet(self.layout, p, dtype=self.gdt) for p in self.pool_t]
             self.x_arg, self.v_arg = self.x_set, self.v_set
+            self.xp_arg = None
+            if self.lam is not None:
+                self.xp_t = [t.clone() for t in self.x_t]
+                torch.cuda.synchronize()
+                self.xp_arg = TensorSet(self.layout, self.xp_t)
         self.configure_streams(overlap, acc_streams)
         self.lr, self.mu, self.wd = float(w.lr), float(w.mu), float(w.wd)
         self.applied = []
@@ -107,11 +115,18 @@ class DeviceRun:
                 calls.append((k, self.grad_arg(wl.pool_index(self.w, t, k, j, R))))
         return calls
 
+    def sync_update(self):
+        """Step 1 + update on the delayed generation (compensated when lam is set)."""
+        if self.lam is None:
+            return self.ctx.abs_sync_update(self.x_arg, self.v_arg, self.lr, self.mu, self.wd)
+        return self.ctx.abs_sync_update_dc(self.x_arg, self.xp_arg, self.v_arg, self.lr, self.mu, self.wd,
+                                           self.lam)
+
     def step(self, t, calls=None):
         """One iteration of Algorithm 1: Step 1 + update on the delayed generation,
         Step 2 (accumulation) on the current one, then the swap."""
         ctx, n, gdt = self.ctx, self.w.n, self.gdt
-        applied = ctx.abs_sync_update(self.x_arg, self.v_arg, self.lr, self.mu, self.wd)
+        applied = self.sync_update()
         for k, g in (self.plan_step(t) if calls is None else calls):
             ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
         ctx.abs_swap_buffers()

@@ -248,20 +248,102 @@ def test_sync_update_unaligned_views(absgd):
 
 
 # ---------------------------------------------------------------------------
+# abs_sync_update_dc: delayed gradient compensation, call by call
+# ---------------------------------------------------------------------------
+
+def _sync_dc_case(absgd, K, P, counts, seed, lam=0.5, lr=0.1, mu=0.9, wd=5e-4, shifts=None):
+    rng = np.random.default_rng(seed)
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    xp0 = (x0 + rng.standard_normal(P).astype(F32) * F32(0.02)).astype(F32)
+    v0 = (rng.standard_normal(P) * 0.02).astype(F32)
+    accs = [(rng.standard_normal(P) * 20.0 * max(c, 1) / 32).astype(F32) for c in counts]   # |Gbar| ~ 1..10
+
+    def up(a, s):
+        if not s:
+            return _up(a)
+        pad = np.zeros(P + 8, dtype=F32)
+        pad[s:s + P] = a
+        return _up(pad)[s:s + P]
+
+    sh = shifts or [0] * (K + 3)
+    x_d, xp_d, v_d = up(x0, sh[0]), up(xp0, sh[1]), up(v0, sh[2])
+    acc_d = [up(a, sh[3 + k]) if c > 0 else torch.full((P,), float("nan"), device="cuda")
+             for k, (a, c) in enumerate(zip(accs, counts))]
+    applied = absgd.abs_sync_update_dc(x_d, xp_d, v_d, acc_d, counts, lr, mu, wd, lam)
+    x32, xp32, v32 = x0.copy(), xp0.copy(), v0.copy()
+    ok32 = orc.sync_update32_dc(x32, xp32, v32, accs, counts, lr, mu, wd, lam)
+    x64, xp64, v64 = (a.astype(np.float64) for a in (x0, xp0, v0))
+    G64 = [a.astype(np.float64) if c > 0 else np.zeros(P) for a, c in zip(accs, counts)]
+    f = lambda t: float(F32(t))
+    ok64 = orc.sync_update_dc(x64, xp64, v64, G64, counts, f(lr), f(mu), f(wd), f(lam))
+    assert applied == ok32 == ok64
+    gx, gp, gv = x_d.cpu().numpy(), xp_d.cpu().numpy(), v_d.cpu().numpy()
+    _assert_bitexact(gx, x32, f"dc x K={K} P={P}")
+    _assert_bitexact(gv, v32, f"dc v K={K} P={P}")
+    _assert_bitexact(gp, xp32, f"dc x_prev K={K} P={P}")
+    _assert_bitexact(gp, x0, "x_prev takes the value x had on entry")
+    if applied:
+        M = float(sum(counts))
+        gbar = sum(g for g in G64) / M
+        gbar_mag = sum(np.abs(g) for g in G64) / M
+        corr = f(lam) * gbar * gbar * np.abs(x0.astype(np.float64) - xp0.astype(np.float64))
+        v_scale = f(mu) * np.abs(v0.astype(np.float64)) + gbar_mag + np.abs(corr) + f(wd) * np.abs(x0.astype(np.float64))
+        # squaring Gbar doubles its relative error: allow for it in the operand scale
+        v_scale = v_scale + 2 * np.abs(corr) * gbar_mag / np.maximum(np.abs(gbar), 1e-30)
+        x_scale = np.abs(x0.astype(np.float64)) + f(lr) * v_scale
+        _assert_close64(gv, v64, v_scale, "dc v")
+        _assert_close64(gx, x64, x_scale, "dc x")
+        if P >= 1000 and lam != 0:
+            assert np.max(np.abs(corr)) > 1e-3 * np.max(gbar_mag)      # the correction is not negligible here
+    else:
+        _assert_bitexact(gx, x0, "untouched x")
+        _assert_bitexact(gv, v0, "untouched v")
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 7, 8, 11, 16, 17, 40])
+def test_sync_update_dc_worker_counts(absgd, K):
+    print(f"[case] sync_update_dc K={K}", flush=True)
+    _sync_dc_case(absgd, K, 3 * 4096 + 1029, [32 * (1 + (3 * k) % 5) for k in range(K)], seed=100 + K)
+
+
+@pytest.mark.parametrize("P", [1, 5, 4097, 100_003, 1_048_576 + 13])
+def test_sync_update_dc_sizes(absgd, P):
+    print(f"[case] sync_update_dc P={P}", flush=True)
+    _sync_dc_case(absgd, 4, P, [64, 64, 128, 256], seed=200 + P % 1000)
+
+
+def test_sync_update_dc_edges(absgd):
+    print("[case] sync_update_dc edges", flush=True)
+    _sync_dc_case(absgd, 3, 9001, [0, 0, 0], seed=301)                       # empty step: x_prev <- x, nothing else
+    _sync_dc_case(absgd, 5, 9001, [0, 96, 0, 32, 0], seed=302)               # idle workers skipped
+    _sync_dc_case(absgd, 4, 9001, [32] * 4, seed=303, lam=0.0)               # lambda = 0
+    _sync_dc_case(absgd, 4, 50_000, [384, 192, 128, 96], seed=304, lr=0.01, mu=0.0, wd=0.0)   # the paper's plain SGD
+    _sync_dc_case(absgd, 3, 4096 + 11, [32, 64, 32], seed=305, shifts=[1, 2, 0, 0, 3, 2])     # unaligned views
+    _sync_dc_case(absgd, 18, 4096 + 11, [32] * 18, seed=306, shifts=[1] + [0] * 20)           # run-time K, unaligned
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+@pytest.mark.parametrize("K", [3, 9, 16])
+def test_sync_update_dc_multi_row_tiles(absgd, tuned, K):
+    print(f"[case] sync_update_dc multi-row K={K} tuning={tuned}", flush=True)
+    _sync_dc_case(absgd, K, 1_048_576 + 13, [32 * (1 + k % 3) for k in range(K)], seed=400 + K)
+
+
+# ---------------------------------------------------------------------------
 # whole trajectories through the double-buffered context (Algorithm 1 loop)
 # ---------------------------------------------------------------------------
 
-def _oracle_trajectory(w, x0, pool, sched, steps, precision, R=None):
+def _oracle_trajectory(w, x0, pool, sched, steps, precision, R=None, lam=None):
     R = len(pool) if R is None else R
 
     def batches(t, i):
         return [pool[wl.pool_index(w, t, i, j, R)] for j in range(int(sched[t, i]))]
 
     return orc.run(x0, w.K, steps, w.n, float(F32(w.lr)), float(F32(w.mu)), float(F32(w.wd)), batches,
-                   precision=precision)
+                   precision=precision, lam=None if lam is None else float(F32(lam)))
 
 
-def _trajectory_case(absgd, name, steps=None, P=None):
+def _trajectory_case(absgd, name, steps=None, P=None, lam=None):
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
     steps = w.steps if steps is None else steps
@@ -272,7 +354,7 @@ def _trajectory_case(absgd, name, steps=None, P=None):
     out = {}
     for overlap in (False, True):
         print(f"[case] trajectory {name} overlap={overlap}", flush=True)
-        run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size)
+        run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size, lam=lam)
         run.run(steps)
         out[overlap] = run.read_state() + (run.count_history, run.applied)
         run.close()
@@ -285,8 +367,8 @@ def _trajectory_case(absgd, name, steps=None, P=None):
     assert cs == co and aps == apo
     assert aps == [False] + [True] * (steps - 1)       # one-iteration delay: step 0 applies nothing
 
-    x32, v32, h32 = _oracle_trajectory(w, x0, pool, sched, steps, "f32")
-    x64, v64, h64 = _oracle_trajectory(w, x0, pool, sched, steps, "f64")
+    x32, v32, h32 = _oracle_trajectory(w, x0, pool, sched, steps, "f32", lam=lam)
+    x64, v64, h64 = _oracle_trajectory(w, x0, pool, sched, steps, "f64", lam=lam)
     assert cs == h32 == h64                            # sample counts: exact
     _assert_bitexact(xo, x32, f"{name} x vs fp32 oracle")
     _assert_bitexact(vo, v32, f"{name} v vs fp32 oracle")
@@ -336,6 +418,13 @@ def test_trajectory_paper_rule(absgd):
     _trajectory_case(absgd, "paper_static", steps=6, P=300_007)
 
 
+@pytest.mark.parametrize("name,kw", [("paper_static", dict(steps=6, P=300_007)), ("cfg1_small", {}),
+                                     ("tiny_tail_bf16", {}), ("ragged_odd_f32", {}), ("ragged_odd_bf16", {})])
+def test_trajectory_with_compensation(absgd, name, kw):
+    """Algorithm 1 complete: delayed update + weighted averaging + compensation, lambda = 0.5."""
+    _trajectory_case(absgd, name, lam=0.5, **kw)
+
+
 def test_trajectory_delay_invariant_on_gpu(absgd):
     """x after step t does not depend on step t's gradients."""
     from paper_2308_15164_amd.driver import DeviceRun
@@ -360,8 +449,10 @@ def test_trajectory_delay_invariant_on_gpu(absgd):
 # full BASELINE sizes in the benchmark's launch configuration, sampled outputs
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("name", ["cfg2_resnet18", "cfg3_resnet50_bf16", "cfg4_vgg16", "cfg5_gpt2_ragged_bf16"])
-def test_full_size_sampled(absgd, name):
+@pytest.mark.parametrize("name,lam", [("cfg2_resnet18", None), ("cfg3_resnet50_bf16", None), ("cfg4_vgg16", None),
+                                      ("cfg5_gpt2_ragged_bf16", None), ("cfg2_resnet18", 0.5),
+                                      ("cfg5_gpt2_ragged_bf16", 0.5)])
+def test_full_size_sampled(absgd, name, lam):
     """Every output element depends only on the same index of the inputs, so the
     oracle runs on a sample of indices gathered from the very same host arrays."""
     from paper_2308_15164_amd.driver import DeviceRun
@@ -372,7 +463,7 @@ def test_full_size_sampled(absgd, name):
     pool = wl.gradient_pool(w, pool=R)
     sched = wl.schedule(w)
     print(f"[case] full size {name}: device run, two streams", flush=True)
-    run = DeviceRun(w, x0, pool, sched, overlap=True)
+    run = DeviceRun(w, x0, pool, sched, overlap=True, lam=lam)
     run.run(w.steps)
     idx = wl.sample_indices(w.P, 200_000, w.seed)
     if w.tensor_sizes is not None:       # both sides of every tensor boundary
@@ -387,8 +478,8 @@ def test_full_size_sampled(absgd, name):
     print(f"[case] full size {name}: oracle on {idx.size} sampled elements", flush=True)
     x0s = np.ascontiguousarray(x0[idx])
     pools = [np.ascontiguousarray(g[idx]) for g in pool]
-    x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R)
-    x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R)
+    x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R, lam=lam)
+    x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R, lam=lam)
     assert counts == h32 == h64
     _assert_bitexact(gx, x32, f"{name} sampled x")
     _assert_bitexact(gv, v32, f"{name} sampled v")
