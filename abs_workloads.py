@@ -111,6 +111,14 @@ WORKLOADS = {w.name: w for w in [
              "fixed", ratio=(12, 6, 4, 3),
              notes="the paper's own setting: plain SGD, lr 0.01, iteration-time ratio "
                    "1:2:3:4 hence micro-batch counts 12:6:4:3"),
+    Workload("paper_dynamic", 11, 11_689_512, 4, "f32", 32, 0.05, 0.01, 0.01, 0.0, 0.0, 20,
+             "speed_jitter", ratio=(1, 1, 1, 1),
+             notes="the paper's dynamic-only cluster: equal workers, each iteration prolonged by "
+                   "U(0, 50 %); a worker fits rint(6 / (1 + u)) reference batches in the window"),
+    Workload("paper_static_dynamic", 12, 11_689_512, 4, "f32", 32, 0.05, 0.01, 0.01, 0.0, 0.0, 20,
+             "speed_jitter", ratio=(1, 2, 3, 4),
+             notes="the paper's third cluster: iteration-time ratio 1:2:3:4, each prolonged by "
+                   "U(0, 50 %); a worker fits max(1, rint(12 / (r (1 + u)))) reference batches"),
 ]}
 
 
@@ -126,6 +134,13 @@ def schedule(w: Workload, steps: Optional[int] = None) -> np.ndarray:
         m = rng.integers(1, 9, size=(T, w.K))
     elif w.schedule == "poisson4_plus1":
         m = rng.poisson(4.0, size=(T, w.K)) + 1
+    elif w.schedule == "speed_jitter":
+        # iteration time of worker k = r_k (1 + u), u ~ U(0, 0.5) per (step, worker); the number
+        # of reference batches that fit in a fixed window is inversely proportional to it
+        u = rng.uniform(0.0, 0.5, size=(T, w.K))
+        r = np.asarray(w.ratio, dtype=np.float64)
+        base = 6.0 * r.max() if r.max() == r.min() else 12.0
+        m = np.maximum(1, np.rint(base / (r * (1.0 + u))))
     elif w.schedule == "ratio_jitter":
         u = rng.uniform(0.5, 1.5, size=(T, w.K))
         m = np.maximum(1, np.rint(np.asarray(w.ratio, dtype=np.float64) * u))
