@@ -28,26 +28,39 @@ METRIC = "sync-update+accumulate GB/s and % of HBM peak; params/s per step"
 MEASURED_TRAFFIC = {
     # FETCH_SIZE x 2.000 = 81.88 MB, WRITE_SIZE x 1.000 = 46.75 MB per launch (average over
     # the 12 read-modify-write and 4 overwrite launches of a step)
-    ("cfg2_resnet18", "absk::accumulate_flat<false, *>"): 128.63e6,
+    ("cfg2_resnet18", "absk::accumulate_flat<false, *, 1>"): 128.63e6,
 }
 
 
-def bytes_per_param(w, m_row, compensated=False):
+MAX_BATCH = 8   # ABS_MAX_BATCH: gradients one accumulate launch folds in
+
+
+def bytes_per_param(w, m_row, compensated=False, batched=False):
     """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
     an accumulate reads one gradient element and reads+writes one fp32
     accumulator element (the first call of a step only writes it); the
     sync-update reads K accumulators and reads+writes x and v (and the previous
     iterate when the delayed gradient compensation is on)."""
     gb = 4 if w.grad_dtype == "f32" else 2
-    acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
+    if batched:
+        # a worker's m gradients go in ceil(m / MAX_BATCH) launches: every gradient is read
+        # once, the accumulator is written once per launch and read by all but the first
+        acc = sum(int(m) * gb + 8 * (-(-int(m) // MAX_BATCH)) - 4 for m in m_row)
+    else:
+        acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
     return acc, 4 * w.K + 16 + (8 if compensated else 0)
 
 
-def dominant_kernel(w):
-    """The accumulate kernel: it moves most of a step's bytes in every workload."""
+def accumulate_launches(m_row, batched):
+    return sum(-(-int(m) // MAX_BATCH) if batched else int(m) for m in m_row)
+
+
+def dominant_kernel(w, batched=False):
+    """The accumulate kernel: it moves most of a step's bytes in every workload.
+    Template arguments: bf16 gradients, streaming flavour, gradients per launch."""
     bf = "true" if w.grad_dtype == "bf16" else "false"
     kind = "ragged" if w.tensor_sizes is not None else "flat"
-    return f"absk::accumulate_{kind}<{bf}, *>"
+    return f"absk::accumulate_{kind}<{bf}, *, {'*' if batched else '1'}>"
 
 
 def time_steps(run, plans, t0, steps, torch):
@@ -67,22 +80,29 @@ def kernel_event_pass(run, plans, t0, steps, torch):
     launches keeps the events' own cost below 1 %).  The sync-update of the
     step runs concurrently on the other stream, as in the timed region."""
     ctx, n, gdt = run.ctx, run.w.n, run.gdt
-    pairs, launches = [], 0
+    pairs, launches = [], []
     torch.cuda.synchronize()
     for t in range(t0, t0 + steps):
         run.sync_update()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(run.s_acc)
-        for k, g in plans[t]:
-            ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+        if run.batched:
+            per_worker = {}
+            for k, g in plans[t]:
+                per_worker.setdefault(k, []).append(g)
+            for k, gs in per_worker.items():
+                ctx.abs_accumulate_batch(k, gs, [n] * len(gs), grad_dtype=gdt)
+            launches.append(sum(-(-len(gs) // MAX_BATCH) for gs in per_worker.values()))
+        else:
+            for k, g in plans[t]:
+                ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+            launches.append(len(plans[t]))
         e1.record(run.s_acc)
         pairs.append((e0, e1))
-        launches += len(plans[t])
         ctx.abs_swap_buffers()
     torch.cuda.synchronize()
-    total_ms = sum(a.elapsed_time(b) for a, b in pairs)
-    return total_ms / launches, launches
+    return [a.elapsed_time(b) for a, b in pairs], launches
 
 
 def probe_ceilings(torch, nbytes=1 << 30, reps=20):
@@ -189,6 +209,9 @@ def main():
     ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
                     help="also apply the delayed gradient compensation with this coefficient "
                          "(abs_sync_update_dc; +8 B/param); default: off, the BASELINE metric's path")
+    ap.add_argument("--batched", action="store_true",
+                    help="one abs_accumulate_batch call per worker and step instead of one abs_accumulate "
+                         "per micro-batch (fewer bytes: the accumulator is read and written once)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB copy kernel (profiler counter calibration)")
     args = ap.parse_args()
@@ -230,7 +253,7 @@ def main():
             plans_wanted.append((f"{n} accumulate streams (workers spread) | sync-update", True, n))
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
-    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation)
+    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched)
     comp = args.compensation is not None
     calls = [run.plan_step(t) for t in range(total)]
     timings = {}
@@ -246,22 +269,28 @@ def main():
     # Dominant kernel (accumulate) alone on the GPU: the one-stream plan, same steps.
     run.configure_streams(False, 1)
     time_steps(run, calls, 0, max(W, 1), torch)
-    kern_ms, launches = kernel_event_pass(run, calls, W, K_steps, torch)
+    bracket_ms, step_launches = kernel_event_pass(run, calls, W, K_steps, torch)
     run.close()
     del run, calls
     torch.cuda.empty_cache()
 
     step_bytes = 0
     for t in range(W, total):
-        a, s_ = bytes_per_param(w, sched[t], comp)
+        a, s_ = bytes_per_param(w, sched[t], comp, args.batched)
         step_bytes += (a + s_) * w.P
     gbs = step_bytes / dt / 1e9
     # Algorithmic bytes per accumulate launch = the step's accumulate bytes
     # (sum_k [m_k (g_b + 8) - 4] per parameter) averaged over its sum_k m_k launches.
-    acc_bytes = sum(bytes_per_param(w, sched[t])[0] for t in range(W, total)) * w.P
-    kern_bytes = acc_bytes / launches
+    # A step whose bracket is far off the others (a hiccup of the box) is left out: steps are
+    # ranked by time per launch and the slowest twentieth dropped.
+    step_acc_bytes = [bytes_per_param(w, sched[t], comp, args.batched)[0] * w.P for t in range(W, total)]
+    order = sorted(range(K_steps), key=lambda i: bracket_ms[i] / step_launches[i])
+    keep = order[:max(1, K_steps - K_steps // 20)]
+    launches = sum(step_launches[i] for i in keep)
+    kern_ms = sum(bracket_ms[i] for i in keep) / launches
+    kern_bytes = sum(step_acc_bytes[i] for i in keep) / launches
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
-    kname = dominant_kernel(w)
+    kname = dominant_kernel(w, args.batched)
     traffic = MEASURED_TRAFFIC.get((w.name, kname))
 
     out = {
@@ -282,7 +311,7 @@ def main():
             "samples_per_microbatch": w.n, "m_k": w.schedule + (str(list(w.ratio)) if w.ratio else ""),
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
             "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
-            "compensation_lambda": args.compensation,
+            "compensation_lambda": args.compensation, "batched_accumulate": args.batched,
             "streams": best + ", double-buffered",
             "algorithmic_bytes_per_step": step_bytes // K_steps,
         },

@@ -37,7 +37,8 @@
 extern "C" {
 #endif
 
-#define ABS_MAX_K 64 /* most workers one sync-update may combine */
+#define ABS_MAX_K 64    /* most workers one sync-update may combine */
+#define ABS_MAX_BATCH 8 /* most gradients one accumulate launch folds in */
 
 enum { ABS_OK = 0, ABS_EMPTY = 1, ABS_EINVAL = -1, ABS_EHIP = -2 };
 
@@ -91,6 +92,19 @@ int abs_set_cache_policy(int accumulate_mode, int update_mode);
  * ---------------------------------------------------------------------- */
 int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
                    int64_t n_samples, int64_t *count, void *stream);
+
+/* (1') Batched accumulation: the J micro-batch gradients a worker has ready are
+ *     folded into its accumulator in ONE pass, in order j = 0..J-1, with exactly
+ *     the roundings of J successive abs_accumulate calls (same bits), but the
+ *     accumulator is read and written once: J*g_b + 8 bytes per parameter
+ *     instead of J*(g_b + 8).  Launches fold at most ABS_MAX_BATCH gradients;
+ *     a larger J is split into several launches.
+ *
+ *   grads      HOST array of J DEVICE pointers, each P elements of grad_dtype
+ *   n_samples  HOST array of J sample counts (each > 0);  *count += their sum
+ *   Errors as abs_accumulate; J < 1 is EINVAL. */
+int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dtype, int J,
+                         int64_t P, const int64_t *n_samples, int64_t *count, void *stream);
 
 /* ------------------------------------------------------------------------
  * (2)+(3) Weighted combination of the K delayed accumulators and the delayed
@@ -184,6 +198,12 @@ int abs_accumulate_mt(abs_layout *layout, const abs_tensorset *acc,
                       const abs_tensorset *grad, int64_t n_samples, int64_t *count,
                       void *stream);
 
+/* abs_accumulate_batch over every tensor of the layout.  grads: HOST array of J
+ * sets of one element type. */
+int abs_accumulate_batch_mt(abs_layout *layout, const abs_tensorset *acc,
+                            const abs_tensorset *const *grads, int J, const int64_t *n_samples,
+                            int64_t *count, void *stream);
+
 /* Same arithmetic as abs_sync_update over every tensor of the layout.
  * acc: HOST array of K sets; counts: HOST array of K int64. */
 int abs_sync_update_mt(abs_layout *layout, const abs_tensorset *params,
@@ -231,6 +251,11 @@ int abs_ctx_set_accumulate_streams(abs_ctx *ctx, void *const *streams, int n);
 int abs_ctx_accumulate(abs_ctx *ctx, int k, const void *grad, abs_dtype grad_dtype,
                        int64_t n_samples);
 int abs_ctx_accumulate_mt(abs_ctx *ctx, int k, const abs_tensorset *grad, int64_t n_samples);
+/* Batched forms (abs_accumulate_batch) into worker k's CURRENT accumulator. */
+int abs_ctx_accumulate_batch(abs_ctx *ctx, int k, const void *const *grads, abs_dtype grad_dtype,
+                             int J, const int64_t *n_samples);
+int abs_ctx_accumulate_batch_mt(abs_ctx *ctx, int k, const abs_tensorset *const *grads, int J,
+                                const int64_t *n_samples);
 
 /* abs_sync_update from the PREVIOUS generation, on stream_upd.  ABS_EMPTY in
  * the first iteration. */

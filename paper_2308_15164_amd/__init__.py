@@ -30,6 +30,7 @@ SYMBOLS = {
     "abs_set_launch_tuning": (_int, [_int, _int]),
     "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
+    "abs_accumulate_batch": (_int, [_vp, _pvp, _int, _int, _i64, _pi64, _pi64, _vp]),
     "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
     "abs_sync_update_dc": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _vp]),
     "abs_layout_create": (_int, [_pvp, _int, _pi64]),
@@ -42,6 +43,7 @@ SYMBOLS = {
     "abs_tensorset_create": (_int, [_pvp, _vp, _pvp, _int]),
     "abs_tensorset_destroy": (_int, [_vp]),
     "abs_accumulate_mt": (_int, [_vp, _vp, _vp, _i64, _pi64, _vp]),
+    "abs_accumulate_batch_mt": (_int, [_vp, _vp, _pvp, _int, _pi64, _pi64, _vp]),
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
     "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
@@ -50,6 +52,8 @@ SYMBOLS = {
     "abs_ctx_set_accumulate_streams": (_int, [_vp, _pvp, _int]),
     "abs_ctx_accumulate": (_int, [_vp, _int, _vp, _int, _i64]),
     "abs_ctx_accumulate_mt": (_int, [_vp, _int, _vp, _i64]),
+    "abs_ctx_accumulate_batch": (_int, [_vp, _int, _pvp, _int, _int, _pi64]),
+    "abs_ctx_accumulate_batch_mt": (_int, [_vp, _int, _pvp, _int, _pi64]),
     "abs_ctx_sync_update": (_int, [_vp, _vp, _vp, _f, _f, _f]),
     "abs_ctx_sync_update_mt": (_int, [_vp, _vp, _vp, _f, _f, _f]),
     "abs_ctx_sync_update_dc": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
@@ -181,6 +185,15 @@ def abs_accumulate(acc, grad, n_samples, count, stream=None, P=None, grad_dtype=
     return _check("abs_accumulate", rc)
 
 
+def abs_accumulate_batch(acc, grads, n_samples, count, stream=None, P=None, grad_dtype=None):
+    """Fold the J gradients `grads` (sample counts `n_samples`) into acc in one pass."""
+    n = acc.numel() if P is None else int(P)
+    rc = lib().abs_accumulate_batch(_dev_ptr(acc), _ptr_array([_dev_ptr(g) for g in grads]),
+                                    _dtype_of(grads[0], grad_dtype), len(grads), n, _i64_array(n_samples),
+                                    ctypes.byref(count._c), _stream_handle(stream))
+    return _check("abs_accumulate_batch", rc)
+
+
 def abs_sync_update(params, momentum, acc, counts, lr, mu, wd, stream=None, P=None):
     """Fused weighted combine of acc[K] + delayed momentum-SGD update.
     Returns False when the total count is zero (nothing applied)."""
@@ -278,6 +291,13 @@ def abs_accumulate_mt(layout, acc, grad, n_samples, count, stream=None):
     return _check("abs_accumulate_mt", rc)
 
 
+def abs_accumulate_batch_mt(layout, acc, grads, n_samples, count, stream=None):
+    rc = lib().abs_accumulate_batch_mt(layout.handle, acc.handle, _ptr_array([g.handle.value for g in grads]),
+                                       len(grads), _i64_array(n_samples), ctypes.byref(count._c),
+                                       _stream_handle(stream))
+    return _check("abs_accumulate_batch_mt", rc)
+
+
 def abs_sync_update_mt(layout, params, momentum, acc, counts, lr, mu, wd, stream=None):
     sets = _ptr_array([a.handle.value for a in acc])
     rc = lib().abs_sync_update_mt(layout.handle, params.handle, momentum.handle, sets,
@@ -332,6 +352,16 @@ class Context:
         rc = lib().abs_ctx_accumulate_mt(self.handle, int(k), grad.handle, int(n_samples))
         return _check("abs_ctx_accumulate_mt", rc)
 
+    def abs_accumulate_batch(self, k, grads, n_samples, grad_dtype=None):
+        if self.layout is None:
+            rc = lib().abs_ctx_accumulate_batch(self.handle, int(k), _ptr_array([_dev_ptr(g) for g in grads]),
+                                                _dtype_of(grads[0], grad_dtype), len(grads),
+                                                _i64_array(n_samples))
+            return _check("abs_ctx_accumulate_batch", rc)
+        rc = lib().abs_ctx_accumulate_batch_mt(self.handle, int(k), _ptr_array([g.handle.value for g in grads]),
+                                               len(grads), _i64_array(n_samples))
+        return _check("abs_ctx_accumulate_batch_mt", rc)
+
     def abs_sync_update(self, params, momentum, lr, mu, wd):
         if self.layout is None:
             rc = lib().abs_ctx_sync_update(self.handle, _dev_ptr(params), _dev_ptr(momentum),
@@ -377,7 +407,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_sync_update", "abs_sync_update_dc", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

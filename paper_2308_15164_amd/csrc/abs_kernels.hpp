@@ -115,44 +115,92 @@ __device__ __forceinline__ float load_grad_one(const typename GradT<BF16>::elem 
     else return *p;
 }
 
-// One workgroup, one tile: acc[0..len) (+)= nf * grad[0..len).
+// J micro-batch gradients of one worker, applied in order in one pass:
+//   r = first ? n_0*g_0 : fma(n_0, g_0, acc);  r = fma(n_j, g_j, r) for j = 1..J-1;  acc = r.
+// Every intermediate is rounded exactly as J separate launches would round it,
+// so batching changes the traffic ((J*g_b + 8) instead of J*(g_b + 8) bytes per
+// parameter), never the bits.
+template <bool BF16, int J>
+struct GradArgs {
+    const typename GradT<BF16>::elem *g[J];
+    float n[J];
+};
+
+// rows per group: keep about 8-10 loads of 128 bits (64 for bf16) in flight per lane
+template <int J>
+constexpr int acc_unroll()
+{
+    return J <= 1 ? ABS_ACC_UNROLL : (J == 2 ? 3 : (J <= 4 ? 2 : 1));
+}
+
+template <int J>
+__device__ __forceinline__ float acc_chain(bool first, const float (&n)[J], const float (&g)[J], float a)
+{
+    float r = acc_one(first, n[0], g[0], a);
+#pragma unroll
+    for (int j = 1; j < J; ++j) r = __builtin_fmaf(n[j], g[j], r);
+    return r;
+}
+
+template <int J>
+__device__ __forceinline__ f32x4 acc_chain_vec(bool first, const float (&n)[J], const f32x4 (&g)[J], f32x4 a)
+{
+    f32x4 r = acc_vec(first, n[0], g[0], a);
+#pragma unroll
+    for (int j = 1; j < J; ++j) {
+        r.x = __builtin_fmaf(n[j], g[j].x, r.x); r.y = __builtin_fmaf(n[j], g[j].y, r.y);
+        r.z = __builtin_fmaf(n[j], g[j].z, r.z); r.w = __builtin_fmaf(n[j], g[j].w, r.w);
+    }
+    return r;
+}
+
+// One workgroup, one tile: acc[0..len) (+)= sum_j n_j * grad_j[0..len), in order.
 // `first` is uniform over the launch.  NTA: accumulator traffic is streaming.
-template <bool BF16, bool NTA>
-__device__ __forceinline__ void accumulate_tile(float *__restrict__ acc,
-                                                const typename GradT<BF16>::elem *__restrict__ grad,
-                                                int len, float nf, bool first, bool vec_ok)
+template <bool BF16, bool NTA, int J>
+__device__ __forceinline__ void accumulate_tile(float *__restrict__ acc, const GradArgs<BF16, J> &G,
+                                                int len, bool first, bool vec_ok)
 {
     typedef typename GradT<BF16>::vec gvec;
-    constexpr int U = ABS_ACC_UNROLL;
+    constexpr int U = acc_unroll<J>();
     const int tid = threadIdx.x;
     if (!vec_ok) {
-        for (int i = tid; i < len; i += BLOCK)
-            acc[i] = acc_one(first, nf, load_grad_one<BF16>(grad + i), first ? 0.f : acc[i]);
+        for (int i = tid; i < len; i += BLOCK) {
+            float g[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) g[j] = load_grad_one<BF16>(G.g[j] + i);
+            acc[i] = acc_chain<J>(first, G.n, g, first ? 0.f : acc[i]);
+        }
         return;
     }
     f32x4 *av = reinterpret_cast<f32x4 *>(acc);
-    const gvec *gv = reinterpret_cast<const gvec *>(grad);
     const int nvec = len / VEC;
     int g0 = 0;
     // whole groups of U rows: no bounds checks, every load issued before the first store
     for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) {
-        f32x4 g[U], a[U] = {};
+        f32x4 g[U][J], a[U] = {};
 #pragma unroll
-        for (int u = 0; u < U; ++u) g[u] = load_grad_vec<BF16>(gv + g0 + u * BLOCK + tid);
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+                g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + g0 + u * BLOCK + tid);
         if (!first) {
 #pragma unroll
             for (int u = 0; u < U; ++u) a[u] = ld<NTA>(av + g0 + u * BLOCK + tid);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) st<NTA>(av + g0 + u * BLOCK + tid, acc_vec(first, nf, g[u], a[u]));
+        for (int u = 0; u < U; ++u)
+            st<NTA>(av + g0 + u * BLOCK + tid, acc_chain_vec<J>(first, G.n, g[u], a[u]));
     }
     // last, partial group
     if (g0 < nvec) {
-        f32x4 g[U] = {}, a[U] = {};
+        f32x4 g[U][J] = {}, a[U] = {};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = g0 + u * BLOCK + tid;
-            if (i < nvec) g[u] = load_grad_vec<BF16>(gv + i);
+            if (i < nvec) {
+#pragma unroll
+                for (int j = 0; j < J; ++j) g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + i);
+            }
         }
         if (!first) {
 #pragma unroll
@@ -164,11 +212,16 @@ __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = g0 + u * BLOCK + tid;
-            if (i < nvec) st<NTA>(av + i, acc_vec(first, nf, g[u], a[u]));
+            if (i < nvec) st<NTA>(av + i, acc_chain_vec<J>(first, G.n, g[u], a[u]));
         }
     }
     const int i = nvec * VEC + tid;          // at most VEC-1 trailing elements
-    if (i < len) acc[i] = acc_one(first, nf, load_grad_one<BF16>(grad + i), first ? 0.f : acc[i]);
+    if (i < len) {
+        float g[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j) g[j] = load_grad_one<BF16>(G.g[j] + i);
+        acc[i] = acc_chain<J>(first, G.n, g, first ? 0.f : acc[i]);
+    }
 }
 
 // --------------------------------------------------------------- sync-update
@@ -370,16 +423,15 @@ __device__ __forceinline__ int tile_len(int64_t total, int64_t base, int tile)
 
 // Flat vector: workgroup b owns elements [b*tile, min(P, (b+1)*tile)); tile is a
 // multiple of ROW chosen by the host.
-template <bool BF16, bool NTA>
+template <bool BF16, bool NTA, int J>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_flat(float *__restrict__ acc,
-                                                            const void *__restrict__ grad,
-                                                            int64_t P, int tile, float nf, int first,
-                                                            int vec_ok)
+                                                            GradArgs<BF16, J> G, int64_t P, int tile,
+                                                            int first, int vec_ok)
 {
-    typedef typename GradT<BF16>::elem gelem;
     const int64_t base = (int64_t)blockIdx.x * tile;
-    accumulate_tile<BF16, NTA>(acc + base, static_cast<const gelem *>(grad) + base,
-                               tile_len(P, base, tile), nf, first != 0, vec_ok != 0);
+#pragma unroll
+    for (int j = 0; j < J; ++j) G.g[j] += base;
+    accumulate_tile<BF16, NTA, J>(acc + base, G, tile_len(P, base, tile), first != 0, vec_ok != 0);
 }
 
 template <int K, bool NTX, bool DC>
@@ -420,20 +472,32 @@ __global__ __launch_bounds__(ABS_BLOCK) void copy_flat(float *__restrict__ dst,
 // these reads are uniform across the workgroup (scalar loads).
 struct Chunk { int32_t tensor; int32_t index; };
 
-template <bool BF16, bool NTA>
+// J gradient pointer tables (one per micro-batch) and their sample counts.
+template <int J>
+struct GradTabs {
+    const void *const *t[J];
+    float n[J];
+};
+
+template <bool BF16, bool NTA, int J>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__restrict__ chunks,
                                                               const int64_t *__restrict__ sizes,
                                                               float *const *__restrict__ acc_tab,
-                                                              const void *const *__restrict__ grad_tab,
-                                                              int tile, float nf, int first)
+                                                              GradTabs<J> tabs, int tile, int first)
 {
     typedef typename GradT<BF16>::elem gelem;
     const Chunk c = chunks[blockIdx.x];
     const int64_t base = (int64_t)c.index * tile;
     float *acc = acc_tab[c.tensor] + base;
-    const gelem *grad = static_cast<const gelem *>(grad_tab[c.tensor]) + base;
-    const bool vec_ok = aligned16(acc) && (BF16 ? aligned8(grad) : aligned16(grad));
-    accumulate_tile<BF16, NTA>(acc, grad, tile_len(sizes[c.tensor], base, tile), nf, first != 0, vec_ok);
+    bool vec_ok = aligned16(acc);
+    GradArgs<BF16, J> G;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        G.g[j] = static_cast<const gelem *>(tabs.t[j][c.tensor]) + base;
+        G.n[j] = tabs.n[j];
+        vec_ok = vec_ok && (BF16 ? aligned8(G.g[j]) : aligned16(G.g[j]));
+    }
+    accumulate_tile<BF16, NTA, J>(acc, G, tile_len(sizes[c.tensor], base, tile), first != 0, vec_ok);
 }
 
 template <int K> struct TabPtrs { const float *const *t[K]; };

@@ -132,18 +132,39 @@ inline bool stream_upd(int64_t P, int vectors = 2) { return g_policy_upd < 0 ? 4
 
 // ------------------------------------------------------------ flat launches
 
-int launch_accumulate_flat(float *acc, const void *grad, abs_dtype dt, int64_t P, float nf,
-                           int first, int vec_ok, hipStream_t s)
+template <bool BF16, int J>
+void launch_accumulate_flat_j(float *acc, const void *const *grads, const float *nf, int64_t P, int tile,
+                              unsigned nblocks, int first, int vec_ok, bool nta, hipStream_t s)
+{
+    GradArgs<BF16, J> G;
+    for (int j = 0; j < J; ++j) {
+        G.g[j] = static_cast<const typename GradT<BF16>::elem *>(grads[j]);
+        G.n[j] = nf[j];
+    }
+    const dim3 grid(nblocks), block(BLOCK);
+    if (nta) hipLaunchKernelGGL((accumulate_flat<BF16, true, J>), grid, block, 0, s, acc, G, P, tile, first, vec_ok);
+    else hipLaunchKernelGGL((accumulate_flat<BF16, false, J>), grid, block, 0, s, acc, G, P, tile, first, vec_ok);
+}
+
+// One launch: J <= ABS_MAX_BATCH gradients into one accumulator.
+int launch_accumulate_flat(float *acc, const void *const *grads, const float *nf, int J, abs_dtype dt,
+                           int64_t P, int first, int vec_ok, hipStream_t s)
 {
     const int64_t tile64 = choose_tile(rows_of(P), acc_resident());
     if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
     const int tile = (int)tile64;
-    const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
+    const unsigned nb = (unsigned)tiles_for(P, tile64);
     const bool bf = dt == ABS_BF16, nta = stream_acc(P);
-    if (bf && nta) hipLaunchKernelGGL((accumulate_flat<true, true>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
-    else if (bf) hipLaunchKernelGGL((accumulate_flat<true, false>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
-    else if (nta) hipLaunchKernelGGL((accumulate_flat<false, true>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
-    else hipLaunchKernelGGL((accumulate_flat<false, false>), grid, block, 0, s, acc, grad, P, tile, nf, first, vec_ok);
+    switch (J) {
+#define ABS_CASE(N)                                                                                     \
+    case N:                                                                                             \
+        if (bf) launch_accumulate_flat_j<true, N>(acc, grads, nf, P, tile, nb, first, vec_ok, nta, s);  \
+        else launch_accumulate_flat_j<false, N>(acc, grads, nf, P, tile, nb, first, vec_ok, nta, s);    \
+        break;
+        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
+#undef ABS_CASE
+    default: return ABS_EINVAL;
+    }
     return ABS_OK;
 }
 
@@ -298,6 +319,22 @@ void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
     }
 }
 
+template <int J>
+void launch_accumulate_ragged_j(const abs_layout *L, float *const *at, const void *const *const *gt,
+                                       const float *nf, int first, bool bf, bool nta, hipStream_t s)
+{
+    GradTabs<J> T;
+    for (int j = 0; j < J; ++j) {
+        T.t[j] = gt[j];
+        T.n[j] = nf[j];
+    }
+    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
+    if (bf && nta) hipLaunchKernelGGL((accumulate_ragged<true, true, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
+    else if (bf) hipLaunchKernelGGL((accumulate_ragged<true, false, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
+    else if (nta) hipLaunchKernelGGL((accumulate_ragged<false, true, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
+    else hipLaunchKernelGGL((accumulate_ragged<false, false, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
+}
+
 bool set_ok(const abs_tensorset *s, const abs_layout *L) { return s && s->layout == L; }
 
 }  // namespace
@@ -342,26 +379,54 @@ int abs_set_cache_policy(int accumulate_mode, int update_mode)
 
 // ------------------------------------------------------------------ flat
 
+int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dtype, int J, int64_t P,
+                         const int64_t *n_samples, int64_t *count, void *stream)
+{
+    if (!count || !grads || !n_samples || J < 1 || P < 0 || *count < 0) return ABS_EINVAL;
+    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
+    int64_t total = *count;
+    for (int j = 0; j < J; ++j) {
+        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
+        total += n_samples[j];
+    }
+    if (P > 0) {
+        if (!acc || !aligned_to(acc, 4)) return ABS_EINVAL;
+        const uintptr_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
+        int vec_ok = aligned_to(acc, 16);
+        for (int j = 0; j < J; ++j) {
+            if (!grads[j] || !aligned_to(grads[j], gsz)) return ABS_EINVAL;
+            vec_ok = vec_ok && aligned_to(grads[j], grad_dtype == ABS_BF16 ? 8 : 16);
+        }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int first = *count == 0 ? 1 : 0;
+        for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
+            const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
+            float nf[ABS_MAX_BATCH];
+            for (int j = 0; j < jn; ++j) nf[j] = (float)n_samples[j0 + j];
+            int rc = launch_accumulate_flat(acc, grads + j0, nf, jn, grad_dtype, P, first, vec_ok, s);
+            if (rc != ABS_OK) return rc;
+            rc = launch_status();
+            if (rc != ABS_OK) return rc;
+            first = 0;
+        }
+    }
+    *count = total;
+    return ABS_OK;
+}
+
 int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
                    int64_t n_samples, int64_t *count, void *stream)
 {
-    if (!count || P < 0 || n_samples <= 0 || *count < 0) return ABS_EINVAL;
-    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
-    if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
-    if (P > 0) {
-        if (!acc || !grad) return ABS_EINVAL;
-        const uintptr_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
-        if (!aligned_to(acc, 4) || !aligned_to(grad, gsz)) return ABS_EINVAL;
-        const int vec_ok = aligned_to(acc, 16) && aligned_to(grad, grad_dtype == ABS_BF16 ? 8 : 16);
-        const float nf = (float)n_samples;
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        int rc = launch_accumulate_flat(acc, grad, grad_dtype, P, nf, *count == 0 ? 1 : 0, vec_ok, s);
-        if (rc != ABS_OK) return rc;
-        rc = launch_status();
-        if (rc != ABS_OK) return rc;
+    if (P > 0 && !grad) return ABS_EINVAL;
+    const void *grads[1] = {grad ? grad : acc};   // P == 0 launches nothing; any non-null stand-in will do
+    if (P == 0) {
+        if (!count || n_samples <= 0 || *count < 0) return ABS_EINVAL;
+        if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
+        if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
+        *count += n_samples;
+        return ABS_OK;
     }
-    *count += n_samples;
-    return ABS_OK;
+    return abs_accumulate_batch(acc, grads, grad_dtype, 1, P, &n_samples, count, stream);
 }
 
 // params_prev == nullptr: no compensation.
@@ -508,31 +573,50 @@ int abs_tensorset_destroy(abs_tensorset *S)
     return ABS_OK;
 }
 
-int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *grad,
-                      int64_t n_samples, int64_t *count, void *stream)
+int abs_accumulate_batch_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *const *grads,
+                            int J, const int64_t *n_samples, int64_t *count, void *stream)
 {
-    if (!L || !set_ok(acc, L) || !set_ok(grad, L) || acc->elem != ABS_F32) return ABS_EINVAL;
-    if (!count || n_samples <= 0 || *count < 0) return ABS_EINVAL;
-    if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
+    if (!L || !set_ok(acc, L) || acc->elem != ABS_F32 || !grads || !n_samples || J < 1) return ABS_EINVAL;
+    if (!count || *count < 0) return ABS_EINVAL;
+    int64_t total = *count;
+    for (int j = 0; j < J; ++j) {
+        if (!set_ok(grads[j], L) || grads[j]->elem != grads[0]->elem) return ABS_EINVAL;
+        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
+        total += n_samples[j];
+    }
     if (!L->chunks.empty()) {
         int rc = layout_to_device(L);
         if (rc != ABS_OK) return rc;
-        const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-        const float nf = (float)n_samples;
         hipStream_t s = static_cast<hipStream_t>(stream);
         float *const *at = reinterpret_cast<float *const *>(acc->d_tab);
-        const void *const *gt = reinterpret_cast<const void *const *>(grad->d_tab);
-        const int first = *count == 0 ? 1 : 0;
-        const bool bf = grad->elem == ABS_BF16, nta = stream_acc(L->total);
-        if (bf && nta) hipLaunchKernelGGL((accumulate_ragged<true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
-        else if (bf) hipLaunchKernelGGL((accumulate_ragged<true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
-        else if (nta) hipLaunchKernelGGL((accumulate_ragged<false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
-        else hipLaunchKernelGGL((accumulate_ragged<false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, gt, L->tile, nf, first);
-        rc = launch_status();
-        if (rc != ABS_OK) return rc;
+        const bool bf = grads[0]->elem == ABS_BF16, nta = stream_acc(L->total);
+        int first = *count == 0 ? 1 : 0;
+        for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
+            const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
+            float nf[ABS_MAX_BATCH];
+            const void *const *gt[ABS_MAX_BATCH];
+            for (int j = 0; j < jn; ++j) {
+                nf[j] = (float)n_samples[j0 + j];
+                gt[j] = reinterpret_cast<const void *const *>(grads[j0 + j]->d_tab);
+            }
+            switch (jn) {
+#define ABS_CASE(N) case N: launch_accumulate_ragged_j<N>(L, at, gt, nf, first, bf, nta, s); break;
+                ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
+#undef ABS_CASE
+            }
+            rc = launch_status();
+            if (rc != ABS_OK) return rc;
+            first = 0;
+        }
     }
-    *count += n_samples;
+    *count = total;
     return ABS_OK;
+}
+
+int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *grad,
+                      int64_t n_samples, int64_t *count, void *stream)
+{
+    return abs_accumulate_batch_mt(L, acc, &grad, 1, &n_samples, count, stream);
 }
 
 static int sync_update_mt_impl(abs_layout *L, const abs_tensorset *params, const abs_tensorset *prev,
@@ -671,6 +755,22 @@ int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype
     if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
     return abs_accumulate(C->acc[C->cur][(size_t)k], grad, grad_dtype, C->P, n_samples,
                           &C->counts[C->cur][(size_t)k], C->stream_of(k));
+}
+
+int abs_ctx_accumulate_batch(abs_ctx *C, int k, const void *const *grads, abs_dtype grad_dtype, int J,
+                             const int64_t *n_samples)
+{
+    if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    return abs_accumulate_batch(C->acc[C->cur][(size_t)k], grads, grad_dtype, J, C->P, n_samples,
+                                &C->counts[C->cur][(size_t)k], C->stream_of(k));
+}
+
+int abs_ctx_accumulate_batch_mt(abs_ctx *C, int k, const abs_tensorset *const *grads, int J,
+                                const int64_t *n_samples)
+{
+    if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    return abs_accumulate_batch_mt(C->layout, C->set[C->cur][(size_t)k], grads, J, n_samples,
+                                   &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
 
 int abs_ctx_set_accumulate_streams(abs_ctx *C, void *const *streams, int n)

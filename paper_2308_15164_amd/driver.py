@@ -25,10 +25,13 @@ class DeviceRun:
 
     overlap=True : accumulation and sync-update on different streams;
     overlap=False: both on one stream, in program order;
-    acc_streams=n: the K workers' accumulations spread over n streams.
+    acc_streams=n: the K workers' accumulations spread over n streams;
+    lam          : coefficient of the delayed gradient compensation (None: off);
+    batched=True : a worker's m_k gradients of a step go in one abs_accumulate_batch
+                   call (same bits, the accumulator is read and written once).
     """
 
-    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None):
+    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
@@ -36,6 +39,7 @@ class DeviceRun:
         self.gdt = ABS_BF16 if w.grad_dtype == "bf16" else ABS_F32
         self.ragged = w.tensor_sizes is not None
         self.lam = None if lam is None else float(lam)   # delayed gradient compensation coefficient
+        self.batched = bool(batched)                     # one accumulate launch per worker and step
         self._streams = [torch.cuda.Stream(device=torch.device("cuda:0")) for _ in range(9)]
         self.ctx = None
         if not self.ragged:
@@ -127,8 +131,16 @@ class DeviceRun:
         Step 2 (accumulation) on the current one, then the swap."""
         ctx, n, gdt = self.ctx, self.w.n, self.gdt
         applied = self.sync_update()
-        for k, g in (self.plan_step(t) if calls is None else calls):
-            ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+        calls = self.plan_step(t) if calls is None else calls
+        if not self.batched:
+            for k, g in calls:
+                ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
+        else:
+            per_worker = {}
+            for k, g in calls:
+                per_worker.setdefault(k, []).append(g)
+            for k, gs in per_worker.items():
+                ctx.abs_accumulate_batch(k, gs, [n] * len(gs), grad_dtype=gdt)
         ctx.abs_swap_buffers()
         return applied
 

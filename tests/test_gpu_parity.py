@@ -160,6 +160,74 @@ def test_accumulate_zero_length_and_large_count(absgd):
 
 
 # ---------------------------------------------------------------------------
+# abs_accumulate_batch: J gradients in one pass == J calls, bit for bit
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("J", [1, 2, 3, 4, 5, 6, 7, 8, 9, 19])
+def test_accumulate_batch_equals_sequential(absgd, dtype, J):
+    print(f"[case] accumulate_batch dtype={dtype} J={J}", flush=True)
+    P = 5 * 4096 + 1031
+    rng = np.random.default_rng(1000 + J)
+    grads = [_grad(rng, P, dtype) for _ in range(J)]
+    ns = [int(v) for v in rng.integers(1, 200, size=J)]
+    g_d = [_up(g) for g in grads]
+    for start_count in (0, 64):                        # batch that starts an accumulator / continues one
+        base = (rng.standard_normal(P)).astype(F32)
+        acc_b = _up(base) if start_count else torch.full((P,), float("nan"), device="cuda")
+        acc_s = acc_b.clone()
+        cb, cs = absgd.Count(start_count), absgd.Count(start_count)
+        absgd.abs_accumulate_batch(acc_b, g_d, ns, cb)
+        for g, n in zip(g_d, ns):
+            absgd.abs_accumulate(acc_s, g, n, cs)
+        G32 = base.copy() if start_count else np.zeros(P, dtype=F32)
+        G64 = G32.astype(np.float64)
+        M = start_count
+        for g, n in zip(grads, ns):
+            orc.accumulate32(G32, g, n, first=(M == 0))
+            orc.accumulate(G64, g, n)
+            M += n
+        assert cb.value == cs.value == M
+        got = acc_b.cpu().numpy()
+        _assert_bitexact(got, acc_s.cpu().numpy(), "batch vs sequential launches")
+        _assert_bitexact(got, G32, "batch vs fp32 oracle")
+        assert np.max(np.abs(got - G64)) <= RTOL * np.max(np.abs(G64))
+
+
+@pytest.mark.parametrize("tuned", [(1, 0), (1, 3)], indirect=True)
+@pytest.mark.parametrize("J", [2, 4, 8])
+def test_accumulate_batch_multi_row_and_unaligned(absgd, tuned, J):
+    print(f"[case] accumulate_batch multi-row J={J} tuning={tuned}", flush=True)
+    P = 1_048_576 + 13
+    rng = np.random.default_rng(1100 + J)
+    for shift in (0, 1):
+        grads = [_grad(rng, P, "bf16" if J == 4 else "f32") for _ in range(J)]
+        def up(a):
+            pad = np.zeros(P + 8, dtype=a.dtype)
+            pad[shift:shift + P] = a
+            return _up(pad)[shift:shift + P]
+        acc = torch.full((P + 8,), float("nan"), device="cuda")[shift:shift + P]
+        cnt = absgd.Count(0)
+        absgd.abs_accumulate_batch(acc, [up(g) for g in grads], [32] * J, cnt)
+        G32 = np.zeros(P, dtype=F32)
+        for j, g in enumerate(grads):
+            orc.accumulate32(G32, g, 32, first=(j == 0))
+        _assert_bitexact(acc.cpu().numpy(), G32, f"batch J={J} shift={shift}")
+
+
+def test_accumulate_batch_rejects_bad_arguments(absgd):
+    acc = torch.zeros(16, device="cuda")
+    g = torch.zeros(16, device="cuda")
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_batch(acc, [g, g], [32, 0], absgd.Count(0))       # a zero sample count
+    import ctypes
+    c = ctypes.c_int64(0)
+    rc = absgd.lib().abs_accumulate_batch(acc.data_ptr(), (ctypes.c_void_p * 1)(g.data_ptr()), 0, 0, 16,
+                                          (ctypes.c_int64 * 1)(32), ctypes.byref(c), None)
+    assert rc == absgd.ABS_EINVAL and c.value == 0                              # J < 1
+
+
+# ---------------------------------------------------------------------------
 # abs_sync_update, call by call
 # ---------------------------------------------------------------------------
 
@@ -343,7 +411,7 @@ def _oracle_trajectory(w, x0, pool, sched, steps, precision, R=None, lam=None):
                    precision=precision, lam=None if lam is None else float(F32(lam)))
 
 
-def _trajectory_case(absgd, name, steps=None, P=None, lam=None):
+def _trajectory_case(absgd, name, steps=None, P=None, lam=None, batched=False):
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
     steps = w.steps if steps is None else steps
@@ -354,7 +422,7 @@ def _trajectory_case(absgd, name, steps=None, P=None, lam=None):
     out = {}
     for overlap in (False, True):
         print(f"[case] trajectory {name} overlap={overlap}", flush=True)
-        run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size, lam=lam)
+        run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size, lam=lam, batched=batched)
         run.run(steps)
         out[overlap] = run.read_state() + (run.count_history, run.applied)
         run.close()
@@ -419,6 +487,13 @@ def test_trajectory_paper_rule(absgd):
 
 
 @pytest.mark.parametrize("name,kw", [("paper_static", dict(steps=6, P=300_007)), ("cfg1_small", {}),
+                                     ("tiny_tail_bf16", {}), ("ragged_odd_f32", {}), ("ragged_odd_bf16", dict(lam=0.5))])
+def test_trajectory_batched_accumulate(absgd, name, kw):
+    """One accumulate launch per worker and step; the oracle still takes the gradients one by one."""
+    _trajectory_case(absgd, name, batched=True, **kw)
+
+
+@pytest.mark.parametrize("name,kw", [("paper_static", dict(steps=6, P=300_007)), ("cfg1_small", {}),
                                      ("tiny_tail_bf16", {}), ("ragged_odd_f32", {}), ("ragged_odd_bf16", {})])
 def test_trajectory_with_compensation(absgd, name, kw):
     """Algorithm 1 complete: delayed update + weighted averaging + compensation, lambda = 0.5."""
@@ -449,10 +524,12 @@ def test_trajectory_delay_invariant_on_gpu(absgd):
 # full BASELINE sizes in the benchmark's launch configuration, sampled outputs
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("name,lam", [("cfg2_resnet18", None), ("cfg3_resnet50_bf16", None), ("cfg4_vgg16", None),
-                                      ("cfg5_gpt2_ragged_bf16", None), ("cfg2_resnet18", 0.5),
-                                      ("cfg5_gpt2_ragged_bf16", 0.5)])
-def test_full_size_sampled(absgd, name, lam):
+@pytest.mark.parametrize("name,lam,batched", [("cfg2_resnet18", None, False), ("cfg3_resnet50_bf16", None, False),
+                                              ("cfg4_vgg16", None, False), ("cfg5_gpt2_ragged_bf16", None, False),
+                                              ("cfg2_resnet18", 0.5, False), ("cfg5_gpt2_ragged_bf16", 0.5, False),
+                                              ("cfg2_resnet18", None, True), ("cfg3_resnet50_bf16", None, True),
+                                              ("cfg5_gpt2_ragged_bf16", None, True)])
+def test_full_size_sampled(absgd, name, lam, batched):
     """Every output element depends only on the same index of the inputs, so the
     oracle runs on a sample of indices gathered from the very same host arrays."""
     from paper_2308_15164_amd.driver import DeviceRun
@@ -463,7 +540,7 @@ def test_full_size_sampled(absgd, name, lam):
     pool = wl.gradient_pool(w, pool=R)
     sched = wl.schedule(w)
     print(f"[case] full size {name}: device run, two streams", flush=True)
-    run = DeviceRun(w, x0, pool, sched, overlap=True, lam=lam)
+    run = DeviceRun(w, x0, pool, sched, overlap=True, lam=lam, batched=batched)
     run.run(w.steps)
     idx = wl.sample_indices(w.P, 200_000, w.seed)
     if w.tensor_sizes is not None:       # both sides of every tensor boundary
