@@ -35,6 +35,14 @@
  * functions with the suffix _dc keep x_{t-1} in a buffer of their own, as the
  * paper's remark on memory overhead implies.
  *
+ * Adam variant (the paper's Section "Conclusions and Future Work" names Adam as
+ * the next update rule to put behind the delayed synchronous mechanism; the
+ * paper does not spell it out).  Here it is the standard Adam recursion driven
+ * by the delayed weighted average, with coupled weight decay:
+ *       g = Gbar + wd*x;  m = b1*m + (1-b1)*g;  v = b2*v + (1-b2)*g*g;
+ *       x = x - gamma * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps),
+ * t = 1, 2, ... counting the updates actually applied.
+ *
  * Precision: everything in IEEE double.  Inputs (fp32 or bf16 gradients, fp32
  * hyper-parameters) are widened exactly before use.
  *
@@ -165,6 +173,33 @@ int oracle_sync_update_dc(double *x, double *x_prev, double *v, const double *co
     return 0;
 }
 
+/* Adam driven by the delayed weighted average.  step >= 1 is the index of this
+ * update among the applied ones.  Returns 1 and touches nothing when
+ * sum(M) == 0. */
+int oracle_sync_update_adam(double *x, double *m, double *v, const double *const *G,
+                            const int64_t *M, int N, int64_t n_params, double gamma, double beta1,
+                            double beta2, double eps, double wd, int64_t step)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const double Mt = (double)M_total;
+    const double bc1 = 1.0 - pow(beta1, (double)step);
+    const double bc2 = 1.0 - pow(beta2, (double)step);
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < N; ++i) s += G[i][j];
+        const double g = s / Mt + wd * x[j];
+        m[j] = beta1 * m[j] + (1.0 - beta1) * g;
+        v[j] = beta2 * v[j] + (1.0 - beta2) * g * g;
+        const double mhat = m[j] / bc1;
+        const double vhat = v[j] / bc2;
+        x[j] = x[j] - gamma * mhat / (sqrt(vhat) + eps);
+    }
+    return 0;
+}
+
 /* ---- fp32 family with a fixed operation order -------------------------- */
 
 /* first != 0: this is the first reference batch since the accumulator was
@@ -252,6 +287,48 @@ int oracle32_sync_update_dc(float *x, float *x_prev, float *v, const float *cons
         v[j] = vn;
         x_prev[j] = x[j];
         x[j] = fmaf(-gamma, vn, x[j]);
+    }
+    return 0;
+}
+
+/* Adam.  Order: Gbar as above; g = fma(wd, x, Gbar); m = fma(beta1, m, (1-beta1)*g)
+ * with (1-beta1) rounded to fp32 first; v = fma(beta2, v, (1-beta2)*(g*g));
+ * mh = m / bc1; vh = v / bc2 with bc = (float)(1 - beta^step) evaluated in double
+ * from the fp32 betas; den = sqrtf(vh) + eps; x = fma(-gamma, mh / den, x). */
+int oracle32_sync_update_adam(float *x, float *m, float *v, const float *const *G,
+                              const int64_t *M, int N, int64_t n_params, float gamma, float beta1,
+                              float beta2, float eps, float wd, int64_t step)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const float Mt = (float)M_total;
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    const float bc1 = (float)(1.0 - pow((double)beta1, (double)step));
+    const float bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        float s = 0.0f;
+        int seen = 0;
+        for (int i = 0; i < N; ++i) {
+            if (M[i] <= 0) continue;
+            s = seen ? s + G[i][j] : G[i][j];
+            seen = 1;
+        }
+        const float Gbar = s / Mt;
+        const float g = fmaf(wd, x[j], Gbar);
+        const float t1 = omb1 * g;
+        const float mn = fmaf(beta1, m[j], t1);
+        const float g2 = g * g;
+        const float t2 = omb2 * g2;
+        const float vn = fmaf(beta2, v[j], t2);
+        m[j] = mn;
+        v[j] = vn;
+        const float mh = mn / bc1;
+        const float vh = vn / bc2;
+        const float den = sqrtf(vh) + eps;
+        const float q = mh / den;
+        x[j] = fmaf(-gamma, q, x[j]);
     }
     return 0;
 }

@@ -60,6 +60,12 @@ def lib():
         _lib.oracle32_sync_update_dc.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
                                                  _c_flt, _c_flt, _c_flt, _c_flt]
         _lib.oracle32_sync_update_dc.restype = ctypes.c_int
+        _lib.oracle_sync_update_adam.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
+                                                 _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_i64]
+        _lib.oracle_sync_update_adam.restype = ctypes.c_int
+        _lib.oracle32_sync_update_adam.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
+                                                   _c_flt, _c_flt, _c_flt, _c_flt, _c_flt, _c_i64]
+        _lib.oracle32_sync_update_adam.restype = ctypes.c_int
         _lib.oracle32_accumulate_f32.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_accumulate_bf16.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_sync_update.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
@@ -153,6 +159,23 @@ def sync_update_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
     return rc == 0
 
 
+def sync_update_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, step):
+    """Adam driven by the delayed weighted average (the paper's stated next step);
+    step = 1, 2, ... counts the updates actually applied."""
+    for a in (x, m, v):
+        _check(a, np.float64)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float64)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    rc = lib().oracle_sync_update_adam(_ptr(x), _ptr(m), _ptr(v), ptrs, _ptr(M), N, x.size, float(gamma),
+                                       float(beta1), float(beta2), float(eps), float(wd), int(step))
+    return rc == 0
+
+
 # ---- fp32 family with the fixed operation order ------------------------------
 
 def accumulate32(G, g, M_r, first):
@@ -197,9 +220,25 @@ def sync_update32_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
     return rc == 0
 
 
+def sync_update32_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, step):
+    for a in (x, m, v):
+        _check(a, np.float32)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float32)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    f = lambda t: float(np.float32(t))
+    rc = lib().oracle32_sync_update_adam(_ptr(x), _ptr(m), _ptr(v), ptrs, _ptr(M), N, x.size, f(gamma),
+                                         f(beta1), f(beta2), f(eps), f(wd), int(step))
+    return rc == 0
+
+
 # ---- Algorithm 1, whole loop --------------------------------------------------
 
-def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None):
+def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None, adam=None):
     """Run T iterations of Algorithm 1 on the flat parameter vector x0.
 
     batches(t, i) -> list of mean-gradient vectors (float32 or bf16 bits), one
@@ -215,6 +254,8 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     precision "f64": the definition in double.  "f32": the fixed-order fp32
     restatement.  lam: compensation coefficient lambda; None leaves the
     compensation line of Algorithm 1 out (then no x_{t-1} is kept).
+    adam: (beta1, beta2, eps) switches the update rule to Adam (mu is unused,
+    the returned "v" is then the pair (m, v)).
     Returns (x_T, v_T, M_history[T][N]).  record(t, x, v) is called after each
     iteration when given.
     """
@@ -232,6 +273,9 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     M = [[0] * N for _ in range(2)]   # G_{-1} = 0; its batch sizes are 0
     cur, prev = 0, 1
     history = []
+    if adam is not None:
+        m1 = np.zeros(P, dtype=ft)
+        applied = 0
     for t in range(T):
         # Step 2: accumulate generation t (at x_t)
         for i in range(N):
@@ -244,7 +288,11 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
                     accumulate32(G[cur][i], g, M_r, first=(M[cur][i] == 0))
                 M[cur][i] += M_r
         # Step 1 + update: apply generation t-1 to x_t
-        if lam is None:
+        if adam is not None:
+            fn = sync_update_adam if precision == "f64" else sync_update32_adam
+            if fn(x, m1, v, G[prev], M[prev], gamma, adam[0], adam[1], adam[2], wd, applied + 1):
+                applied += 1
+        elif lam is None:
             upd_fn(x, v, G[prev], M[prev], gamma, mu, wd)
         elif precision == "f64":
             sync_update_dc(x, x_prev, v, G[prev], M[prev], gamma, mu, wd, lam)
@@ -254,4 +302,6 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
         if record is not None:
             record(t, x, v)
         cur, prev = prev, cur
+    if adam is not None:
+        return x, (m1, v), history
     return x, v, history

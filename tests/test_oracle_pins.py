@@ -498,3 +498,125 @@ def test_compensation_fp32_family_tracks_double_family():
     assert np.max(np.abs(x64 - xb)) > 1e-4                       # the compensation is active here
     assert np.max(np.abs(x32 - x64)) <= 2e-6 * np.max(np.abs(x64))
     assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
+
+
+# ---------------------------------------------------------------------------
+# 11. Adam behind the delayed synchronous mechanism (Section "Conclusions and
+#     Future Work" names it; the recursion is the published Adam algorithm)
+# ---------------------------------------------------------------------------
+
+def test_adam_constant_gradient_closed_form():
+    """With a constant gradient the bias-corrected moments are exactly g and g^2,
+    so every step moves x by gamma * g / (|g| + eps)."""
+    g = np.array([0.25, -3.0, 1e-3])
+    gamma, b1, b2, eps = 0.01, 0.9, 0.999, 1e-8
+    G = [g * 96]
+    x, m, v = np.zeros(3), np.zeros(3), np.zeros(3)
+    for t in range(1, 13):
+        assert orc.sync_update_adam(x, m, v, G, [96], gamma, b1, b2, eps, 0.0, t)
+        np.testing.assert_allclose(x, -t * gamma * g / (np.abs(g) + eps), rtol=1e-12)
+        np.testing.assert_allclose(m, g * (1 - b1 ** t), rtol=1e-12)
+        np.testing.assert_allclose(v, g * g * (1 - b2 ** t), rtol=1e-12)
+
+
+def test_adam_matches_a_library_adam_on_delayed_averaged_gradients():
+    """The same gradients fed to torch.optim.Adam (double, CPU): an independent
+    implementation of the published recursion, including coupled weight decay."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(21)
+    P, N, T, M_r = 37, 3, 7, 32
+    gamma, b1, b2, eps, wd = 0.01, 0.9, 0.999, 1e-8, 5e-3
+    m = rng.integers(0, 4, size=(T, N))
+    m[2, :] = 0                                              # an iteration without samples: no Adam step
+    means = {(t, i, j): (rng.standard_normal(P) * 0.1).astype(F32)
+             for t in range(T) for i in range(N) for j in range(int(m[t, i]))}
+    x0 = rng.standard_normal(P).astype(F32)
+
+    x_o, (m_o, v_o), _ = orc.run(x0, N, T, M_r, gamma, 0.0, wd,
+                                 lambda t, i: [means[(t, i, j)] for j in range(int(m[t, i]))],
+                                 adam=(b1, b2, eps))
+
+    p = torch.tensor(x0.astype(np.float64), requires_grad=True)
+    opt = torch.optim.Adam([p], lr=gamma, betas=(b1, b2), eps=eps, weight_decay=wd)
+    for t in range(1, T):                                    # iteration t applies the average of t-1
+        batch = [means[(t - 1, i, j)].astype(np.float64) for i in range(N) for j in range(int(m[t - 1, i]))]
+        if not batch:
+            continue
+        p.grad = torch.tensor(np.mean(batch, axis=0))        # equal-size batches: the sample-weighted mean
+        opt.step()
+    np.testing.assert_allclose(x_o, p.detach().numpy(), rtol=1e-11, atol=1e-13)
+    st = opt.state[p]
+    np.testing.assert_allclose(m_o, st["exp_avg"].numpy(), rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(v_o, st["exp_avg_sq"].numpy(), rtol=1e-11, atol=1e-18)
+
+
+def test_adam_brute_force_high_precision():
+    """Per-sample gradients expanded and the recursion evaluated in 60-digit decimals."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    rng = np.random.default_rng(22)
+    P, N, T, M_r = 3, 2, 5, 4
+    gamma, b1, b2, eps, wd = F32(0.01), F32(0.9), F32(0.999), F32(1e-8), F32(1e-2)
+    D = lambda t: Decimal(float(t))
+    m = rng.integers(1, 3, size=(T, N))
+    samples = {(t, i, j): rng.integers(-512, 513, size=(M_r, P))
+               for t in range(T) for i in range(N) for j in range(int(m[t, i]))}
+    x0 = (rng.integers(-1024, 1025, size=P) / 512.0).astype(F32)
+
+    def batches(t, i):
+        return [(samples[(t, i, j)].sum(axis=0) / (256.0 * M_r)).astype(F32) for j in range(int(m[t, i]))]
+
+    x_o, (m_o, v_o), _ = orc.run(x0, N, T, M_r, gamma, 0.0, wd, batches, adam=(b1, b2, eps))
+    x = [D(a) for a in x0]
+    mm = [Decimal(0)] * P
+    vv = [Decimal(0)] * P
+    step = 0
+    for t in range(1, T):
+        alls = [samples[(t - 1, i, j)][s] for i in range(N) for j in range(int(m[t - 1, i])) for s in range(M_r)]
+        step += 1
+        for p in range(P):
+            gbar = Decimal(int(sum(int(s[p]) for s in alls))) / Decimal(256 * len(alls))
+            g = gbar + D(wd) * x[p]
+            mm[p] = D(b1) * mm[p] + (1 - D(b1)) * g
+            vv[p] = D(b2) * vv[p] + (1 - D(b2)) * g * g
+            mh = mm[p] / (1 - D(b1) ** step)
+            vh = vv[p] / (1 - D(b2) ** step)
+            x[p] = x[p] - D(gamma) * mh / (vh.sqrt() + D(eps))
+    np.testing.assert_allclose(x_o, [float(a) for a in x], rtol=1e-12)
+    np.testing.assert_allclose(m_o, [float(a) for a in mm], rtol=1e-12)
+    np.testing.assert_allclose(v_o, [float(a) for a in vv], rtol=1e-12)
+
+
+def test_adam_is_invariant_to_gradient_scale_and_skips_empty_steps():
+    rng = np.random.default_rng(23)
+    P = 11
+    G = [rng.standard_normal(P) * 32]
+    xa, ma, va = np.zeros(P), np.zeros(P), np.zeros(P)
+    xb, mb, vb = np.zeros(P), np.zeros(P), np.zeros(P)
+    for t in (1, 2, 3):
+        orc.sync_update_adam(xa, ma, va, G, [32], 0.01, 0.9, 0.999, 0.0, 0.0, t)
+        orc.sync_update_adam(xb, mb, vb, [G[0] * 1000.0], [32], 0.01, 0.9, 0.999, 0.0, 0.0, t)
+    np.testing.assert_allclose(xa, xb, rtol=1e-12)           # eps = 0: only the direction matters
+    before = xa.copy()
+    assert orc.sync_update_adam(xa, ma, va, G, [0], 0.01, 0.9, 0.999, 0.0, 0.0, 4) is False
+    np.testing.assert_array_equal(xa, before)
+
+
+def test_adam_fp32_family_tracks_double_family():
+    rng = np.random.default_rng(24)
+    P, N, T, M_r = 2051, 3, 8, 32
+    m = rng.integers(1, 4, size=(T, N))
+    pool = [(rng.standard_normal(P) * 0.01).astype(F32) for _ in range(8)]
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+
+    def batches(t, i):
+        return [pool[(3 * t + 5 * i + j) % 8] for j in range(int(m[t, i]))]
+
+    args = (x0, N, T, M_r, F32(0.001), 0.0, F32(1e-2), batches)
+    ad = (F32(0.9), F32(0.999), F32(1e-8))
+    x64, (m64, v64), _ = orc.run(*args, precision="f64", adam=ad)
+    x32, (m32, v32), _ = orc.run(*args, precision="f32", adam=ad)
+    assert np.max(np.abs(x32 - x64)) <= 2e-6 * np.max(np.abs(x64))
+    assert np.max(np.abs(m32 - m64)) <= 2e-6 * np.max(np.abs(m64))
+    assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
+    assert np.max(np.abs(x64 - x0)) > 1e-3                     # seven updates of ~lr each
