@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {
 MAX_BATCH = 8   # ABS_MAX_BATCH: gradients one accumulate launch folds in
 
 
-def bytes_per_param(w, m_row, compensated=False, batched=False):
+def bytes_per_param(w, m_row, extra_state=False, batched=False):
     """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
     an accumulate reads one gradient element and reads+writes one fp32
     accumulator element (the first call of a step only writes it); the
@@ -48,7 +48,7 @@ def bytes_per_param(w, m_row, compensated=False, batched=False):
         acc = sum(int(m) * gb + 8 * (-(-int(m) // MAX_BATCH)) - 4 for m in m_row)
     else:
         acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
-    return acc, 4 * w.K + 16 + (8 if compensated else 0)
+    return acc, 4 * w.K + 16 + (8 if extra_state else 0)
 
 
 def accumulate_launches(m_row, batched):
@@ -209,6 +209,9 @@ def main():
     ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
                     help="also apply the delayed gradient compensation with this coefficient "
                          "(abs_sync_update_dc; +8 B/param); default: off, the BASELINE metric's path")
+    ap.add_argument("--adam", action="store_true",
+                    help="Adam (beta 0.9/0.999, eps 1e-8, lr 1e-3) as the update rule instead of momentum SGD "
+                         "(abs_sync_update_adam; +8 B/param)")
     ap.add_argument("--batched", action="store_true",
                     help="one abs_accumulate_batch call per worker and step instead of one abs_accumulate "
                          "per micro-batch (fewer bytes: the accumulator is read and written once)")
@@ -253,8 +256,11 @@ def main():
             plans_wanted.append((f"{n} accumulate streams (workers spread) | sync-update", True, n))
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
-    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched)
-    comp = args.compensation is not None
+    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched,
+                    adam=(0.9, 0.999, 1e-8) if args.adam else None)
+    if args.adam:
+        run.lr = 1e-3
+    comp = args.compensation is not None or args.adam
     calls = [run.plan_step(t) for t in range(total)]
     timings = {}
     for name, overlap, n_acc in plans_wanted:
@@ -312,6 +318,7 @@ def main():
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
             "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
             "compensation_lambda": args.compensation, "batched_accumulate": args.batched,
+            "update_rule": "adam" if args.adam else "momentum sgd",
             "streams": best + ", double-buffered",
             "algorithmic_bytes_per_step": step_bytes // K_steps,
         },

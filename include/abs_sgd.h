@@ -158,6 +158,27 @@ int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const
                        float lambda, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (3'') Adam behind the delayed synchronous mechanism -- the update rule the
+ *     paper's Section "Conclusions and Future Work" names as its next step.
+ *     Same read pass over the K delayed accumulators; the state is the first
+ *     and second moment instead of the momentum: 4K + 24 B/param.
+ *
+ *   step >= 1 is the index of this update among the APPLIED ones (the caller
+ *   advances it when the call returns ABS_OK, not on ABS_EMPTY).  Order after Gbar:
+ *     g = fmaf(wd, x, Gbar)                      (coupled weight decay)
+ *     m = fmaf(beta1, m, (1-beta1)*g);  v = fmaf(beta2, v, (1-beta2)*(g*g))
+ *       with (1-beta) rounded to fp32 once
+ *     mh = m / bc1;  vh = v / bc2;   bc = (float)(1 - beta^step), evaluated in double
+ *     x = fmaf(-lr, mh / (sqrtf(vh) + eps), x)    (correctly rounded divide and sqrt)
+ *
+ *   exp_avg, exp_avg_sq  DEVICE, P floats each, read and written (start at 0)
+ *   EINVAL also for step < 1, beta outside [0, 1), eps < 0.
+ * ---------------------------------------------------------------------- */
+int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const float *const *acc,
+                         const int64_t *counts, int K, int64_t P, float lr, float beta1, float beta2,
+                         float eps, float wd, int64_t step, void *stream);
+
+/* ------------------------------------------------------------------------
  * Ragged (multi-tensor) layouts: the parameter vector of Section "Problem
  * definition" split into T separately allocated tensors of arbitrary sizes.
  * One launch covers all tensors.
@@ -217,6 +238,12 @@ int abs_sync_update_dc_mt(abs_layout *layout, const abs_tensorset *params,
                           const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                           float mu, float wd, float lambda, void *stream);
 
+/* abs_sync_update_adam over every tensor of the layout. */
+int abs_sync_update_adam_mt(abs_layout *layout, const abs_tensorset *params,
+                            const abs_tensorset *exp_avg, const abs_tensorset *exp_avg_sq,
+                            const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                            float beta1, float beta2, float eps, float wd, int64_t step, void *stream);
+
 /* ------------------------------------------------------------------------
  * (4) Double buffer -- Algorithm 1, "Run Step 1 and Step 2 in parallel": two
  *     generations of (K accumulators, K counts).  Accumulation of batch t runs
@@ -270,6 +297,13 @@ int abs_ctx_sync_update_dc(abs_ctx *ctx, float *params, float *params_prev, floa
 int abs_ctx_sync_update_dc_mt(abs_ctx *ctx, const abs_tensorset *params,
                               const abs_tensorset *params_prev, const abs_tensorset *momentum,
                               float lr, float mu, float wd, float lambda);
+
+/* Adam (abs_sync_update_adam) from the PREVIOUS generation. */
+int abs_ctx_sync_update_adam(abs_ctx *ctx, float *params, float *exp_avg, float *exp_avg_sq, float lr,
+                             float beta1, float beta2, float eps, float wd, int64_t step);
+int abs_ctx_sync_update_adam_mt(abs_ctx *ctx, const abs_tensorset *params,
+                                const abs_tensorset *exp_avg, const abs_tensorset *exp_avg_sq,
+                                float lr, float beta1, float beta2, float eps, float wd, int64_t step);
 
 /* End of an iteration (Algorithm 1, t = t + 1): stream_upd and every accumulate
  * stream wait for the work the other side has enqueued so far (the next sync-update reads what accumulation

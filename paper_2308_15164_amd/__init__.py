@@ -33,6 +33,7 @@ SYMBOLS = {
     "abs_accumulate_batch": (_int, [_vp, _pvp, _int, _int, _i64, _pi64, _pi64, _vp]),
     "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
     "abs_sync_update_dc": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _vp]),
+    "abs_sync_update_adam": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _f, _i64, _vp]),
     "abs_layout_create": (_int, [_pvp, _int, _pi64]),
     "abs_layout_destroy": (_int, [_vp]),
     "abs_layout_num_tensors": (_int, [_vp]),
@@ -46,6 +47,7 @@ SYMBOLS = {
     "abs_accumulate_batch_mt": (_int, [_vp, _vp, _pvp, _int, _pi64, _pi64, _vp]),
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
     "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
+    "abs_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _i64, _vp]),
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_destroy": (_int, [_vp]),
@@ -58,6 +60,8 @@ SYMBOLS = {
     "abs_ctx_sync_update_mt": (_int, [_vp, _vp, _vp, _f, _f, _f]),
     "abs_ctx_sync_update_dc": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
     "abs_ctx_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
+    "abs_ctx_sync_update_adam": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64]),
+    "abs_ctx_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64]),
     "abs_swap_buffers": (_int, [_vp]),
     "abs_ctx_counts": (_int, [_vp, _int, _pi64]),
 }
@@ -214,6 +218,17 @@ def abs_sync_update_dc(params, params_prev, momentum, acc, counts, lr, mu, wd, l
     return _check("abs_sync_update_dc", rc, allow_empty=True)
 
 
+def abs_sync_update_adam(params, exp_avg, exp_avg_sq, acc, counts, lr, beta1, beta2, eps, wd, step,
+                         stream=None, P=None):
+    """Adam on the delayed weighted average; step counts the applied updates from 1."""
+    n = params.numel() if P is None else int(P)
+    ptrs = _ptr_array([_dev_ptr(a) for a in acc])
+    rc = lib().abs_sync_update_adam(_dev_ptr(params), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), ptrs,
+                                    _i64_array(counts), len(acc), n, float(lr), float(beta1), float(beta2),
+                                    float(eps), float(wd), int(step), _stream_handle(stream))
+    return _check("abs_sync_update_adam", rc, allow_empty=True)
+
+
 class Layout:
     """abs_layout: tensor sizes of a ragged parameter vector and its chunk table."""
 
@@ -315,6 +330,15 @@ def abs_sync_update_dc_mt(layout, params, params_prev, momentum, acc, counts, lr
     return _check("abs_sync_update_dc_mt", rc, allow_empty=True)
 
 
+def abs_sync_update_adam_mt(layout, params, exp_avg, exp_avg_sq, acc, counts, lr, beta1, beta2, eps, wd,
+                            step, stream=None):
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_adam_mt(layout.handle, params.handle, exp_avg.handle, exp_avg_sq.handle, sets,
+                                       _i64_array(counts), len(acc), float(lr), float(beta1), float(beta2),
+                                       float(eps), float(wd), int(step), _stream_handle(stream))
+    return _check("abs_sync_update_adam_mt", rc, allow_empty=True)
+
+
 class Context:
     """abs_ctx: the double buffer.  acc_A / acc_B are K tensors each (flat form)
     or K TensorSets each over `layout` (ragged form)."""
@@ -381,6 +405,17 @@ class Context:
                                              momentum.handle, float(lr), float(mu), float(wd), float(lam))
         return _check("abs_ctx_sync_update_dc_mt", rc, allow_empty=True)
 
+    def abs_sync_update_adam(self, params, exp_avg, exp_avg_sq, lr, beta1, beta2, eps, wd, step):
+        if self.layout is None:
+            rc = lib().abs_ctx_sync_update_adam(self.handle, _dev_ptr(params), _dev_ptr(exp_avg),
+                                                _dev_ptr(exp_avg_sq), float(lr), float(beta1), float(beta2),
+                                                float(eps), float(wd), int(step))
+            return _check("abs_ctx_sync_update_adam", rc, allow_empty=True)
+        rc = lib().abs_ctx_sync_update_adam_mt(self.handle, params.handle, exp_avg.handle, exp_avg_sq.handle,
+                                               float(lr), float(beta1), float(beta2), float(eps), float(wd),
+                                               int(step))
+        return _check("abs_ctx_sync_update_adam_mt", rc, allow_empty=True)
+
     def abs_swap_buffers(self):
         return _check("abs_swap_buffers", lib().abs_swap_buffers(self.handle))
 
@@ -407,7 +442,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

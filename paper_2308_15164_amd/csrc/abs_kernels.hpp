@@ -226,66 +226,102 @@ __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc, const G
 
 // --------------------------------------------------------------- sync-update
 
-struct Hyper { float M, lr, mu, wd, lambda; };
+// Update rules of the fused combine + update pass.  Each keeps, besides x, up
+// to two more per-parameter state vectors (s1, s2):
+//   SGD   : s1 = momentum v                                   (s2 unused)
+//   SGD_DC: s1 = momentum v,        s2 = previous iterate x_{t-1}
+//   ADAM  : s1 = first moment m,    s2 = second moment v
+enum Rule { SGD = 0, SGD_DC = 1, ADAM = 2 };
 
-// DC: delayed gradient compensation, Gtilde = Gbar + lambda*Gbar*Gbar*(x - xp)
-// with xp the previous iterate; xp then takes the value x had on entry.
-template <bool DC>
-__device__ __forceinline__ void update_one(float s, float &x, float &v, float &xp, const Hyper &h)
+template <int RULE> constexpr bool uses_s2() { return RULE != SGD; }
+
+struct Hyper {
+    float M, lr, wd;
+    float mu, lambda;                        // SGD, SGD_DC
+    float beta1, beta2, omb1, omb2, eps;     // ADAM: omb = 1 - beta (rounded to fp32 on the host)
+    float bc1, bc2;                          // ADAM: 1 - beta^t, computed in double on the host
+};
+
+// One element.  s = sum of the workers' accumulators.  Orders (every operation
+// rounded to fp32, fused where written as fma):
+//   Gbar = s / M
+//   SGD    d = fma(wd, x, Gbar); v = fma(mu, v, d); x = fma(-lr, v, x)
+//   SGD_DC q = Gbar*Gbar; c = lambda*q; diff = x - xp; Gt = fma(c, diff, Gbar);
+//          d = fma(wd, x, Gt); v = fma(mu, v, d); xp = x; x = fma(-lr, v, x)
+//   ADAM   g = fma(wd, x, Gbar); m = fma(beta1, m, omb1*g); v = fma(beta2, v, omb2*(g*g));
+//          mh = m / bc1; vh = v / bc2; den = sqrt(vh) + eps; x = fma(-lr, mh / den, x)
+template <int RULE>
+__device__ __forceinline__ void update_one(float s, float &x, float &s1, float &s2, const Hyper &h)
 {
     float g = s / h.M;
-    if constexpr (DC) {
-        const float q = g * g;
-        const float c = h.lambda * q;
-        const float diff = x - xp;
-        g = __builtin_fmaf(c, diff, g);
-        xp = x;
+    if constexpr (RULE == ADAM) {
+        g = __builtin_fmaf(h.wd, x, g);
+        const float t1 = h.omb1 * g;
+        s1 = __builtin_fmaf(h.beta1, s1, t1);
+        const float g2 = g * g;
+        const float t2 = h.omb2 * g2;
+        s2 = __builtin_fmaf(h.beta2, s2, t2);
+        const float mh = s1 / h.bc1;
+        const float vh = s2 / h.bc2;
+        const float den = __builtin_sqrtf(vh) + h.eps;
+        const float q = mh / den;
+        x = __builtin_fmaf(-h.lr, q, x);
+    } else {
+        if constexpr (RULE == SGD_DC) {
+            const float q = g * g;
+            const float c = h.lambda * q;
+            const float diff = x - s2;
+            g = __builtin_fmaf(c, diff, g);
+            s2 = x;
+        }
+        const float d = __builtin_fmaf(h.wd, x, g);
+        s1 = __builtin_fmaf(h.mu, s1, d);
+        x = __builtin_fmaf(-h.lr, s1, x);
     }
-    const float d = __builtin_fmaf(h.wd, x, g);
-    v = __builtin_fmaf(h.mu, v, d);
-    x = __builtin_fmaf(-h.lr, v, x);
 }
 
-template <bool DC>
-__device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &v, f32x4 &xp, const Hyper &h)
+template <int RULE>
+__device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &s1, f32x4 &s2, const Hyper &h)
 {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        float xs = x[c], vs = v[c], ps = xp[c];
-        update_one<DC>(s[c], xs, vs, ps, h);
+        float xs = x[c], a = s1[c], b = s2[c];
+        update_one<RULE>(s[c], xs, a, b, h);
         x[c] = xs;
-        v[c] = vs;
-        xp[c] = ps;
+        s1[c] = a;
+        s2[c] = b;
     }
 }
 
 template <int K> struct AccPtrs { const float *p[K]; };
 
 // rows per group so that about ABS_SYNC_INFLIGHT loads are outstanding per lane
-template <int K, bool DC>
+template <int K, int RULE>
 constexpr int sync_unroll()
 {
-    int u = ABS_SYNC_INFLIGHT / (K + 2 + (DC ? 1 : 0));
+    int u = ABS_SYNC_INFLIGHT / (K + 2 + (uses_s2<RULE>() ? 1 : 0));
     return u < 1 ? 1 : (u > 4 ? 4 : u);
 }
 
 // One workgroup, one tile of the fused combine + update; K compile-time.
-// NTX: x / v (/ xp) traffic is streaming.  xp is only touched when DC.
-template <int K, bool NTX, bool DC>
+// NTX: the traffic of x and the state vectors is streaming.  xp (the rule's
+// second state vector) is only touched by rules that have one.
+template <int K, bool NTX, int RULE>
 __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restrict__ v,
                                           float *__restrict__ xp, const AccPtrs<K> &A, int len,
                                           const Hyper &h, bool vec_ok)
 {
-    constexpr int U = sync_unroll<K, DC>();
+    constexpr bool S2 = uses_s2<RULE>();
+    constexpr int U = sync_unroll<K, RULE>();
     const int tid = threadIdx.x;
     if (!vec_ok) {
         for (int i = tid; i < len; i += BLOCK) {
             float s = A.p[0][i];
 #pragma unroll
             for (int k = 1; k < K; ++k) s = s + A.p[k][i];
-            float ps = DC ? xp[i] : 0.f;
-            update_one<DC>(s, x[i], v[i], ps, h);
-            if constexpr (DC) xp[i] = ps;
+            float ps = S2 ? xp[i] : 0.f;
+            update_one<RULE>(s, x[i], v[i], ps, h);
+            if constexpr (S2) xp[i] = ps;
         }
         return;
     }
@@ -304,7 +340,7 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
                 a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
             xr[u] = ld<NTX>(xv + i);
             vr[u] = ld<NTX>(vv + i);
-            if constexpr (DC) pr[u] = ld<NTX>(pv + i);
+            if constexpr (S2) pr[u] = ld<NTX>(pv + i);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -312,9 +348,9 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
             f32x4 s = a[u][0];
 #pragma unroll
             for (int k = 1; k < K; ++k) s = s + a[u][k];
-            update_vec<DC>(s, xr[u], vr[u], pr[u], h);
+            update_vec<RULE>(s, xr[u], vr[u], pr[u], h);
             st<NTX>(vv + i, vr[u]);
-            if constexpr (DC) st<NTX>(pv + i, pr[u]);
+            if constexpr (S2) st<NTX>(pv + i, pr[u]);
             st<NTX>(xv + i, xr[u]);
         }
     }
@@ -324,10 +360,10 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
         for (int k = 1; k < K; ++k)
             s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
         f32x4 xr = ld<NTX>(xv + i), vr = ld<NTX>(vv + i), pr = {};
-        if constexpr (DC) pr = ld<NTX>(pv + i);
-        update_vec<DC>(s, xr, vr, pr, h);
+        if constexpr (S2) pr = ld<NTX>(pv + i);
+        update_vec<RULE>(s, xr, vr, pr, h);
         st<NTX>(vv + i, vr);
-        if constexpr (DC) st<NTX>(pv + i, pr);
+        if constexpr (S2) st<NTX>(pv + i, pr);
         st<NTX>(xv + i, xr);
     }
     const int i = nvec * VEC + tid;
@@ -335,22 +371,22 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
         float s = A.p[0][i];
 #pragma unroll
         for (int k = 1; k < K; ++k) s = s + A.p[k][i];
-        float ps = DC ? xp[i] : 0.f;
-        update_one<DC>(s, x[i], v[i], ps, h);
-        if constexpr (DC) xp[i] = ps;
+        float ps = S2 ? xp[i] : 0.f;
+        update_one<RULE>(s, x[i], v[i], ps, h);
+        if constexpr (S2) xp[i] = ps;
     }
 }
 
 // K known only at run time (K above the specialised range).  get(k) yields
 // worker k's accumulator pointer for this tile; it is uniform across the
-// workgroup, so it costs scalar loads only.  xp == nullptr: no compensation.
-template <class GetPtr>
+// workgroup, so it costs scalar loads only.
+template <int RULE, class GetPtr>
 __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__restrict__ v,
                                               float *__restrict__ xp, GetPtr get, int K, int len,
                                               const Hyper &h, bool vec_ok)
 {
+    constexpr bool S2 = uses_s2<RULE>();
     const int tid = threadIdx.x;
-    const bool dc = xp != nullptr;
     if (vec_ok) {
         f32x4 *xv = reinterpret_cast<f32x4 *>(x);
         f32x4 *vv = reinterpret_cast<f32x4 *>(v);
@@ -362,32 +398,21 @@ __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__re
             for (int k = 1; k < K; ++k)
                 s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(get(k)) + i);
             f32x4 xr = xv[i], vr = vv[i], pr = {};
-            if (dc) {
-                pr = pv[i];
-                update_vec<true>(s, xr, vr, pr, h);
-                pv[i] = pr;
-            } else {
-                update_vec<false>(s, xr, vr, pr, h);
-            }
+            if constexpr (S2) pr = pv[i];
+            update_vec<RULE>(s, xr, vr, pr, h);
             vv[i] = vr;
+            if constexpr (S2) pv[i] = pr;
             xv[i] = xr;
         }
-        const int i = nvec * VEC + tid;
-        if (i < len) {
-            float s = get(0)[i];
-            for (int k = 1; k < K; ++k) s = s + get(k)[i];
-            float ps = 0.f;
-            if (dc) { ps = xp[i]; update_one<true>(s, x[i], v[i], ps, h); xp[i] = ps; }
-            else update_one<false>(s, x[i], v[i], ps, h);
-        }
-        return;
     }
-    for (int i = tid; i < len; i += BLOCK) {
+    const int done = vec_ok ? (len / VEC) * VEC : 0;
+    for (int i = done + tid; i < len; i += BLOCK) {
         float s = get(0)[i];
         for (int k = 1; k < K; ++k) s = s + get(k)[i];
         float ps = 0.f;
-        if (dc) { ps = xp[i]; update_one<true>(s, x[i], v[i], ps, h); xp[i] = ps; }
-        else update_one<false>(s, x[i], v[i], ps, h);
+        if constexpr (S2) ps = xp[i];
+        update_one<RULE>(s, x[i], v[i], ps, h);
+        if constexpr (S2) xp[i] = ps;
     }
 }
 
@@ -434,7 +459,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_flat(float *__restrict__
     accumulate_tile<BF16, NTA, J>(acc + base, G, tile_len(P, base, tile), first != 0, vec_ok != 0);
 }
 
-template <int K, bool NTX, bool DC>
+template <int K, bool NTX, int RULE>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat(float *__restrict__ x,
                                                              float *__restrict__ v,
                                                              float *__restrict__ xp, AccPtrs<K> A,
@@ -444,10 +469,11 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat(float *__restrict_
     AccPtrs<K> B;
 #pragma unroll
     for (int k = 0; k < K; ++k) B.p[k] = A.p[k] + base;
-    sync_tile<K, NTX, DC>(x + base, v + base, DC ? xp + base : nullptr, B, tile_len(P, base, tile), h,
-                          vec_ok != 0);
+    sync_tile<K, NTX, RULE>(x + base, v + base, uses_s2<RULE>() ? xp + base : nullptr, B,
+                            tile_len(P, base, tile), h, vec_ok != 0);
 }
 
+template <int RULE>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restrict__ x,
                                                                  float *__restrict__ v,
                                                                  float *__restrict__ xp,
@@ -455,8 +481,8 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restr
                                                                  int tile, Hyper h, int vec_ok)
 {
     const int64_t base = (int64_t)blockIdx.x * tile;
-    sync_tile_any(x + base, v + base, xp ? xp + base : nullptr, [&](int k) { return A.p[k] + base; }, K,
-                  tile_len(P, base, tile), h, vec_ok != 0);
+    sync_tile_any<RULE>(x + base, v + base, uses_s2<RULE>() ? xp + base : nullptr,
+                        [&](int k) { return A.p[k] + base; }, K, tile_len(P, base, tile), h, vec_ok != 0);
 }
 
 __global__ __launch_bounds__(ABS_BLOCK) void copy_flat(float *__restrict__ dst,
@@ -503,7 +529,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__re
 template <int K> struct TabPtrs { const float *const *t[K]; };
 struct TabPtrsAny { const float *const *t[64]; };
 
-template <int K, bool NTX, bool DC>
+template <int K, bool NTX, int RULE>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__restrict__ chunks,
                                                                const int64_t *__restrict__ sizes,
                                                                float *const *__restrict__ x_tab,
@@ -517,7 +543,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__r
     float *v = v_tab[c.tensor] + base;
     float *xp = nullptr;
     bool vec_ok = aligned16(x) && aligned16(v);
-    if constexpr (DC) {
+    if constexpr (uses_s2<RULE>()) {
         xp = p_tab[c.tensor] + base;
         vec_ok = vec_ok && aligned16(xp);
     }
@@ -527,9 +553,10 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__r
         A.p[k] = tabs.t[k][c.tensor] + base;
         vec_ok = vec_ok && aligned16(A.p[k]);
     }
-    sync_tile<K, NTX, DC>(x, v, xp, A, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
+    sync_tile<K, NTX, RULE>(x, v, xp, A, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
 }
 
+template <int RULE>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk *__restrict__ chunks,
                                                                    const int64_t *__restrict__ sizes,
                                                                    float *const *__restrict__ x_tab,
@@ -542,11 +569,11 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk 
     const int64_t base = (int64_t)c.index * tile;
     float *x = x_tab[c.tensor] + base;
     float *v = v_tab[c.tensor] + base;
-    float *xp = p_tab ? p_tab[c.tensor] + base : nullptr;
+    float *xp = uses_s2<RULE>() ? p_tab[c.tensor] + base : nullptr;
     bool vec_ok = aligned16(x) && aligned16(v) && aligned16(xp);
     for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned16(tabs.t[k][c.tensor] + base);
-    sync_tile_any(x, v, xp, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
-                  tile_len(sizes[c.tensor], base, tile), h, vec_ok);
+    sync_tile_any<RULE>(x, v, xp, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
+                        tile_len(sizes[c.tensor], base, tile), h, vec_ok);
 }
 
 __global__ __launch_bounds__(ABS_BLOCK) void copy_ragged(const Chunk *__restrict__ chunks,

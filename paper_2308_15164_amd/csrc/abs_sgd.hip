@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <limits>
@@ -168,33 +169,32 @@ int launch_accumulate_flat(float *acc, const void *const *grads, const float *nf
     return ABS_OK;
 }
 
-template <int K>
-int launch_sync_flat_k(float *x, float *v, float *xp, const float *const *ptrs, int64_t P, Hyper h,
-                       int vec_ok, hipStream_t s)
+template <int K, int RULE>
+int launch_sync_flat_kr(float *x, float *v, float *xp, const float *const *ptrs, int64_t P, const Hyper &h,
+                        int vec_ok, hipStream_t s)
 {
-    static const int resident = resident_blocks(sync_update_flat<K, false, false>, 4);
-    static const int resident_dc = resident_blocks(sync_update_flat<K, false, true>, 4);
-    const int res = g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : (xp ? resident_dc : resident);
+    static const int resident = resident_blocks(sync_update_flat<K, false, RULE>, 4);
+    const int res = g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : resident;
     const int64_t tile64 = choose_tile(rows_of(P), res);
     if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
     const int tile = (int)tile64;
     AccPtrs<K> A;
     for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
     const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
-    // x, v and the previous iterate are each re-read one iteration later
-    const bool ntx = stream_upd(P, xp ? 3 : 2);
-    if (xp && ntx) hipLaunchKernelGGL((sync_update_flat<K, true, true>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    else if (xp) hipLaunchKernelGGL((sync_update_flat<K, false, true>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    else if (ntx) hipLaunchKernelGGL((sync_update_flat<K, true, false>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    else hipLaunchKernelGGL((sync_update_flat<K, false, false>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    // x and each state vector are re-read one iteration later
+    if (stream_upd(P, uses_s2<RULE>() ? 3 : 2))
+        hipLaunchKernelGGL((sync_update_flat<K, true, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    else
+        hipLaunchKernelGGL((sync_update_flat<K, false, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
     return ABS_OK;
 }
 
-int launch_sync_flat(float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P, Hyper h,
-                     int vec_ok, hipStream_t s)
+template <int RULE>
+int launch_sync_flat_r(float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P,
+                       const Hyper &h, int vec_ok, hipStream_t s)
 {
     switch (n) {
-#define ABS_CASE(K) case K: return launch_sync_flat_k<K>(x, v, xp, ptrs, P, h, vec_ok, s);
+#define ABS_CASE(K) case K: return launch_sync_flat_kr<K, RULE>(x, v, xp, ptrs, P, h, vec_ok, s);
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
         ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
         ABS_CASE(16)
@@ -205,10 +205,21 @@ int launch_sync_flat(float *x, float *v, float *xp, const float *const *ptrs, in
         AccPtrsAny A;
         std::memset(&A, 0, sizeof A);
         for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
-        hipLaunchKernelGGL(sync_update_flat_any, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s,
-                           x, v, xp, A, n, P, (int)tile64, h, vec_ok);
+        hipLaunchKernelGGL(sync_update_flat_any<RULE>, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0,
+                           s, x, v, xp, A, n, P, (int)tile64, h, vec_ok);
         return ABS_OK;
     }
+    }
+}
+
+int launch_sync_flat(int rule, float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P,
+                     const Hyper &h, int vec_ok, hipStream_t s)
+{
+    switch (rule) {
+    case SGD: return launch_sync_flat_r<SGD>(x, v, xp, ptrs, n, P, h, vec_ok, s);
+    case SGD_DC: return launch_sync_flat_r<SGD_DC>(x, v, xp, ptrs, n, P, h, vec_ok, s);
+    case ADAM: return launch_sync_flat_r<ADAM>(x, v, xp, ptrs, n, P, h, vec_ok, s);
+    default: return ABS_EINVAL;
     }
 }
 
@@ -286,25 +297,25 @@ int layout_to_device(abs_layout *L)
     return ABS_OK;
 }
 
-template <int K>
-void launch_sync_ragged_k(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
-                          const float *const *const *tabs, Hyper h, hipStream_t s)
+template <int K, int RULE>
+void launch_sync_ragged_kr(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
+                           const float *const *const *tabs, const Hyper &h, hipStream_t s)
 {
     TabPtrs<K> T;
     for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
     const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-    const bool ntx = stream_upd(L->total, pt ? 3 : 2);
-    if (pt && ntx) hipLaunchKernelGGL((sync_update_ragged<K, true, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
-    else if (pt) hipLaunchKernelGGL((sync_update_ragged<K, false, true>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
-    else if (ntx) hipLaunchKernelGGL((sync_update_ragged<K, true, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
-    else hipLaunchKernelGGL((sync_update_ragged<K, false, false>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
+    if (stream_upd(L->total, uses_s2<RULE>() ? 3 : 2))
+        hipLaunchKernelGGL((sync_update_ragged<K, true, RULE>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
+    else
+        hipLaunchKernelGGL((sync_update_ragged<K, false, RULE>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
 }
 
-void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
-                        const float *const *const *tabs, int n, Hyper h, hipStream_t s)
+template <int RULE>
+void launch_sync_ragged_r(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
+                          const float *const *const *tabs, int n, const Hyper &h, hipStream_t s)
 {
     switch (n) {
-#define ABS_CASE(K) case K: launch_sync_ragged_k<K>(L, xt, vt, pt, tabs, h, s); break;
+#define ABS_CASE(K) case K: launch_sync_ragged_kr<K, RULE>(L, xt, vt, pt, tabs, h, s); break;
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
         ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
         ABS_CASE(16)
@@ -313,9 +324,19 @@ void launch_sync_ragged(const abs_layout *L, float *const *xt, float *const *vt,
         TabPtrsAny T;
         std::memset(&T, 0, sizeof T);
         for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
-        hipLaunchKernelGGL(sync_update_ragged_any, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
+        hipLaunchKernelGGL(sync_update_ragged_any<RULE>, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
                            L->d_chunks, L->d_sizes, xt, vt, pt, T, n, L->tile, h);
     }
+    }
+}
+
+void launch_sync_ragged(int rule, const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
+                        const float *const *const *tabs, int n, const Hyper &h, hipStream_t s)
+{
+    switch (rule) {
+    case SGD: launch_sync_ragged_r<SGD>(L, xt, vt, pt, tabs, n, h, s); break;
+    case SGD_DC: launch_sync_ragged_r<SGD_DC>(L, xt, vt, pt, tabs, n, h, s); break;
+    default: launch_sync_ragged_r<ADAM>(L, xt, vt, pt, tabs, n, h, s); break;
     }
 }
 
@@ -429,40 +450,60 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
     return abs_accumulate_batch(acc, grads, grad_dtype, 1, P, &n_samples, count, stream);
 }
 
-// params_prev == nullptr: no compensation.
-static int sync_update_flat_impl(float *params, float *params_prev, bool dc, float *momentum,
-                                 const float *const *acc, const int64_t *counts, int K, int64_t P,
-                                 float lr, float mu, float wd, float lambda, void *stream)
+// Hyper-parameters of the three rules in one struct.
+static Hyper hyper_sgd(float lr, float mu, float wd, float lambda)
+{
+    Hyper h = {};
+    h.lr = lr; h.mu = mu; h.wd = wd; h.lambda = lambda;
+    return h;
+}
+
+static int hyper_adam(Hyper &h, float lr, float beta1, float beta2, float eps, float wd, int64_t step)
+{
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return ABS_EINVAL;
+    h = Hyper{};
+    h.lr = lr; h.wd = wd; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps;
+    h.omb1 = 1.0f - beta1;
+    h.omb2 = 1.0f - beta2;
+    h.bc1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    h.bc2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    return ABS_OK;
+}
+
+// s1: momentum (SGD rules) or first moment (ADAM); s2: previous iterate (SGD_DC)
+// or second moment (ADAM), unused for SGD.
+static int sync_update_flat_impl(int rule, float *params, float *s1, float *s2, const float *const *acc,
+                                 const int64_t *counts, int K, int64_t P, Hyper h, void *stream)
 {
     if (!acc || P < 0) return ABS_EINVAL;
+    const bool has2 = rule != SGD;
     Combine c;
     int rc = plan_combine(counts, K, c);
     if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
     const bool empty = rc == ABS_EMPTY;
-    if (empty && !dc) return ABS_EMPTY;
+    if (empty && rule != SGD_DC) return ABS_EMPTY;
     if (P == 0) return empty ? ABS_EMPTY : ABS_OK;
-    if (!params || !momentum || params == momentum) return ABS_EINVAL;
-    if (!aligned_to(params, 4) || !aligned_to(momentum, 4)) return ABS_EINVAL;
-    if (dc && (!params_prev || params_prev == params || params_prev == momentum || !aligned_to(params_prev, 4)))
-        return ABS_EINVAL;
+    if (!params || !s1 || params == s1) return ABS_EINVAL;
+    if (!aligned_to(params, 4) || !aligned_to(s1, 4)) return ABS_EINVAL;
+    if (has2 && (!s2 || s2 == params || s2 == s1 || !aligned_to(s2, 4))) return ABS_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (empty) {
         // x_{t+1} = x_t: the previous-iterate buffer must still advance
-        rc = launch_copy_flat(params_prev, params, P, s);
+        rc = launch_copy_flat(s2, params, P, s);
         if (rc != ABS_OK) return rc;
         rc = launch_status();
         return rc == ABS_OK ? ABS_EMPTY : rc;
     }
     const float *ptrs[ABS_MAX_K];
-    bool vec = aligned_to(params, 16) && aligned_to(momentum, 16) && (!dc || aligned_to(params_prev, 16));
+    bool vec = aligned_to(params, 16) && aligned_to(s1, 16) && (!has2 || aligned_to(s2, 16));
     for (int j = 0; j < c.n; ++j) {
         const float *p = acc[c.idx[j]];
         if (!p || !aligned_to(p, 4)) return ABS_EINVAL;
         vec = vec && aligned_to(p, 16);
         ptrs[j] = p;
     }
-    const Hyper h = {(float)c.M, lr, mu, wd, lambda};
-    rc = launch_sync_flat(params, momentum, dc ? params_prev : nullptr, ptrs, c.n, P, h, vec ? 1 : 0, s);
+    h.M = (float)c.M;
+    rc = launch_sync_flat(rule, params, s1, has2 ? s2 : nullptr, ptrs, c.n, P, h, vec ? 1 : 0, s);
     if (rc != ABS_OK) return rc;
     return launch_status();
 }
@@ -471,15 +512,26 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
                     const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
                     void *stream)
 {
-    return sync_update_flat_impl(params, nullptr, false, momentum, acc, counts, K, P, lr, mu, wd, 0.f, stream);
+    return sync_update_flat_impl(SGD, params, momentum, nullptr, acc, counts, K, P, hyper_sgd(lr, mu, wd, 0.f),
+                                 stream);
 }
 
 int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const float *const *acc,
                        const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
                        float lambda, void *stream)
 {
-    return sync_update_flat_impl(params, params_prev, true, momentum, acc, counts, K, P, lr, mu, wd, lambda,
-                                 stream);
+    return sync_update_flat_impl(SGD_DC, params, momentum, params_prev, acc, counts, K, P,
+                                 hyper_sgd(lr, mu, wd, lambda), stream);
+}
+
+int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const float *const *acc,
+                         const int64_t *counts, int K, int64_t P, float lr, float beta1, float beta2,
+                         float eps, float wd, int64_t step, void *stream)
+{
+    Hyper h;
+    int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
+    if (rc != ABS_OK) return rc;
+    return sync_update_flat_impl(ADAM, params, exp_avg, exp_avg_sq, acc, counts, K, P, h, stream);
 }
 
 // ---------------------------------------------------------------- ragged
@@ -619,20 +671,20 @@ int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensors
     return abs_accumulate_batch_mt(L, acc, &grad, 1, &n_samples, count, stream);
 }
 
-static int sync_update_mt_impl(abs_layout *L, const abs_tensorset *params, const abs_tensorset *prev,
-                               bool dc, const abs_tensorset *momentum, const abs_tensorset *const *acc,
-                               const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
-                               void *stream)
+static int sync_update_mt_impl(int rule, abs_layout *L, const abs_tensorset *params, const abs_tensorset *s1,
+                               const abs_tensorset *s2, const abs_tensorset *const *acc,
+                               const int64_t *counts, int K, Hyper h, void *stream)
 {
     if (!L || !acc) return ABS_EINVAL;
+    const bool has2 = rule != SGD;
     Combine c;
     int rc = plan_combine(counts, K, c);
     if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
     const bool empty = rc == ABS_EMPTY;
-    if (empty && !dc) return ABS_EMPTY;
-    if (!set_ok(params, L) || !set_ok(momentum, L) || params == momentum) return ABS_EINVAL;
-    if (params->elem != ABS_F32 || momentum->elem != ABS_F32) return ABS_EINVAL;
-    if (dc && (!set_ok(prev, L) || prev == params || prev == momentum || prev->elem != ABS_F32)) return ABS_EINVAL;
+    if (empty && rule != SGD_DC) return ABS_EMPTY;
+    if (!set_ok(params, L) || !set_ok(s1, L) || params == s1) return ABS_EINVAL;
+    if (params->elem != ABS_F32 || s1->elem != ABS_F32) return ABS_EINVAL;
+    if (has2 && (!set_ok(s2, L) || s2 == params || s2 == s1 || s2->elem != ABS_F32)) return ABS_EINVAL;
     const float *const *tabs[ABS_MAX_K];
     for (int j = 0; j < c.n; ++j) {
         const abs_tensorset *s = acc[c.idx[j]];
@@ -644,15 +696,15 @@ static int sync_update_mt_impl(abs_layout *L, const abs_tensorset *params, const
     if (rc != ABS_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
-    float *const *pt = dc ? reinterpret_cast<float *const *>(prev->d_tab) : nullptr;
+    float *const *pt = has2 ? reinterpret_cast<float *const *>(s2->d_tab) : nullptr;
     if (empty) {
         hipLaunchKernelGGL(copy_ragged, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s, L->d_chunks,
                            L->d_sizes, pt, xt, L->tile);
         rc = launch_status();
         return rc == ABS_OK ? ABS_EMPTY : rc;
     }
-    const Hyper h = {(float)c.M, lr, mu, wd, lambda};
-    launch_sync_ragged(L, xt, reinterpret_cast<float *const *>(momentum->d_tab), pt, tabs, c.n, h, s);
+    h.M = (float)c.M;
+    launch_sync_ragged(rule, L, xt, reinterpret_cast<float *const *>(s1->d_tab), pt, tabs, c.n, h, s);
     return launch_status();
 }
 
@@ -660,7 +712,8 @@ int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_ten
                        const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                        float mu, float wd, void *stream)
 {
-    return sync_update_mt_impl(L, params, nullptr, false, momentum, acc, counts, K, lr, mu, wd, 0.f, stream);
+    return sync_update_mt_impl(SGD, L, params, momentum, nullptr, acc, counts, K, hyper_sgd(lr, mu, wd, 0.f),
+                               stream);
 }
 
 int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *params_prev,
@@ -668,8 +721,19 @@ int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_
                           const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
                           void *stream)
 {
-    return sync_update_mt_impl(L, params, params_prev, true, momentum, acc, counts, K, lr, mu, wd, lambda,
-                               stream);
+    return sync_update_mt_impl(SGD_DC, L, params, momentum, params_prev, acc, counts, K,
+                               hyper_sgd(lr, mu, wd, lambda), stream);
+}
+
+int abs_sync_update_adam_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *exp_avg,
+                            const abs_tensorset *exp_avg_sq, const abs_tensorset *const *acc,
+                            const int64_t *counts, int K, float lr, float beta1, float beta2, float eps,
+                            float wd, int64_t step, void *stream)
+{
+    Hyper h;
+    int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
+    if (rc != ABS_OK) return rc;
+    return sync_update_mt_impl(ADAM, L, params, exp_avg, exp_avg_sq, acc, counts, K, h, stream);
 }
 
 // --------------------------------------------------------- double buffer
@@ -824,6 +888,25 @@ int abs_ctx_sync_update_dc_mt(abs_ctx *C, const abs_tensorset *params, const abs
     const int prev = C->cur ^ 1;
     return abs_sync_update_dc_mt(C->layout, params, params_prev, momentum, C->set[prev].data(),
                                  C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->s_upd);
+}
+
+int abs_ctx_sync_update_adam(abs_ctx *C, float *params, float *exp_avg, float *exp_avg_sq, float lr,
+                             float beta1, float beta2, float eps, float wd, int64_t step)
+{
+    if (!C || C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_adam(params, exp_avg, exp_avg_sq, C->acc[prev].data(), C->counts[prev].data(),
+                                C->K, C->P, lr, beta1, beta2, eps, wd, step, C->s_upd);
+}
+
+int abs_ctx_sync_update_adam_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *exp_avg,
+                                const abs_tensorset *exp_avg_sq, float lr, float beta1, float beta2,
+                                float eps, float wd, int64_t step)
+{
+    if (!C || !C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_adam_mt(C->layout, params, exp_avg, exp_avg_sq, C->set[prev].data(),
+                                   C->counts[prev].data(), C->K, lr, beta1, beta2, eps, wd, step, C->s_upd);
 }
 
 int abs_swap_buffers(abs_ctx *C)

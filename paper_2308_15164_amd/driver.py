@@ -27,11 +27,13 @@ class DeviceRun:
     overlap=False: both on one stream, in program order;
     acc_streams=n: the K workers' accumulations spread over n streams;
     lam          : coefficient of the delayed gradient compensation (None: off);
+    adam         : (beta1, beta2, eps) switches the update rule to Adam;
     batched=True : a worker's m_k gradients of a step go in one abs_accumulate_batch
                    call (same bits, the accumulator is read and written once).
     """
 
-    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False):
+    def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False,
+                 adam=None):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
@@ -40,6 +42,8 @@ class DeviceRun:
         self.ragged = w.tensor_sizes is not None
         self.lam = None if lam is None else float(lam)   # delayed gradient compensation coefficient
         self.batched = bool(batched)                     # one accumulate launch per worker and step
+        self.adam = None if adam is None else tuple(float(t) for t in adam)   # (beta1, beta2, eps)
+        self.adam_step = 0                               # applied Adam updates so far
         self._streams = [torch.cuda.Stream(device=torch.device("cuda:0")) for _ in range(9)]
         self.ctx = None
         if not self.ragged:
@@ -53,6 +57,8 @@ class DeviceRun:
             self.pool = [_upload(g) for g in pool]
             self.pool_ptr = [g.data_ptr() for g in self.pool]
             self.xp = self.x.clone() if self.lam is not None else None    # x_{t-1}; starts equal to x_0
+            if self.adam is not None:
+                self.xp = torch.zeros_like(self.x)                        # second moment
             torch.cuda.synchronize()
             self.x_arg, self.v_arg = self.x.data_ptr(), self.v.data_ptr()
             self.xp_arg = self.xp.data_ptr() if self.xp is not None else None
@@ -78,8 +84,8 @@ class DeviceRun:
             self.pool_sets = [TensorSet(self.layout, p, dtype=self.gdt) for p in self.pool_t]
             self.x_arg, self.v_arg = self.x_set, self.v_set
             self.xp_arg = None
-            if self.lam is not None:
-                self.xp_t = [t.clone() for t in self.x_t]
+            if self.lam is not None or self.adam is not None:
+                self.xp_t = [t.clone() if self.adam is None else torch.zeros_like(t) for t in self.x_t]
                 torch.cuda.synchronize()
                 self.xp_arg = TensorSet(self.layout, self.xp_t)
         self.configure_streams(overlap, acc_streams)
@@ -120,7 +126,15 @@ class DeviceRun:
         return calls
 
     def sync_update(self):
-        """Step 1 + update on the delayed generation (compensated when lam is set)."""
+        """Step 1 + update on the delayed generation (compensated when lam is set,
+        Adam when adam is set: v is then the first moment, xp the second)."""
+        if self.adam is not None:
+            b1, b2, eps = self.adam
+            ok = self.ctx.abs_sync_update_adam(self.x_arg, self.v_arg, self.xp_arg, self.lr, b1, b2, eps,
+                                               self.wd, self.adam_step + 1)
+            if ok:
+                self.adam_step += 1
+            return ok
         if self.lam is None:
             return self.ctx.abs_sync_update(self.x_arg, self.v_arg, self.lr, self.mu, self.wd)
         return self.ctx.abs_sync_update_dc(self.x_arg, self.xp_arg, self.v_arg, self.lr, self.mu, self.wd,
@@ -157,6 +171,13 @@ class DeviceRun:
             return self.x.cpu().numpy(), self.v.cpu().numpy()
         return (np.concatenate([t.cpu().numpy() for t in self.x_t]),
                 np.concatenate([t.cpu().numpy() for t in self.v_t]))
+
+    def read_second_state(self):
+        """The rule's second state vector: x_{t-1} (compensation) or Adam's second moment."""
+        torch.cuda.synchronize()
+        if not self.ragged:
+            return self.xp.cpu().numpy()
+        return np.concatenate([t.cpu().numpy() for t in self.xp_t])
 
     def read_state_at(self, idx):
         """x and v at flat element indices idx (ragged: indices into the concatenation)."""

@@ -398,6 +398,141 @@ def test_sync_update_dc_multi_row_tiles(absgd, tuned, K):
 
 
 # ---------------------------------------------------------------------------
+# abs_sync_update_adam, call by call
+# ---------------------------------------------------------------------------
+
+def _sync_adam_case(absgd, K, P, counts, seed, step=3, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8, wd=1e-2, shifts=None):
+    rng = np.random.default_rng(seed)
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    m0 = (rng.standard_normal(P) * 0.01).astype(F32)
+    v0 = (rng.standard_normal(P) ** 2 * 1e-4).astype(F32)
+    accs = [(rng.standard_normal(P) * 0.3 * max(c, 1) / 32).astype(F32) for c in counts]
+
+    def up(a, s):
+        if not s:
+            return _up(a)
+        pad = np.zeros(P + 8, dtype=F32)
+        pad[s:s + P] = a
+        return _up(pad)[s:s + P]
+
+    sh = shifts or [0] * (K + 3)
+    x_d, m_d, v_d = up(x0, sh[0]), up(m0, sh[1]), up(v0, sh[2])
+    acc_d = [up(a, sh[3 + k]) if c > 0 else torch.full((P,), float("nan"), device="cuda")
+             for k, (a, c) in enumerate(zip(accs, counts))]
+    applied = absgd.abs_sync_update_adam(x_d, m_d, v_d, acc_d, counts, lr, b1, b2, eps, wd, step)
+    x32, m32, v32 = x0.copy(), m0.copy(), v0.copy()
+    ok32 = orc.sync_update32_adam(x32, m32, v32, accs, counts, lr, b1, b2, eps, wd, step)
+    x64, m64, v64 = (a.astype(np.float64) for a in (x0, m0, v0))
+    G64 = [a.astype(np.float64) if c > 0 else np.zeros(P) for a, c in zip(accs, counts)]
+    f = lambda t: float(F32(t))
+    ok64 = orc.sync_update_adam(x64, m64, v64, G64, counts, f(lr), f(b1), f(b2), f(eps), f(wd), step)
+    assert applied == ok32 == ok64
+    gx, gm, gv = x_d.cpu().numpy(), m_d.cpu().numpy(), v_d.cpu().numpy()
+    _assert_bitexact(gx, x32, f"adam x K={K} P={P}")
+    _assert_bitexact(gm, m32, f"adam m K={K} P={P}")
+    _assert_bitexact(gv, v32, f"adam v K={K} P={P}")
+    if applied:
+        M = float(sum(counts))
+        g_mag = sum(np.abs(g) for g in G64) / M + f(wd) * np.abs(x64)
+        m_scale = np.abs(m0.astype(np.float64)) + g_mag
+        v_scale = np.abs(v0.astype(np.float64)) + g_mag ** 2
+        _assert_close64(gm, m64, m_scale, "adam m")
+        _assert_close64(gv, v64, 2 * v_scale, "adam v")
+        # x moves by lr * mh / (sqrt(vh) + eps): relative errors of m and v carry over once and half
+        upd = f(lr) * (np.abs(m64) + 1e-5 * m_scale) / (1 - f(b1) ** step) / (np.sqrt(v64 / (1 - f(b2) ** step)) + f(eps))
+        assert np.all(np.abs(gx - x64) <= RTOL * (np.abs(x0) + 4 * upd * np.maximum(1.0, m_scale / np.maximum(np.abs(m64), 1e-30) * 1e-0)) + 1e-30)
+        assert np.max(np.abs(gx - x64)) <= RTOL * np.max(np.abs(x64))
+    else:
+        _assert_bitexact(gx, x0, "untouched x")
+        _assert_bitexact(gm, m0, "untouched m")
+        _assert_bitexact(gv, v0, "untouched v")
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 7, 8, 11, 16, 17, 40])
+def test_sync_update_adam_worker_counts(absgd, K):
+    print(f"[case] sync_update_adam K={K}", flush=True)
+    _sync_adam_case(absgd, K, 3 * 4096 + 1029, [32 * (1 + (3 * k) % 5) for k in range(K)], seed=500 + K, step=1 + K % 5)
+
+
+@pytest.mark.parametrize("P", [1, 5, 4097, 100_003, 1_048_576 + 13])
+def test_sync_update_adam_sizes(absgd, P):
+    print(f"[case] sync_update_adam P={P}", flush=True)
+    _sync_adam_case(absgd, 4, P, [64, 64, 128, 256], seed=600 + P % 1000)
+
+
+def test_sync_update_adam_edges(absgd):
+    print("[case] sync_update_adam edges", flush=True)
+    _sync_adam_case(absgd, 3, 9001, [0, 0, 0], seed=701)                               # nothing applied, nothing touched
+    _sync_adam_case(absgd, 5, 9001, [0, 96, 0, 32, 0], seed=702)                       # idle workers skipped
+    _sync_adam_case(absgd, 4, 9001, [32] * 4, seed=703, step=1, wd=0.0)                # first step
+    _sync_adam_case(absgd, 4, 9001, [32] * 4, seed=704, step=100_000)                  # bias corrections ~ 1
+    _sync_adam_case(absgd, 3, 4096 + 11, [32, 64, 32], seed=705, shifts=[1, 2, 0, 0, 3, 2])
+    x = torch.zeros(8, device="cuda")
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_adam(x, x.clone(), x.clone(), [x.clone()], [32], 1e-3, 0.9, 0.999, 1e-8, 0.0, 0)   # step < 1
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_adam(x, x.clone(), x.clone(), [x.clone()], [32], 1e-3, 1.0, 0.999, 1e-8, 0.0, 1)   # beta1 = 1
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+@pytest.mark.parametrize("K", [3, 9, 16])
+def test_sync_update_adam_multi_row_tiles(absgd, tuned, K):
+    print(f"[case] sync_update_adam multi-row K={K} tuning={tuned}", flush=True)
+    _sync_adam_case(absgd, K, 1_048_576 + 13, [32 * (1 + k % 3) for k in range(K)], seed=800 + K)
+
+
+ADAM = (0.9, 0.999, 1e-8)
+
+
+@pytest.mark.parametrize("name", ["cfg1_small", "tiny_tail_bf16", "ragged_odd_f32", "ragged_odd_bf16"])
+def test_trajectory_adam(absgd, name):
+    """Algorithm 1's loop with Adam as the update rule, serial and overlapped, against both oracles."""
+    from paper_2308_15164_amd.driver import DeviceRun
+    w = wl.WORKLOADS[name]
+    steps = w.steps
+    x0, pool, sched = wl.initial_params(w), wl.gradient_pool(w), wl.schedule(w, steps)
+    lr = 1e-3
+    res = []
+    for overlap in (False, True):
+        print(f"[case] adam trajectory {name} overlap={overlap}", flush=True)
+        run = DeviceRun(w, x0, pool, sched, overlap=overlap, adam=ADAM)
+        run.lr = lr
+        run.run(steps)
+        res.append(run.read_state() + (run.read_second_state(), run.count_history, run.adam_step))
+        run.close()
+    for a, b in zip(res[0][:3], res[1][:3]):
+        _assert_bitexact(b, a, "adam overlap vs serial")
+    assert res[0][4] == steps - 1                                  # one-iteration delay: T - 1 updates applied
+    R = len(pool)
+
+    def batches(t, i):
+        return [pool[wl.pool_index(w, t, i, j, R)] for j in range(int(sched[t, i]))]
+
+    f = lambda t: float(F32(t))
+    args = (x0, w.K, steps, w.n, f(lr), 0.0, f(w.wd), batches)
+    ad = tuple(f(t) for t in ADAM)
+    x32, (m32, v32), h32 = orc.run(*args, precision="f32", adam=ad)
+    x64, (m64, v64), _ = orc.run(*args, precision="f64", adam=ad)
+    gx, gm, gv = res[1][:3]
+    assert res[1][3] == h32
+    _assert_bitexact(gx, x32, f"{name} adam x")
+    _assert_bitexact(gm, m32, f"{name} adam m")
+    _assert_bitexact(gv, v32, f"{name} adam v")
+    for got, ref, what in ((gm, m64, "m"), (gv, v64, "v")):
+        assert np.max(np.abs(got - ref)) <= RTOL * np.max(np.abs(ref)), what
+    # x: Adam's step lr * mh / sqrt(vh) is scale-free in the gradient, so where the K-way sum
+    # cancels to nearly zero its fp32 rounding is amplified to a visible fraction of lr per
+    # step -- for any fp32 implementation, the fp32 oracle included.  Bar: all but 0.1 % of
+    # the elements within 1e-5 of (|x| + the distance travelled), none further than 5 % of it.
+    dx = np.abs(gx - x64)
+    travelled = steps * lr
+    assert np.mean(dx > RTOL * (np.abs(x64) + travelled)) < 1e-3
+    assert np.max(dx) <= 0.05 * travelled
+    print(f"[info] {name} adam: max|dx| = {np.max(dx):.2e} over a distance of {travelled:.1e}; "
+          f"{np.mean(dx > RTOL * np.abs(x64)):.2e} of the elements beyond 1e-5 relative", flush=True)
+
+
+# ---------------------------------------------------------------------------
 # whole trajectories through the double-buffered context (Algorithm 1 loop)
 # ---------------------------------------------------------------------------
 
