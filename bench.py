@@ -29,6 +29,8 @@ MEASURED_TRAFFIC = {
     # FETCH_SIZE x 2.000 = 81.88 MB, WRITE_SIZE x 1.000 = 46.75 MB per launch (average over
     # the 12 read-modify-write and 4 overwrite launches of a step)
     ("cfg2_resnet18", "absk::accumulate_flat<false, *, 1>"): 128.63e6,
+    # cfg4: 923.7 MB fetched + 553.4 MB written per launch (schedule average)
+    ("cfg4_vgg16", "absk::accumulate_flat<false, *, 1>"): 1477.1e6,
 }
 
 

@@ -6,7 +6,8 @@
 //     consecutive memory per instruction; a workgroup "row" is BLOCK such
 //     vectors (ROW elements);
 //   * a workgroup owns one tile = a run of consecutive rows and walks it in
-//     groups of U rows, issuing ALL loads of a group before the first use;
+//     groups of 4 rows, issuing the loads of a group before the first use (the
+//     K-way read of sync-update in batches of up to 4 workers);
 //   * the host picks the tile size per launch so that the grid is a whole
 //     number of resident rounds (256 CUs x resident workgroups per CU): every
 //     CU then finishes together instead of idling behind a ragged last round,
@@ -42,8 +43,11 @@
 #ifndef ABS_NT_SYNC_ACC
 #define ABS_NT_SYNC_ACC 1      // accumulator loads in sync-update (dead afterwards)
 #endif
+#ifndef ABS_SYNC_ROWS
+#define ABS_SYNC_ROWS 4        // rows per group in sync-update
+#endif
 #ifndef ABS_SYNC_INFLIGHT
-#define ABS_SYNC_INFLIGHT 24   // target number of 128-bit loads in flight per lane in sync-update
+#define ABS_SYNC_INFLIGHT 24   // 128-bit loads in flight per lane in sync-update (bounds the workers per load batch)
 #endif
 
 namespace absk {
@@ -126,11 +130,27 @@ struct GradArgs {
     float n[J];
 };
 
-// rows per group: keep about 8-10 loads of 128 bits (64 for bf16) in flight per lane
+// Rows per group and gradients whose loads are issued together.  One gradient per
+// launch: 4 rows (8 loads in flight per lane).  Several: 2 rows and all of them at
+// once (up to 18 loads); measured best among 1-4 rows x 2-8 gradients per batch.
+#ifndef ABS_ACCB_BATCH
+#define ABS_ACCB_BATCH 8       // gradients per load batch when a launch folds in several
+#endif
+#ifndef ABS_ACCB_ROWS
+#define ABS_ACCB_ROWS 2        // rows per group when a launch folds in several gradients
+#endif
 template <int J>
-constexpr int acc_unroll()
+constexpr int acc_batch() { return J < ABS_ACCB_BATCH ? J : ABS_ACCB_BATCH; }
+template <int J>
+constexpr int acc_rows() { return J == 1 ? ABS_ACC_UNROLL : ABS_ACCB_ROWS; }
+
+// r = first ? n_0*g_0 : fma(n_0, g_0, a)   -- only for the first gradient of a chain
+// r = fma(n_j, g_j, r)                     -- for the rest
+__device__ __forceinline__ f32x4 fma_vec(float n, f32x4 g, f32x4 r)
 {
-    return J <= 1 ? ABS_ACC_UNROLL : (J == 2 ? 3 : (J <= 4 ? 2 : 1));
+    r.x = __builtin_fmaf(n, g.x, r.x); r.y = __builtin_fmaf(n, g.y, r.y);
+    r.z = __builtin_fmaf(n, g.z, r.z); r.w = __builtin_fmaf(n, g.w, r.w);
+    return r;
 }
 
 template <int J>
@@ -142,16 +162,60 @@ __device__ __forceinline__ float acc_chain(bool first, const float (&n)[J], cons
     return r;
 }
 
-template <int J>
-__device__ __forceinline__ f32x4 acc_chain_vec(bool first, const float (&n)[J], const f32x4 (&g)[J], f32x4 a)
+// One group of U rows starting at vector g0.  WHOLE: the group lies inside the
+// tile and needs no bounds checks (straight-line code: loads, then stores).
+template <bool BF16, bool NTA, int J, bool WHOLE>
+__device__ __forceinline__ void accumulate_group(f32x4 *__restrict__ av, const GradArgs<BF16, J> &G, int g0,
+                                                 int nvec, int tid, bool first)
 {
-    f32x4 r = acc_vec(first, n[0], g[0], a);
+    typedef typename GradT<BF16>::vec gvec;
+    constexpr int U = acc_rows<J>();
+    constexpr int JC = acc_batch<J>();
+    f32x4 g[U][JC] = {}, r[U] = {};
 #pragma unroll
-    for (int j = 1; j < J; ++j) {
-        r.x = __builtin_fmaf(n[j], g[j].x, r.x); r.y = __builtin_fmaf(n[j], g[j].y, r.y);
-        r.z = __builtin_fmaf(n[j], g[j].z, r.z); r.w = __builtin_fmaf(n[j], g[j].w, r.w);
+    for (int u = 0; u < U; ++u) {
+        const int i = g0 + u * BLOCK + tid;
+        if (WHOLE || i < nvec) {
+#pragma unroll
+            for (int j = 0; j < JC; ++j) g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + i);
+        }
     }
-    return r;
+    if (!first) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = g0 + u * BLOCK + tid;
+            if (WHOLE || i < nvec) r[u] = ld<NTA>(av + i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        r[u] = acc_vec(first, G.n[0], g[u][0], r[u]);
+#pragma unroll
+        for (int j = 1; j < JC; ++j) r[u] = fma_vec(G.n[j], g[u][j], r[u]);
+    }
+    // remaining gradients in batches of JC, in order
+#pragma unroll
+    for (int j0 = JC; j0 < J; j0 += JC) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = g0 + u * BLOCK + tid;
+            if (WHOLE || i < nvec) {
+#pragma unroll
+                for (int j = 0; j < JC; ++j)
+                    if (j0 + j < J) g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j0 + j]) + i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < JC; ++j)
+                if (j0 + j < J) r[u] = fma_vec(G.n[j0 + j], g[u][j], r[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = g0 + u * BLOCK + tid;
+        if (WHOLE || i < nvec) st<NTA>(av + i, r[u]);
+    }
 }
 
 // One workgroup, one tile: acc[0..len) (+)= sum_j n_j * grad_j[0..len), in order.
@@ -160,8 +224,7 @@ template <bool BF16, bool NTA, int J>
 __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc, const GradArgs<BF16, J> &G,
                                                 int len, bool first, bool vec_ok)
 {
-    typedef typename GradT<BF16>::vec gvec;
-    constexpr int U = acc_unroll<J>();
+    constexpr int U = acc_rows<J>();
     const int tid = threadIdx.x;
     if (!vec_ok) {
         for (int i = tid; i < len; i += BLOCK) {
@@ -175,46 +238,8 @@ __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc, const G
     f32x4 *av = reinterpret_cast<f32x4 *>(acc);
     const int nvec = len / VEC;
     int g0 = 0;
-    // whole groups of U rows: no bounds checks, every load issued before the first store
-    for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) {
-        f32x4 g[U][J], a[U] = {};
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < J; ++j)
-                g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + g0 + u * BLOCK + tid);
-        if (!first) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) a[u] = ld<NTA>(av + g0 + u * BLOCK + tid);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            st<NTA>(av + g0 + u * BLOCK + tid, acc_chain_vec<J>(first, G.n, g[u], a[u]));
-    }
-    // last, partial group
-    if (g0 < nvec) {
-        f32x4 g[U][J] = {}, a[U] = {};
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
-            if (i < nvec) {
-#pragma unroll
-                for (int j = 0; j < J; ++j) g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + i);
-            }
-        }
-        if (!first) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
-                if (i < nvec) a[u] = ld<NTA>(av + i);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
-            if (i < nvec) st<NTA>(av + i, acc_chain_vec<J>(first, G.n, g[u], a[u]));
-        }
-    }
+    for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) accumulate_group<BF16, NTA, J, true>(av, G, g0, nvec, tid, first);
+    if (g0 < nvec) accumulate_group<BF16, NTA, J, false>(av, G, g0, nvec, tid, first);
     const int i = nvec * VEC + tid;          // at most VEC-1 trailing elements
     if (i < len) {
         float g[J];
@@ -295,12 +320,17 @@ __device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &s1, f32x4 &
 
 template <int K> struct AccPtrs { const float *p[K]; };
 
-// rows per group so that about ABS_SYNC_INFLIGHT loads are outstanding per lane
+// Workers whose accumulators are loaded together.  A group always spans
+// ABS_SYNC_ROWS rows, so every wavefront reads ABS_SYNC_ROWS KiB of consecutive
+// memory per stream; with many workers the K-way read is cut into batches of KC
+// so that about ABS_SYNC_INFLIGHT loads are outstanding per lane.  Measured at
+// P = 1.2e8, K = 16: 4 rows x 4 workers at a time reach 5.8 TB/s, 1 row x 16
+// workers 5.1 TB/s.  The sum still runs over the workers in ascending order.
 template <int K, int RULE>
-constexpr int sync_unroll()
+constexpr int sync_batch()
 {
-    int u = ABS_SYNC_INFLIGHT / (K + 2 + (uses_s2<RULE>() ? 1 : 0));
-    return u < 1 ? 1 : (u > 4 ? 4 : u);
+    int kc = ABS_SYNC_INFLIGHT / ABS_SYNC_ROWS - 2 - (uses_s2<RULE>() ? 1 : 0);
+    return kc < 1 ? 1 : (kc > K ? K : kc);
 }
 
 // One workgroup, one tile of the fused combine + update; K compile-time.
@@ -312,7 +342,7 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
                                           const Hyper &h, bool vec_ok)
 {
     constexpr bool S2 = uses_s2<RULE>();
-    constexpr int U = sync_unroll<K, RULE>();
+    constexpr int U = ABS_SYNC_ROWS;
     const int tid = threadIdx.x;
     if (!vec_ok) {
         for (int i = tid; i < len; i += BLOCK) {
@@ -331,12 +361,13 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
     const int nvec = len / VEC;
     int g0 = 0;
     for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) {
-        f32x4 a[U][K], xr[U], vr[U], pr[U] = {};
+        constexpr int KC = sync_batch<K, RULE>();
+        f32x4 a[U][KC], sum[U], xr[U], vr[U], pr[U] = {};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = g0 + u * BLOCK + tid;
 #pragma unroll
-            for (int k = 0; k < K; ++k)
+            for (int k = 0; k < KC; ++k)
                 a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
             xr[u] = ld<NTX>(xv + i);
             vr[u] = ld<NTX>(vv + i);
@@ -344,10 +375,30 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
-            f32x4 s = a[u][0];
+            sum[u] = a[u][0];
 #pragma unroll
-            for (int k = 1; k < K; ++k) s = s + a[u][k];
+            for (int k = 1; k < KC; ++k) sum[u] = sum[u] + a[u][k];
+        }
+        // remaining workers in batches of KC, still in ascending order
+#pragma unroll
+        for (int k0 = KC; k0 < K; k0 += KC) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = g0 + u * BLOCK + tid;
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k0 + k < K) a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k0 + k]) + i);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k0 + k < K) sum[u] = sum[u] + a[u][k];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = g0 + u * BLOCK + tid;
+            f32x4 s = sum[u];
             update_vec<RULE>(s, xr[u], vr[u], pr[u], h);
             st<NTX>(vv + i, vr[u]);
             if constexpr (S2) st<NTX>(pv + i, pr[u]);
