@@ -102,7 +102,9 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
  *
  *   grads      HOST array of J DEVICE pointers, each P elements of grad_dtype
  *   n_samples  HOST array of J sample counts (each > 0);  *count += their sum
- *   Errors as abs_accumulate; J < 1 is EINVAL. */
+ *   Errors as abs_accumulate; J < 1 is EINVAL.  If a HIP error stops a call that
+ *   needed several launches, earlier launches have already been enqueued and
+ *   *count is left unchanged: treat the accumulator as undefined. */
 int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dtype, int J,
                          int64_t P, const int64_t *n_samples, int64_t *count, void *stream);
 

@@ -61,11 +61,25 @@ constexpr int64_t kMaxTile = int64_t(1) << 30;   // tile sizes travel as int
 // covers n rows in `rounds` rounds, rounds being the fewest that keep a tile
 // within g_max_rows rows (0 = no limit: always one round, every workgroup
 // walks one long run of memory).  Measured on MI355X: short tiles (<= 4 rows,
-// many rounds) beat long per-workgroup runs by 5-20 % once P exceeds ~30 M,
-// because all resident workgroups then sweep one compact window of memory.
-constexpr int kCUs = 256;                 // MI355X
-int g_blocks_per_cu = 0;                  // 0 = ask the runtime per kernel
+// many rounds) beat long per-workgroup runs by 15-20 % at P >= 1e8, because all
+// resident workgroups then sweep one compact window of memory.
+int g_blocks_per_cu = 0;                  // 0 = what each kernel's register use allows
 int g_max_rows = ABS_MAX_ROWS;
+
+// Compute units of the current device; 256 (MI355X) when no device can be asked,
+// e.g. when a layout is built on a host without a GPU.
+int cu_count()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            return cus;
+        (void)hipGetLastError();
+        return 256;
+    }();
+    return n;
+}
 
 inline int64_t rows_of(int64_t P) { return (P + ROW - 1) / ROW; }
 
@@ -80,22 +94,22 @@ int64_t choose_tile(int64_t rows, int resident)
 
 inline int64_t tiles_for(int64_t P, int64_t tile) { return (P + tile - 1) / tile; }
 
-// Workgroups of `kernel` that fit on the chip at once.
+// Workgroups of `kernel` one CU can hold, from the runtime's occupancy calculator.
 template <class Kernel>
-int resident_blocks(Kernel kernel, int fallback_per_cu)
+int occupancy_per_cu(Kernel kernel, int fallback)
 {
-    int per_cu = g_blocks_per_cu;
-    if (per_cu <= 0) {
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, BLOCK, 0) == hipSuccess && n > 0) per_cu = n;
-        else { (void)hipGetLastError(); per_cu = fallback_per_cu; }
-    }
-    return per_cu * kCUs;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, BLOCK, 0) == hipSuccess && n > 0) return n;
+    (void)hipGetLastError();
+    return fallback;
 }
+
+// Workgroups resident on the whole chip, with the caller's override applied.
+inline int resident(int per_cu) { return (g_blocks_per_cu > 0 ? g_blocks_per_cu : per_cu) * cu_count(); }
 
 // The accumulate kernels need few registers: 8 workgroups of 4 wavefronts per CU.
 constexpr int kAccBlocksPerCU = 8;
-inline int acc_resident() { return (g_blocks_per_cu > 0 ? g_blocks_per_cu : kAccBlocksPerCU) * kCUs; }
+inline int acc_resident() { return resident(kAccBlocksPerCU); }
 
 // counts -> compacted list of non-empty workers and their total.
 struct Combine {
@@ -173,9 +187,8 @@ template <int K, int RULE>
 int launch_sync_flat_kr(float *x, float *v, float *xp, const float *const *ptrs, int64_t P, const Hyper &h,
                         int vec_ok, hipStream_t s)
 {
-    static const int resident = resident_blocks(sync_update_flat<K, false, RULE>, 4);
-    const int res = g_blocks_per_cu > 0 ? g_blocks_per_cu * kCUs : resident;
-    const int64_t tile64 = choose_tile(rows_of(P), res);
+    static const int per_cu = occupancy_per_cu(sync_update_flat<K, false, RULE>, 4);
+    const int64_t tile64 = choose_tile(rows_of(P), resident(per_cu));
     if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
     const int tile = (int)tile64;
     AccPtrs<K> A;
@@ -200,7 +213,7 @@ int launch_sync_flat_r(float *x, float *v, float *xp, const float *const *ptrs, 
         ABS_CASE(16)
 #undef ABS_CASE
     default: {
-        const int64_t tile64 = choose_tile(rows_of(P), 4 * kCUs);
+        const int64_t tile64 = choose_tile(rows_of(P), resident(4));
         if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
         AccPtrsAny A;
         std::memset(&A, 0, sizeof A);
@@ -438,15 +451,7 @@ int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dt
 int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
                    int64_t n_samples, int64_t *count, void *stream)
 {
-    if (P > 0 && !grad) return ABS_EINVAL;
-    const void *grads[1] = {grad ? grad : acc};   // P == 0 launches nothing; any non-null stand-in will do
-    if (P == 0) {
-        if (!count || n_samples <= 0 || *count < 0) return ABS_EINVAL;
-        if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
-        if (*count > std::numeric_limits<int64_t>::max() - n_samples) return ABS_EINVAL;
-        *count += n_samples;
-        return ABS_OK;
-    }
+    const void *grads[1] = {grad};
     return abs_accumulate_batch(acc, grads, grad_dtype, 1, P, &n_samples, count, stream);
 }
 

@@ -704,6 +704,71 @@ def test_full_size_sampled(absgd, name, lam, batched):
 
 
 # ---------------------------------------------------------------------------
+# vectors longer than 2^31 elements: 64-bit indexing end to end
+# ---------------------------------------------------------------------------
+
+def test_more_than_2_31_elements(absgd):
+    """P = 2^31 + 3 tiles + 5 elements (8.6 GB per fp32 vector).  Inputs are made on the device
+    with PyTorch (an input generator, not the path under test); the oracle runs on elements
+    sampled around 0, 2^31, the 2^32-byte boundaries and the tail."""
+    P = 2**31 + 3 * 4096 + 5
+    print(f"[case] P = {P}: allocating", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0x15164)
+
+    def fill_normal(t, sigma):
+        step = 1 << 28
+        for a in range(0, t.numel(), step):
+            t[a:a + step].normal_(0.0, sigma, generator=gen)
+        return t
+
+    acc0 = torch.empty(P, device="cuda")
+    acc1 = fill_normal(torch.empty(P, device="cuda"), 3.0)
+    g_bf = fill_normal(torch.empty(P, device="cuda", dtype=torch.bfloat16), 0.01)
+    g_f32 = fill_normal(torch.empty(P, device="cuda"), 0.01)
+    x = fill_normal(torch.empty(P, device="cuda"), 0.05)
+    v = torch.zeros(P, device="cuda")
+    idx = np.unique(np.concatenate([
+        wl.sample_indices(P, 20000, 99),
+        np.arange(2**30 - 8, 2**30 + 8), np.arange(2**31 - 4100, 2**31 + 4100), np.arange(P - 9000, P)]))
+    idx = idx[(idx >= 0) & (idx < P)]
+    it = torch.from_numpy(idx).cuda()
+
+    def at(t):
+        h = t[it].cpu()
+        return h.view(torch.int16).numpy().view(np.uint16).copy() if t.dtype == torch.bfloat16 else h.numpy().copy()
+
+    g_bf_s, g_f32_s, x_s, acc1_s = at(g_bf), at(g_f32), at(x), at(acc1)
+    torch.cuda.synchronize()
+    print("[case] accumulate (overwrite with bf16, then fp32 on top)", flush=True)
+    cnt = absgd.Count(0)
+    absgd.abs_accumulate(acc0, g_bf, 32, cnt)
+    absgd.abs_accumulate(acc0, g_f32, 64, cnt)
+    assert cnt.value == 96
+    print("[case] sync-update K = 2", flush=True)
+    absgd.abs_sync_update(x, v, [acc0, acc1], [96, 160], 0.1, 0.9, 5e-4)
+    torch.cuda.synchronize()
+    G0 = np.zeros(idx.size, dtype=F32)
+    orc.accumulate32(G0, g_bf_s, 32, first=True)
+    orc.accumulate32(G0, g_f32_s, 64, first=False)
+    _assert_bitexact(at(acc0), G0, "accumulate beyond 2^31")
+    xo, vo = x_s.copy(), np.zeros(idx.size, dtype=F32)
+    orc.sync_update32(xo, vo, [G0, acc1_s], [96, 160], 0.1, 0.9, 5e-4)
+    _assert_bitexact(at(x), xo, "sync-update x beyond 2^31")
+    _assert_bitexact(at(v), vo, "sync-update v beyond 2^31")
+    # against the double oracle, norm-wise
+    x64, v64 = x_s.astype(np.float64), np.zeros(idx.size)
+    G64 = np.zeros(idx.size)
+    orc.accumulate(G64, g_bf_s, 32)
+    orc.accumulate(G64, g_f32_s, 64)
+    orc.sync_update(x64, v64, [G64, acc1_s.astype(np.float64)], [96, 160], float(F32(0.1)), float(F32(0.9)), float(F32(5e-4)))
+    assert np.max(np.abs(at(x) - x64)) <= RTOL * np.max(np.abs(x64))
+    assert np.max(np.abs(at(v) - v64)) <= RTOL * np.max(np.abs(v64))
+    del acc0, acc1, g_bf, g_f32, x, v
+    torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------
 # the paper's own setting, long run: drift of the fp32 path against the double oracle
 # ---------------------------------------------------------------------------
 
