@@ -12,11 +12,13 @@
 //     number of resident rounds (256 CUs x resident workgroups per CU): every
 //     CU then finishes together instead of idling behind a ragged last round,
 //     which matters when a launch lasts only tens of microseconds;
-//   * every kernel (accumulate fp32 / bf16, sync-update, flat or ragged) maps
-//     workgroup b to tile b.  Workgroups are handed to the 8 XCDs round-robin,
-//     so with equal tile sizes tile c is always served by XCD c % 8: an
-//     accumulator tile written by one accumulate launch is found in that XCD's
-//     L2 by the next one when the working set is small enough;
+//   * workgroup b owns tile b in every kernel; workgroups go to the 8 XCDs
+//     round-robin, so consecutive tiles (consecutive memory) are spread over all
+//     XCDs and their L2s at any moment.  No reuse is sought in L2: the byte
+//     counters show that nothing survives there from one launch to the next
+//     (a steady accumulate launch over 4 MiB buffers still fetches gradient +
+//     accumulator in full), so the only cache that spans launches is the
+//     memory-side cache, which all XCDs share;
 //   * gradients are read once and never again: non-temporal loads keep them
 //     from displacing accumulator / parameter lines in L2 and the memory-side
 //     cache.  Accumulators, x and v are re-read soon (next micro-batch, next
