@@ -131,3 +131,43 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(absgd, "LIB_PATH", "/nonexistent/libabs_sgd.so")
     with pytest.raises(ImportError, match="no CPU or PyTorch fallback"):
         absgd.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU per box: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_accumulate_batch_host_checks():
+    L = absgd.lib()
+    c = ctypes.c_int64(32)
+    n2 = (ctypes.c_int64 * 2)(32, 64)
+    g2 = (ctypes.c_void_p * 2)(64, 128)
+    # P == 0: only the count moves, by the sum of the batch
+    assert L.abs_accumulate_batch(None, g2, absgd.ABS_F32, 2, 0, n2, ctypes.byref(c), None) == absgd.ABS_OK
+    assert c.value == 128
+    assert L.abs_accumulate_batch(16, g2, absgd.ABS_F32, 0, 8, n2, ctypes.byref(c), None) == absgd.ABS_EINVAL
+    bad = (ctypes.c_void_p * 2)(64, None)
+    assert L.abs_accumulate_batch(16, bad, absgd.ABS_F32, 2, 8, n2, ctypes.byref(c), None) == absgd.ABS_EINVAL
+    assert c.value == 128
+
+
+def test_update_rule_host_checks():
+    L = absgd.lib()
+    arr = (ctypes.c_void_p * 1)(64)
+    cnt = (ctypes.c_int64 * 1)(32)
+    zero = (ctypes.c_int64 * 1)(0)
+    # compensation: the previous-iterate buffer must be distinct
+    assert L.abs_sync_update_dc(16, 16, 32, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_dc(16, None, 32, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, None) == absgd.ABS_EINVAL
+    # Adam: step >= 1, betas in [0, 1), eps >= 0; an empty step is reported before anything else happens
+    assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 1.5, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, -1.0, 0.0, 1, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_adam(16, 32, 48, arr, zero, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EMPTY
+    assert L.abs_sync_update_adam(16, 32, 32, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EINVAL
