@@ -154,14 +154,9 @@ def calibrate_copy(torch, nbytes=1 << 30, reps=10):
                       "bytes_written_per_launch": nbytes, "launches": reps}))
 
 
-def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
-    """The oracle as it stands, on the host cores, on a bounded run of the same
-    workload: whole steps at full P until about budget_s of wall time is spent."""
+def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
+    """Whole steps of the workload through the oracle until budget_s of wall time is spent."""
     import numpy as np
-    import abs_workloads as wl
-    from oracle import abs_oracle as orc
-
-    threads = orc.max_threads()
     P, K = x0.size, w.K
     x = x0.astype(np.float64)
     v = np.zeros(P)
@@ -187,11 +182,29 @@ def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
         done_steps += 1
         if time.perf_counter() - t_start > budget_s:
             break
-    dt = time.perf_counter() - t_start
-    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": f"{done_steps} whole steps of {w.name} at full P={P} (same inputs and m_k), "
+    return done_bytes, done_steps, time.perf_counter() - t_start
+
+
+def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
+    """The oracle as it stands, on the host cores, on a bounded run of the same
+    workload: whole steps at full P, about budget_s of wall time with every core the
+    box gives the process (OpenMP over the parameter index), then a few seconds on
+    one thread."""
+    import abs_workloads as wl
+    from oracle import abs_oracle as orc
+
+    threads = orc.max_threads()
+    P = x0.size
+    nbytes, steps, dt = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s)
+    orc.set_threads(1)
+    b1, s1, dt1 = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s / 4)
+    orc.set_threads(threads)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{steps} whole steps of {w.name} at full P={P} (same inputs and m_k), "
                       f"{dt:.1f} s wall, OpenMP over the parameter index",
-            "ms_per_step": dt / done_steps * 1e3, "params_per_s": P * done_steps / dt}
+            "ms_per_step": dt / steps * 1e3, "params_per_s": P * steps / dt,
+            "single_thread": {"value": b1 / dt1 / 1e9, "unit": "GB/s", "ms_per_step": dt1 / s1 * 1e3,
+                              "sample": f"{s1} whole steps, {dt1:.1f} s wall"}}
 
 
 def main():
