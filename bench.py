@@ -266,9 +266,9 @@ def main():
     # steps; the fastest one is the library's configuration for this workload and
     # gives `value`.
     plans_wanted = [("one stream", False, 1), ("accumulate | sync-update", True, 1)]
-    for n in (2, 4):
+    for n in (2, 3, 4):
         if n <= w.K:
-            plans_wanted.append((f"{n} accumulate streams (workers spread) | sync-update", True, n))
+            plans_wanted.append((f"{n} accumulate streams (workers balanced over them) | sync-update", True, n))
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
     run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched,

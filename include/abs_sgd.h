@@ -271,7 +271,10 @@ int abs_ctx_destroy(abs_ctx *ctx);
  * (replaces stream_acc).  The K workers of Algorithm 1 compute at the same
  * time; their accumulators are independent, so their launches may overlap,
  * which hides launch ramp-up and drain when P is small.  A worker's own
- * launches stay ordered on its stream.  Only before the first accumulate;
+ * launches of a step stay ordered on one stream.  With fewer streams than
+ * workers, abs_swap_buffers re-places the workers for the next step so that the
+ * streams carry about equal numbers of launches, forecasting from the step just
+ * finished (initially worker k is on streams[k % n]).  Only before the first accumulate;
  * EINVAL afterwards, or for n < 1, n > ABS_MAX_K.  streams: HOST array. */
 int abs_ctx_set_accumulate_streams(abs_ctx *ctx, void *const *streams, int n);
 

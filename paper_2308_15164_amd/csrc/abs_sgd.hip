@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -282,7 +283,10 @@ struct abs_ctx {
     hipEvent_t ev_upd = nullptr;
     bool joins = false;                  // more than one distinct stream in use
 
-    hipStream_t stream_of(int k) const { return s_acc[(size_t)k % s_acc.size()]; }
+    std::vector<int> slot;               // worker k accumulates on s_acc[slot[k]]
+    std::vector<int64_t> launches;       // accumulate launches of worker k in the current step
+
+    hipStream_t stream_of(int k) const { return s_acc[(size_t)slot[(size_t)k]]; }
 };
 
 namespace {
@@ -748,6 +752,9 @@ static int ctx_set_streams(abs_ctx *C, const hipStream_t *streams, int n)
     for (hipEvent_t e : C->ev_acc) (void)hipEventDestroy(e);
     C->ev_acc.clear();
     C->s_acc.assign(streams, streams + n);
+    C->slot.resize((size_t)C->K);
+    for (int k = 0; k < C->K; ++k) C->slot[(size_t)k] = k % n;
+    C->launches.assign((size_t)C->K, 0);
     C->joins = false;
     for (hipStream_t s : C->s_acc) C->joins = C->joins || s != C->s_upd;
     if (C->joins) {
@@ -822,6 +829,7 @@ int abs_ctx_destroy(abs_ctx *C)
 int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype, int64_t n_samples)
 {
     if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    C->launches[(size_t)k] += 1;
     return abs_accumulate(C->acc[C->cur][(size_t)k], grad, grad_dtype, C->P, n_samples,
                           &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
@@ -830,6 +838,7 @@ int abs_ctx_accumulate_batch(abs_ctx *C, int k, const void *const *grads, abs_dt
                              const int64_t *n_samples)
 {
     if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    C->launches[(size_t)k] += J > 0 ? (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH : 0;
     return abs_accumulate_batch(C->acc[C->cur][(size_t)k], grads, grad_dtype, J, C->P, n_samples,
                                 &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
@@ -838,6 +847,7 @@ int abs_ctx_accumulate_batch_mt(abs_ctx *C, int k, const abs_tensorset *const *g
                                 const int64_t *n_samples)
 {
     if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    C->launches[(size_t)k] += J > 0 ? (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH : 0;
     return abs_accumulate_batch_mt(C->layout, C->set[C->cur][(size_t)k], grads, J, n_samples,
                                    &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
@@ -856,6 +866,7 @@ int abs_ctx_set_accumulate_streams(abs_ctx *C, void *const *streams, int n)
 int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
 {
     if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
+    C->launches[(size_t)k] += 1;
     return abs_accumulate_mt(C->layout, C->set[C->cur][(size_t)k], grad, n_samples,
                              &C->counts[C->cur][(size_t)k], C->stream_of(k));
 }
@@ -928,6 +939,28 @@ int abs_swap_buffers(abs_ctx *C)
             ABS_HIP(hipStreamWaitEvent(C->s_acc[i], C->ev_upd, 0));
         }
     }
+    // Fewer streams than workers: place the workers for the next step so that the
+    // streams carry about equal numbers of launches, taking this step's counts as
+    // the forecast (static heterogeneity persists from step to step; under purely
+    // dynamic heterogeneity any placement is as good as another).  Longest first,
+    // each to the least loaded stream.  Safe at this point only: every stream has
+    // just been ordered after everything the others have enqueued.
+    const size_t ns = C->s_acc.size();
+    if (ns > 1 && ns < (size_t)C->K) {
+        std::vector<int> order((size_t)C->K);
+        for (int k = 0; k < C->K; ++k) order[(size_t)k] = k;
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int a, int b) { return C->launches[(size_t)a] > C->launches[(size_t)b]; });
+        std::vector<int64_t> load(ns, 0);
+        for (int k : order) {
+            size_t best = 0;
+            for (size_t i = 1; i < ns; ++i)
+                if (load[i] < load[best]) best = i;
+            C->slot[(size_t)k] = (int)best;
+            load[best] += C->launches[(size_t)k] > 0 ? C->launches[(size_t)k] : 1;
+        }
+    }
+    for (auto &l : C->launches) l = 0;
     C->cur ^= 1;
     for (auto &c : C->counts[C->cur]) c = 0;
     return ABS_OK;
