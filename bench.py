@@ -266,7 +266,7 @@ def main():
     # steps; the fastest one is the library's configuration for this workload and
     # gives `value`.
     plans_wanted = [("one stream", False, 1), ("accumulate | sync-update", True, 1)]
-    for n in (2, 3, 4):
+    for n in (2, 4):
         if n <= w.K:
             plans_wanted.append((f"{n} accumulate streams (workers balanced over them) | sync-update", True, n))
     if args.acc_streams > 1:
