@@ -97,7 +97,7 @@ WORKLOADS = {w.name: w for w in [
     Workload("cfg5_gpt2_ragged_bf16", 5, sum(_GPT2), 16, "bf16", 32, 0.05, 0.01, 0.1, 0.9,
              5e-4, 10, "uniform_1_8", tensor_sizes=_GPT2,
              notes="148 separately allocated tensors in a seeded order"),
-    # builder-side extras (not BASELINE configs)
+    # extras beyond the five stated configurations
     Workload("ragged_odd_f32", 6, sum(_ODD), 3, "f32", 32, 0.05, 0.01, 0.1, 0.9, 5e-4, 4,
              "uniform_1_4", tensor_sizes=_ODD, pool=12,
              notes="odd tensor sizes: vector tails, tiny tensors"),

@@ -6,7 +6,8 @@ sync-update of the delayed generation (K accumulators -> x, v) on one stream,
 sum_k m_k accumulate calls into the current generation on another, and the
 swap.  Inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line; see the design doc for the meaning of every field.
+Prints ONE JSON line: whole-step throughput under the fastest stream plan, the dominant
+kernel against the HBM roofline, and the CPU oracle timed on the same box.
 """
 import argparse
 import json
@@ -223,7 +224,7 @@ def main():
                     help="streams the K workers' accumulations are spread over")
     ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
                     help="also apply the delayed gradient compensation with this coefficient "
-                         "(abs_sync_update_dc; +8 B/param); default: off, the BASELINE metric's path")
+                         "(abs_sync_update_dc; +8 B/param); default: off, the four-part path of the headline metric")
     ap.add_argument("--adam", action="store_true",
                     help="Adam (beta 0.9/0.999, eps 1e-8, lr 1e-3) as the update rule instead of momentum SGD "
                          "(abs_sync_update_adam; +8 B/param)")

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library, called through its C ABI, against the CPU oracle
 on the same seeded inputs.
 
-Bars (written out here, derived in the design doc):
+Bars:
   * sample counts: exact integers;
   * against the fixed-order fp32 oracle: bit for bit;
   * against the double oracle (the judge of accuracy):
@@ -656,7 +656,7 @@ def test_trajectory_delay_invariant_on_gpu(absgd):
 
 
 # ---------------------------------------------------------------------------
-# full BASELINE sizes in the benchmark's launch configuration, sampled outputs
+# the full stated sizes in the benchmark's launch configuration, sampled outputs
 # ---------------------------------------------------------------------------
 
 @pytest.mark.parametrize("name,lam,batched", [("cfg2_resnet18", None, False), ("cfg3_resnet50_bf16", None, False),
