@@ -83,10 +83,12 @@ def kernel_event_pass(run, plans, t0, steps, torch):
     launches keeps the events' own cost below 1 %).  The sync-update of the
     step runs concurrently on the other stream, as in the timed region."""
     ctx, n, gdt = run.ctx, run.w.n, run.gdt
-    pairs, launches = [], []
+    pairs, launches, sync_pairs = [], [], []
     torch.cuda.synchronize()
     for t in range(t0, t0 + steps):
-        run.sync_update()
+        es = torch.cuda.Event(enable_timing=True)
+        es.record(run.s_acc)
+        applied = run.sync_update()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(run.s_acc)
@@ -103,9 +105,11 @@ def kernel_event_pass(run, plans, t0, steps, torch):
             launches.append(len(plans[t]))
         e1.record(run.s_acc)
         pairs.append((e0, e1))
+        if applied:
+            sync_pairs.append((es, e0))      # one stream: the sync-update sits between these two
         ctx.abs_swap_buffers()
     torch.cuda.synchronize()
-    return [a.elapsed_time(b) for a, b in pairs], launches
+    return [a.elapsed_time(b) for a, b in pairs], launches, [a.elapsed_time(b) for a, b in sync_pairs]
 
 
 def probe_ceilings(torch, nbytes=1 << 30, reps=20):
@@ -291,7 +295,7 @@ def main():
     # Dominant kernel (accumulate) alone on the GPU: the one-stream plan, same steps.
     run.configure_streams(False, 1)
     time_steps(run, calls, 0, max(W, 1), torch)
-    bracket_ms, step_launches = kernel_event_pass(run, calls, W, K_steps, torch)
+    bracket_ms, step_launches, sync_ms = kernel_event_pass(run, calls, W, K_steps, torch)
     run.close()
     del run, calls
     torch.cuda.empty_cache()
@@ -312,6 +316,10 @@ def main():
     kern_ms = sum(bracket_ms[i] for i in keep) / launches
     kern_bytes = sum(step_acc_bytes[i] for i in keep) / launches
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+    sync_ms = sorted(sync_ms)[:max(1, len(sync_ms) - len(sync_ms) // 20)]
+    sync_avg_ms = sum(sync_ms) / len(sync_ms)
+    sync_bytes = bytes_per_param(w, sched[W], comp, args.batched)[1] * w.P
+    sync_gbs = sync_bytes / (sync_avg_ms * 1e-3) / 1e9
     kname = dominant_kernel(w, args.batched)
     traffic = MEASURED_TRAFFIC.get((w.name, kname))
 
@@ -350,8 +358,15 @@ def main():
             "measured": "HIP events around each step's accumulate launches, one-stream plan "
                         "(the kernel alone on the GPU), same steps as the timed region",
         },
+        "sync_update_kernel": {
+            "achieved": sync_gbs, "unit": "GB/s", "frac": sync_gbs / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": sync_bytes, "avg_launch_ms": sync_avg_ms,
+            "measured": "HIP events around the sync-update launch, one-stream plan, same steps",
+        },
         "box_ceilings": probe_ceilings(torch),
     }
+    if out["box_ceilings"]:
+        out["pct_of_box_copy_rate"] = 100.0 * gbs / out["box_ceilings"]["copy_GBs"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:])
     print(json.dumps(out))
