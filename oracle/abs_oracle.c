@@ -43,6 +43,13 @@
  *       x = x - gamma * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps),
  * t = 1, 2, ... counting the updates actually applied.
  *
+ * LARS variant (the other rule named in "Conclusions and Future Work"; not spelt
+ * out by the paper).  The published layer-wise rule, per tensor ("layer") l, driven
+ * by the delayed weighted average g_l = Gbar restricted to the layer:
+ *       rate_l = eta * ||x_l|| / (||g_l|| + wd * ||x_l||)   (1 when either norm is 0)
+ *       v_l = mu * v_l + gamma * rate_l * (g_l + wd * x_l);   x_l = x_l - v_l
+ * with Euclidean norms over the layer.
+ *
  * Precision: everything in IEEE double.  Inputs (fp32 or bf16 gradients, fp32
  * hyper-parameters) are widened exactly before use.
  *
@@ -196,6 +203,41 @@ int oracle_sync_update_adam(double *x, double *m, double *v, const double *const
         const double mhat = m[j] / bc1;
         const double vhat = v[j] / bc2;
         x[j] = x[j] - gamma * mhat / (sqrt(vhat) + eps);
+    }
+    return 0;
+}
+
+/* LARS over n_tensors consecutive layers of the flat vector; sizes[l] elements each
+ * (they sum to n_params).  Returns 1 and touches nothing when sum(M) == 0. */
+int oracle_sync_update_lars(double *x, double *v, const double *const *G, const int64_t *M, int N,
+                            int n_tensors, const int64_t *sizes, double gamma, double mu, double wd,
+                            double eta)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const double Mt = (double)M_total;
+    int64_t base = 0;
+    for (int l = 0; l < n_tensors; ++l) {
+        const int64_t n = sizes[l];
+        double xx = 0.0, gg = 0.0;
+        for (int64_t j = base; j < base + n; ++j) {
+            double s = 0.0;
+            for (int i = 0; i < N; ++i) s += G[i][j];
+            const double g = s / Mt;
+            xx += x[j] * x[j];
+            gg += g * g;
+        }
+        const double xn = sqrt(xx), gn = sqrt(gg);
+        const double rate = (xn > 0.0 && gn > 0.0) ? eta * xn / (gn + wd * xn) : 1.0;
+        for (int64_t j = base; j < base + n; ++j) {
+            double s = 0.0;
+            for (int i = 0; i < N; ++i) s += G[i][j];
+            const double g = s / Mt;
+            v[j] = mu * v[j] + gamma * rate * (g + wd * x[j]);
+            x[j] = x[j] - v[j];
+        }
+        base += n;
     }
     return 0;
 }

@@ -66,6 +66,9 @@ def lib():
         _lib.oracle32_sync_update_adam.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
                                                    _c_flt, _c_flt, _c_flt, _c_flt, _c_flt, _c_i64]
         _lib.oracle32_sync_update_adam.restype = ctypes.c_int
+        _lib.oracle_sync_update_lars.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int, _vp,
+                                                 _c_dbl, _c_dbl, _c_dbl, _c_dbl]
+        _lib.oracle_sync_update_lars.restype = ctypes.c_int
         _lib.oracle32_accumulate_f32.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_accumulate_bf16.argtypes = [_vp, _vp, _c_i64, _c_i64, ctypes.c_int]
         _lib.oracle32_sync_update.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
@@ -176,6 +179,27 @@ def sync_update_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, step
     return rc == 0
 
 
+def sync_update_lars(x, v, G_list, M_list, sizes, gamma, mu, wd, eta):
+    """Layer-wise adaptive rate scaling driven by the delayed weighted average;
+    sizes: elements of each consecutive layer of the flat vector.  Double only:
+    there is no fixed-order fp32 restatement of the norm reductions."""
+    _check(x, np.float64)
+    _check(v, np.float64)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float64)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    sz = np.ascontiguousarray(np.asarray(sizes, dtype=np.int64))
+    if int(sz.sum()) != x.size or (sz < 0).any():
+        raise ValueError("sizes must be non-negative and sum to the vector length")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    rc = lib().oracle_sync_update_lars(_ptr(x), _ptr(v), ptrs, _ptr(M), N, sz.size, _ptr(sz), float(gamma),
+                                       float(mu), float(wd), float(eta))
+    return rc == 0
+
+
 # ---- fp32 family with the fixed operation order ------------------------------
 
 def accumulate32(G, g, M_r, first):
@@ -238,7 +262,8 @@ def sync_update32_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, st
 
 # ---- Algorithm 1, whole loop --------------------------------------------------
 
-def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None, adam=None):
+def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None, adam=None,
+        lars=None):
     """Run T iterations of Algorithm 1 on the flat parameter vector x0.
 
     batches(t, i) -> list of mean-gradient vectors (float32 or bf16 bits), one
@@ -256,6 +281,7 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     compensation line of Algorithm 1 out (then no x_{t-1} is kept).
     adam: (beta1, beta2, eps) switches the update rule to Adam (mu is unused,
     the returned "v" is then the pair (m, v)).
+    lars: (sizes, eta) switches it to LARS over those layers (double only).
     Returns (x_T, v_T, M_history[T][N]).  record(t, x, v) is called after each
     iteration when given.
     """
@@ -288,7 +314,11 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
                     accumulate32(G[cur][i], g, M_r, first=(M[cur][i] == 0))
                 M[cur][i] += M_r
         # Step 1 + update: apply generation t-1 to x_t
-        if adam is not None:
+        if lars is not None:
+            if precision != "f64":
+                raise ValueError("LARS has no fixed-order fp32 restatement")
+            sync_update_lars(x, v, G[prev], M[prev], lars[0], gamma, mu, wd, lars[1])
+        elif adam is not None:
             fn = sync_update_adam if precision == "f64" else sync_update32_adam
             if fn(x, m1, v, G[prev], M[prev], gamma, adam[0], adam[1], adam[2], wd, applied + 1):
                 applied += 1

@@ -620,3 +620,80 @@ def test_adam_fp32_family_tracks_double_family():
     assert np.max(np.abs(m32 - m64)) <= 2e-6 * np.max(np.abs(m64))
     assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
     assert np.max(np.abs(x64 - x0)) > 1e-3                     # seven updates of ~lr each
+
+
+# ---------------------------------------------------------------------------
+# 12. LARS behind the delayed synchronous mechanism (named with Adam in Section
+#     "Conclusions and Future Work"; the recursion is the published layer-wise rule)
+# ---------------------------------------------------------------------------
+
+def test_lars_worked_example():
+    gold = _read_golden("worked_example.txt")
+    x, v = np.array([3.0, 4.0]), np.zeros(2)
+    assert orc.sync_update_lars(x, v, [np.array([0.6, 0.8]) * 64], [64], [2], 0.5, 0.0, 0.1, 0.02)
+    np.testing.assert_allclose(v, [float(f) for f in gold["lars_v"]], rtol=1e-14)
+    np.testing.assert_allclose(x, [float(f) for f in gold["lars_x"]], rtol=1e-14)
+
+
+def test_lars_matches_an_independent_numpy_statement():
+    rng = np.random.default_rng(31)
+    sizes = [7, 1, 30, 12]
+    P = sum(sizes)
+    G = [rng.standard_normal(P) * 32, rng.standard_normal(P) * 64, rng.standard_normal(P) * 96]
+    M = [32, 64, 96]
+    x0, v0 = rng.standard_normal(P), rng.standard_normal(P) * 0.01
+    gamma, mu, wd, eta = 0.1, 0.9, 5e-4, 0.001
+    x, v = x0.copy(), v0.copy()
+    orc.sync_update_lars(x, v, G, M, sizes, gamma, mu, wd, eta)
+    gbar = sum(G) / sum(M)
+    off = np.cumsum([0] + sizes)
+    for a, b in zip(off[:-1], off[1:]):
+        wn, gn = np.linalg.norm(x0[a:b]), np.linalg.norm(gbar[a:b])
+        rate = eta * wn / (gn + wd * wn)
+        v_ref = mu * v0[a:b] + gamma * rate * (gbar[a:b] + wd * x0[a:b])
+        np.testing.assert_allclose(v[a:b], v_ref, rtol=1e-12)
+        np.testing.assert_allclose(x[a:b], x0[a:b] - v_ref, rtol=1e-12, atol=1e-15)
+
+
+def test_lars_step_length_ignores_gradient_scale_and_layers_are_independent():
+    rng = np.random.default_rng(32)
+    sizes = [16, 16]
+    G = [rng.standard_normal(32) * 32]
+    x0 = rng.standard_normal(32)
+    xa, va = x0.copy(), np.zeros(32)
+    orc.sync_update_lars(xa, va, G, [32], sizes, 0.1, 0.0, 0.0, 0.01)
+    # wd = 0: the step is gamma * eta * ||x_l|| * g_l / ||g_l||, whatever the gradient's scale
+    xb, vb = x0.copy(), np.zeros(32)
+    orc.sync_update_lars(xb, vb, [G[0] * 1e3], [32], sizes, 0.1, 0.0, 0.0, 0.01)
+    np.testing.assert_allclose(xa, xb, rtol=1e-12)
+    for sl in (slice(0, 16), slice(16, 32)):
+        np.testing.assert_allclose(np.linalg.norm(va[sl]), 0.1 * 0.01 * np.linalg.norm(x0[sl]), rtol=1e-12)
+    # changing layer 1's gradients leaves layer 0 alone
+    G2 = [G[0].copy()]
+    G2[0][16:] *= -3.0
+    xc, vc = x0.copy(), np.zeros(32)
+    orc.sync_update_lars(xc, vc, G2, [32], sizes, 0.1, 0.0, 0.0, 0.01)
+    np.testing.assert_array_equal(xc[:16], xa[:16])
+    assert np.max(np.abs(xc[16:] - xa[16:])) > 1e-4
+
+
+def test_lars_degenerate_norms_and_empty_step():
+    x, v = np.zeros(3), np.zeros(3)
+    G = [np.array([32.0, -64.0, 0.0])]
+    orc.sync_update_lars(x, v, G, [32], [3], 0.1, 0.9, 0.0, 0.01)       # ||x|| = 0: rate 1, a plain step
+    np.testing.assert_allclose(x, [-0.1, 0.2, 0.0], rtol=1e-15)
+    x2, v2 = np.array([1.0, 2.0]), np.array([0.5, 0.5])
+    orc.sync_update_lars(x2, v2, [np.zeros(2)], [32], [2], 0.1, 0.0, 0.01, 0.5)   # ||g|| = 0: rate 1
+    np.testing.assert_allclose(v2, [0.001, 0.002], rtol=1e-14)
+    x3, v3 = np.array([1.0, 2.0]), np.array([0.5, 0.5])
+    assert orc.sync_update_lars(x3, v3, [np.zeros(2)], [0], [2], 0.1, 0.9, 0.01, 0.5) is False
+    assert x3.tolist() == [1.0, 2.0] and v3.tolist() == [0.5, 0.5]
+
+
+def test_lars_one_layer_per_element_is_sign_like():
+    """With one element per layer and wd = 0 the step is gamma*eta*|x| in the direction of g."""
+    x0 = np.array([2.0, -3.0, 0.5])
+    g = np.array([0.1, 5.0, -7.0])
+    x, v = x0.copy(), np.zeros(3)
+    orc.sync_update_lars(x, v, [g * 32], [32], [1, 1, 1], 0.1, 0.0, 0.0, 0.05)
+    np.testing.assert_allclose(x, x0 - 0.1 * 0.05 * np.abs(x0) * np.sign(g), rtol=1e-14)
