@@ -38,7 +38,7 @@ MEASURED_TRAFFIC = {
 MAX_BATCH = 8   # ABS_MAX_BATCH: gradients one accumulate launch folds in
 
 
-def bytes_per_param(w, m_row, extra_state=False, batched=False):
+def bytes_per_param(w, m_row, extra_state=False, batched=False, lars=False):
     """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
     an accumulate reads one gradient element and reads+writes one fp32
     accumulator element (the first call of a step only writes it); the
@@ -51,6 +51,9 @@ def bytes_per_param(w, m_row, extra_state=False, batched=False):
         acc = sum(int(m) * gb + 8 * (-(-int(m) // MAX_BATCH)) - 4 for m in m_row)
     else:
         acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
+    if lars:
+        # K accumulators + x read, Gbar written; then Gbar, x, v read and x, v written
+        return acc, (4 * w.K + 8) + 20
     return acc, 4 * w.K + 16 + (8 if extra_state else 0)
 
 
@@ -232,6 +235,9 @@ def main():
     ap.add_argument("--adam", action="store_true",
                     help="Adam (beta 0.9/0.999, eps 1e-8, lr 1e-3) as the update rule instead of momentum SGD "
                          "(abs_sync_update_adam; +8 B/param)")
+    ap.add_argument("--lars", action="store_true",
+                    help="LARS (trust 0.001) per tensor as the update rule (abs_sync_update_lars_mt; ragged "
+                         "workloads only; 4K + 28 B/param)")
     ap.add_argument("--batched", action="store_true",
                     help="one abs_accumulate_batch call per worker and step instead of one abs_accumulate "
                          "per micro-batch (fewer bytes: the accumulator is read and written once)")
@@ -277,7 +283,7 @@ def main():
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
     run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched,
-                    adam=(0.9, 0.999, 1e-8) if args.adam else None)
+                    adam=(0.9, 0.999, 1e-8) if args.adam else None, lars=0.001 if args.lars else None)
     if args.adam:
         run.lr = 1e-3
     comp = args.compensation is not None or args.adam
@@ -302,14 +308,14 @@ def main():
 
     step_bytes = 0
     for t in range(W, total):
-        a, s_ = bytes_per_param(w, sched[t], comp, args.batched)
+        a, s_ = bytes_per_param(w, sched[t], comp, args.batched, args.lars)
         step_bytes += (a + s_) * w.P
     gbs = step_bytes / dt / 1e9
     # Algorithmic bytes per accumulate launch = the step's accumulate bytes
     # (sum_k [m_k (g_b + 8) - 4] per parameter) averaged over its sum_k m_k launches.
     # A step whose bracket is far off the others (a hiccup of the box) is left out: steps are
     # ranked by time per launch and the slowest twentieth dropped.
-    step_acc_bytes = [bytes_per_param(w, sched[t], comp, args.batched)[0] * w.P for t in range(W, total)]
+    step_acc_bytes = [bytes_per_param(w, sched[t], comp, args.batched, args.lars)[0] * w.P for t in range(W, total)]
     order = sorted(range(K_steps), key=lambda i: bracket_ms[i] / step_launches[i])
     keep = order[:max(1, K_steps - K_steps // 20)]
     launches = sum(step_launches[i] for i in keep)
@@ -318,7 +324,7 @@ def main():
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
     sync_ms = sorted(sync_ms)[:max(1, len(sync_ms) - len(sync_ms) // 20)]
     sync_avg_ms = sum(sync_ms) / len(sync_ms)
-    sync_bytes = bytes_per_param(w, sched[W], comp, args.batched)[1] * w.P
+    sync_bytes = bytes_per_param(w, sched[W], comp, args.batched, args.lars)[1] * w.P
     sync_gbs = sync_bytes / (sync_avg_ms * 1e-3) / 1e9
     kname = dominant_kernel(w, args.batched)
     traffic = MEASURED_TRAFFIC.get((w.name, kname))
@@ -342,7 +348,7 @@ def main():
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
             "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
             "compensation_lambda": args.compensation, "batched_accumulate": args.batched,
-            "update_rule": "adam" if args.adam else "momentum sgd",
+            "update_rule": "adam" if args.adam else ("lars" if args.lars else "momentum sgd"),
             "streams": best + ", double-buffered",
             "algorithmic_bytes_per_step": step_bytes // K_steps,
         },

@@ -246,6 +246,26 @@ int abs_sync_update_adam_mt(abs_layout *layout, const abs_tensorset *params,
                             const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                             float beta1, float beta2, float eps, float wd, int64_t step, void *stream);
 
+/* LARS behind the delayed synchronous mechanism -- the other rule the paper's
+ * Section "Conclusions and Future Work" names.  Layer = tensor of the layout.  Per
+ * tensor l, with g_l the delayed weighted average Gbar restricted to it:
+ *     rate_l = eta * ||x_l|| / (||g_l|| + wd * ||x_l||)      (1 if either norm is 0)
+ *     v = fmaf(mu, v, step_l * fmaf(wd, x, Gbar)),  step_l = (float)(lr * rate_l);   x = x - v
+ * Norms are accumulated in double in a fixed order (results do not depend on
+ * timing).  Three launches: Gbar and the sums of squares (4K + 8 B/param), the
+ * per-tensor rates, the update (20 B/param).
+ *
+ *   gbar  an ABS_F32 set over the layout, caller-owned workspace: it receives Gbar
+ *         and must differ from every other set of the call.
+ *   The per-chunk sums and per-tensor rates live in device memory owned by the
+ *   layout (allocated on the first LARS call): two LARS calls on one layout must
+ *   not overlap in time.  A flat vector is a layout of one tensor.
+ *   Other arguments, ABS_EMPTY and errors: as abs_sync_update_mt. */
+int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
+                            const abs_tensorset *momentum, const abs_tensorset *gbar,
+                            const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                            float mu, float wd, float eta, void *stream);
+
 /* ------------------------------------------------------------------------
  * (4) Double buffer -- Algorithm 1, "Run Step 1 and Step 2 in parallel": two
  *     generations of (K accumulators, K counts).  Accumulation of batch t runs
@@ -309,6 +329,11 @@ int abs_ctx_sync_update_adam(abs_ctx *ctx, float *params, float *exp_avg, float 
 int abs_ctx_sync_update_adam_mt(abs_ctx *ctx, const abs_tensorset *params,
                                 const abs_tensorset *exp_avg, const abs_tensorset *exp_avg_sq,
                                 float lr, float beta1, float beta2, float eps, float wd, int64_t step);
+
+/* LARS (abs_sync_update_lars_mt) from the PREVIOUS generation; ragged contexts only. */
+int abs_ctx_sync_update_lars_mt(abs_ctx *ctx, const abs_tensorset *params,
+                                const abs_tensorset *momentum, const abs_tensorset *gbar, float lr,
+                                float mu, float wd, float eta);
 
 /* End of an iteration (Algorithm 1, t = t + 1): stream_upd and every accumulate
  * stream wait for the work the other side has enqueued so far (the next sync-update reads what accumulation

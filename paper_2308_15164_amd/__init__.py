@@ -48,6 +48,7 @@ SYMBOLS = {
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
     "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _i64, _vp]),
+    "abs_sync_update_lars_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_destroy": (_int, [_vp]),
@@ -62,6 +63,7 @@ SYMBOLS = {
     "abs_ctx_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
     "abs_ctx_sync_update_adam": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64]),
     "abs_ctx_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64]),
+    "abs_ctx_sync_update_lars_mt": (_int, [_vp, _vp, _vp, _vp, _f, _f, _f, _f]),
     "abs_swap_buffers": (_int, [_vp]),
     "abs_ctx_counts": (_int, [_vp, _int, _pi64]),
 }
@@ -336,7 +338,16 @@ def abs_sync_update_adam_mt(layout, params, exp_avg, exp_avg_sq, acc, counts, lr
     rc = lib().abs_sync_update_adam_mt(layout.handle, params.handle, exp_avg.handle, exp_avg_sq.handle, sets,
                                        _i64_array(counts), len(acc), float(lr), float(beta1), float(beta2),
                                        float(eps), float(wd), int(step), _stream_handle(stream))
-    return _check("abs_sync_update_adam_mt", rc, allow_empty=True)
+    return _check("abs_sync_update_adam_mt", "abs_sync_update_lars_mt", rc, allow_empty=True)
+
+
+def abs_sync_update_lars_mt(layout, params, momentum, gbar, acc, counts, lr, mu, wd, eta, stream=None):
+    """LARS per tensor of the layout on the delayed weighted average; gbar is workspace."""
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_lars_mt(layout.handle, params.handle, momentum.handle, gbar.handle, sets,
+                                       _i64_array(counts), len(acc), float(lr), float(mu), float(wd),
+                                       float(eta), _stream_handle(stream))
+    return _check("abs_sync_update_lars_mt", rc, allow_empty=True)
 
 
 class Context:
@@ -416,6 +427,11 @@ class Context:
                                                int(step))
         return _check("abs_ctx_sync_update_adam_mt", rc, allow_empty=True)
 
+    def abs_sync_update_lars(self, params, momentum, gbar, lr, mu, wd, eta):
+        rc = lib().abs_ctx_sync_update_lars_mt(self.handle, params.handle, momentum.handle, gbar.handle,
+                                               float(lr), float(mu), float(wd), float(eta))
+        return _check("abs_ctx_sync_update_lars_mt", rc, allow_empty=True)
+
     def abs_swap_buffers(self):
         return _check("abs_swap_buffers", lib().abs_swap_buffers(self.handle))
 
@@ -442,7 +458,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

@@ -260,6 +260,11 @@ struct abs_layout {
     Chunk *d_chunks = nullptr;
     int64_t *d_sizes = nullptr;
     int device = -1;
+    // LARS only, made on its first use: first chunk of every tensor (T + 1 entries),
+    // per-chunk sums of squares, per-tensor step factors
+    int32_t *d_chunk_begin = nullptr;
+    double *d_partials = nullptr;
+    float *d_step = nullptr;
 };
 
 struct abs_tensorset {
@@ -311,6 +316,31 @@ int layout_to_device(abs_layout *L)
     L->d_chunks = dc;
     L->d_sizes = ds;
     L->device = dev;
+    return ABS_OK;
+}
+
+int layout_lars_scratch(abs_layout *L)
+{
+    if (L->d_partials) return ABS_OK;
+    std::vector<int32_t> begin(L->sizes.size() + 1, 0);
+    for (const Chunk &c : L->chunks) begin[(size_t)c.tensor + 1] += 1;
+    for (size_t t = 0; t < L->sizes.size(); ++t) begin[t + 1] += begin[t];
+    int32_t *db = nullptr;
+    double *dp = nullptr;
+    float *ds = nullptr;
+    hipError_t e = hipMalloc(&db, begin.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(&dp, 2 * L->chunks.size() * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(&ds, L->sizes.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(db, begin.data(), begin.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (db) (void)hipFree(db);
+        if (dp) (void)hipFree(dp);
+        if (ds) (void)hipFree(ds);
+        return hip_fail(e);
+    }
+    L->d_chunk_begin = db;
+    L->d_partials = dp;
+    L->d_step = ds;
     return ABS_OK;
 }
 
@@ -581,6 +611,9 @@ int abs_layout_destroy(abs_layout *L)
     if (!L) return ABS_EINVAL;
     if (L->d_chunks) (void)hipFree(L->d_chunks);
     if (L->d_sizes) (void)hipFree(L->d_sizes);
+    if (L->d_chunk_begin) (void)hipFree(L->d_chunk_begin);
+    if (L->d_partials) (void)hipFree(L->d_partials);
+    if (L->d_step) (void)hipFree(L->d_step);
     delete L;
     return ABS_OK;
 }
@@ -743,6 +776,43 @@ int abs_sync_update_adam_mt(abs_layout *L, const abs_tensorset *params, const ab
     int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
     if (rc != ABS_OK) return rc;
     return sync_update_mt_impl(ADAM, L, params, exp_avg, exp_avg_sq, acc, counts, K, h, stream);
+}
+
+int abs_sync_update_lars_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                            const abs_tensorset *gbar, const abs_tensorset *const *acc,
+                            const int64_t *counts, int K, float lr, float mu, float wd, float eta,
+                            void *stream)
+{
+    if (!L || !acc) return ABS_EINVAL;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK) return rc;
+    if (!set_ok(params, L) || !set_ok(momentum, L) || !set_ok(gbar, L)) return ABS_EINVAL;
+    if (params == momentum || gbar == params || gbar == momentum) return ABS_EINVAL;
+    if (params->elem != ABS_F32 || momentum->elem != ABS_F32 || gbar->elem != ABS_F32) return ABS_EINVAL;
+    TabPtrsAny tabs;
+    std::memset(&tabs, 0, sizeof tabs);
+    for (int j = 0; j < c.n; ++j) {
+        const abs_tensorset *s = acc[c.idx[j]];
+        if (!set_ok(s, L) || s->elem != ABS_F32 || s == gbar) return ABS_EINVAL;
+        tabs.t[j] = reinterpret_cast<const float *const *>(s->d_tab);
+    }
+    if (L->chunks.empty()) return ABS_OK;
+    rc = layout_to_device(L);
+    if (rc == ABS_OK) rc = layout_lars_scratch(L);
+    if (rc != ABS_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
+    float *const *vt = reinterpret_cast<float *const *>(momentum->d_tab);
+    float *const *gt = reinterpret_cast<float *const *>(gbar->d_tab);
+    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
+    hipLaunchKernelGGL(lars_reduce_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, gt, tabs, c.n, L->tile,
+                       (float)c.M, L->d_partials);
+    hipLaunchKernelGGL(lars_rates, dim3((unsigned)L->sizes.size()), dim3(64), 0, s, L->d_chunk_begin,
+                       L->d_partials, L->d_step, (double)lr, (double)wd, (double)eta);
+    hipLaunchKernelGGL(lars_update_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, gt, L->d_step,
+                       L->tile, mu, wd);
+    return launch_status();
 }
 
 // --------------------------------------------------------- double buffer
@@ -923,6 +993,15 @@ int abs_ctx_sync_update_adam_mt(abs_ctx *C, const abs_tensorset *params, const a
     const int prev = C->cur ^ 1;
     return abs_sync_update_adam_mt(C->layout, params, exp_avg, exp_avg_sq, C->set[prev].data(),
                                    C->counts[prev].data(), C->K, lr, beta1, beta2, eps, wd, step, C->s_upd);
+}
+
+int abs_ctx_sync_update_lars_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *momentum,
+                                const abs_tensorset *gbar, float lr, float mu, float wd, float eta)
+{
+    if (!C || !C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    return abs_sync_update_lars_mt(C->layout, params, momentum, gbar, C->set[prev].data(),
+                                   C->counts[prev].data(), C->K, lr, mu, wd, eta, C->s_upd);
 }
 
 int abs_swap_buffers(abs_ctx *C)

@@ -28,12 +28,13 @@ class DeviceRun:
     acc_streams=n: the K workers' accumulations spread over n streams;
     lam          : coefficient of the delayed gradient compensation (None: off);
     adam         : (beta1, beta2, eps) switches the update rule to Adam;
+    lars         : trust coefficient eta switches it to LARS (one layer per tensor);
     batched=True : a worker's m_k gradients of a step go in one abs_accumulate_batch
                    call (same bits, the accumulator is read and written once).
     """
 
     def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False,
-                 adam=None):
+                 adam=None, lars=None):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
@@ -44,6 +45,7 @@ class DeviceRun:
         self.batched = bool(batched)                     # one accumulate launch per worker and step
         self.adam = None if adam is None else tuple(float(t) for t in adam)   # (beta1, beta2, eps)
         self.adam_step = 0                               # applied Adam updates so far
+        self.lars = None if lars is None else float(lars)   # LARS trust coefficient eta (ragged layouts)
         self._streams = [torch.cuda.Stream(device=torch.device("cuda:0")) for _ in range(9)]
         self.ctx = None
         if not self.ragged:
@@ -88,6 +90,12 @@ class DeviceRun:
                 self.xp_t = [t.clone() if self.adam is None else torch.zeros_like(t) for t in self.x_t]
                 torch.cuda.synchronize()
                 self.xp_arg = TensorSet(self.layout, self.xp_t)
+        if self.lars is not None:
+            if not self.ragged:
+                raise ValueError("LARS works per tensor: the workload needs a ragged layout")
+            self.gbar_t = [torch.zeros_like(t) for t in self.x_t]        # workspace for the averaged gradient
+            torch.cuda.synchronize()
+            self.gbar_set = TensorSet(self.layout, self.gbar_t)
         self.configure_streams(overlap, acc_streams)
         self.lr, self.mu, self.wd = float(w.lr), float(w.mu), float(w.wd)
         self.applied = []
@@ -128,6 +136,9 @@ class DeviceRun:
     def sync_update(self):
         """Step 1 + update on the delayed generation (compensated when lam is set,
         Adam when adam is set: v is then the first moment, xp the second)."""
+        if self.lars is not None:
+            return self.ctx.abs_sync_update_lars(self.x_arg, self.v_arg, self.gbar_set, self.lr, self.mu,
+                                                 self.wd, self.lars)
         if self.adam is not None:
             b1, b2, eps = self.adam
             ok = self.ctx.abs_sync_update_adam(self.x_arg, self.v_arg, self.xp_arg, self.lr, b1, b2, eps,

@@ -533,6 +533,113 @@ def test_trajectory_adam(absgd, name):
 
 
 # ---------------------------------------------------------------------------
+# abs_sync_update_lars_mt: per-tensor norms + update.  Double oracle only (the norm
+# reductions have no fixed-order fp32 restatement); results must not depend on timing.
+# ---------------------------------------------------------------------------
+
+def _lars_case(absgd, sizes, counts, seed, lr=0.1, mu=0.9, wd=5e-4, eta=0.001, zero_tensor=None):
+    rng = np.random.default_rng(seed)
+    P, K = int(sum(sizes)), len(counts)
+    off = wl.tensor_offsets(sizes)
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    v0 = (rng.standard_normal(P) * 0.001).astype(F32)
+    accs = [(rng.standard_normal(P) * 0.3 * max(c, 1) / 32).astype(F32) for c in counts]
+    if zero_tensor is not None:                        # a layer whose parameters are all zero: rate 1
+        x0[off[zero_tensor]:off[zero_tensor + 1]] = 0
+
+    def split(a):
+        return [_up(np.ascontiguousarray(a[off[t]:off[t + 1]])) for t in range(len(sizes))]
+
+    lay = absgd.Layout(sizes)
+    outs = []
+    for rep in range(2):
+        xt, vt = split(x0), split(v0)
+        gt = [torch.full_like(t, float("nan")) for t in xt]
+        at = [split(a) if c > 0 else [torch.full_like(t, float("nan")) for t in xt] for a, c in zip(accs, counts)]
+        xs, vs, gs = absgd.TensorSet(lay, xt), absgd.TensorSet(lay, vt), absgd.TensorSet(lay, gt)
+        asets = [absgd.TensorSet(lay, a) for a in at]
+        applied = absgd.abs_sync_update_lars_mt(lay, xs, vs, gs, asets, counts, lr, mu, wd, eta)
+        torch.cuda.synchronize()
+        cat = lambda ts: np.concatenate([t.cpu().numpy() for t in ts]) if ts else np.zeros(0, dtype=F32)
+        outs.append((cat(xt), cat(vt), cat(gt)))
+    _assert_bitexact(outs[1][0], outs[0][0], "LARS x, second run")         # fixed reduction order
+    _assert_bitexact(outs[1][1], outs[0][1], "LARS v, second run")
+    gx, gv, gg = outs[0]
+    x64, v64 = x0.astype(np.float64), v0.astype(np.float64)
+    G64 = [a.astype(np.float64) if c > 0 else np.zeros(P) for a, c in zip(accs, counts)]
+    f = lambda t: float(F32(t))
+    ok = orc.sync_update_lars(x64, v64, G64, counts, sizes, f(lr), f(mu), f(wd), f(eta))
+    assert applied == ok
+    if not ok:
+        _assert_bitexact(gx, x0, "untouched x")
+        _assert_bitexact(gv, v0, "untouched v")
+        return
+    M = float(sum(counts))
+    gbar = sum(G64) / M
+    gmag = sum(np.abs(g) for g in G64) / M
+    assert np.max(np.abs(gg - gbar)) <= RTOL * np.max(gmag)                # the workspace holds Gbar
+    step = np.abs(v64 - f(mu) * v0.astype(np.float64))                     # |lr*rate*(g + wd x)| per element
+    rel = step / np.maximum(np.abs(gbar + f(wd) * x0), 1e-300)             # lr*rate of the element's layer
+    v_scale = f(mu) * np.abs(v0.astype(np.float64)) + rel * (gmag + f(wd) * np.abs(x0))
+    x_scale = np.abs(x0.astype(np.float64)) + v_scale
+    _assert_close64(gv, v64, v_scale, "LARS v")
+    _assert_close64(gx, x64, x_scale, "LARS x")
+
+
+@pytest.mark.parametrize("K", [1, 3, 4, 5, 8, 16, 17])
+def test_lars_worker_counts(absgd, K):
+    print(f"[case] lars K={K}", flush=True)
+    _lars_case(absgd, [4096 * 3 + 5, 1, 700, 65_537, 12], [32 * (1 + k % 3) for k in range(K)], seed=900 + K)
+
+
+def test_lars_layouts_and_edges(absgd):
+    print("[case] lars layouts", flush=True)
+    _lars_case(absgd, [1_048_576 + 13], [64, 32], seed=921)                               # one layer = a flat vector
+    _lars_case(absgd, list(wl.WORKLOADS["ragged_odd_f32"].tensor_sizes), [32, 96, 64], seed=922)
+    _lars_case(absgd, [5, 0, 9000, 3], [32, 32], seed=923)                                # an empty tensor
+    _lars_case(absgd, [300, 5000, 70], [0, 64, 0, 32], seed=924)                          # idle workers (NaN buffers)
+    _lars_case(absgd, [300, 5000, 70], [0, 0], seed=925)                                  # nothing to apply
+    _lars_case(absgd, [300, 5000, 70], [32, 32], seed=926, zero_tensor=1)                 # ||x_l|| = 0: rate 1
+    _lars_case(absgd, [300, 5000], [32, 32], seed=927, mu=0.0, wd=0.0, eta=0.02)
+
+
+@pytest.mark.parametrize("tuned", [(1, 0), (1, 3)], indirect=True)
+def test_lars_multi_row_tiles(absgd, tuned):
+    print(f"[case] lars multi-row tuning={tuned}", flush=True)
+    _lars_case(absgd, [1_048_576 + 13, 300_007, 5], [32, 64, 32], seed=930)
+
+
+@pytest.mark.parametrize("name", ["ragged_odd_f32", "ragged_odd_bf16"])
+def test_trajectory_lars(absgd, name):
+    from paper_2308_15164_amd.driver import DeviceRun
+    w = wl.WORKLOADS[name]
+    steps, eta = w.steps, 0.02
+    x0, pool, sched = wl.initial_params(w), wl.gradient_pool(w), wl.schedule(w, steps)
+    res = []
+    for overlap in (False, True):
+        print(f"[case] lars trajectory {name} overlap={overlap}", flush=True)
+        run = DeviceRun(w, x0, pool, sched, overlap=overlap, lars=eta)
+        run.run(steps)
+        res.append(run.read_state() + (run.count_history,))
+        run.close()
+    _assert_bitexact(res[1][0], res[0][0], "lars overlap vs serial x")
+    _assert_bitexact(res[1][1], res[0][1], "lars overlap vs serial v")
+    R = len(pool)
+
+    def batches(t, i):
+        return [pool[wl.pool_index(w, t, i, j, R)] for j in range(int(sched[t, i]))]
+
+    f = lambda t: float(F32(t))
+    x64, v64, h = orc.run(x0, w.K, steps, w.n, f(w.lr), f(w.mu), f(w.wd), batches,
+                          lars=(list(w.tensor_sizes), f(eta)))
+    assert res[1][2] == h
+    gx, gv = res[1][:2]
+    assert np.max(np.abs(gx - x64)) <= RTOL * np.max(np.abs(x64))
+    assert np.max(np.abs(gv - v64)) <= RTOL * np.max(np.abs(v64))
+    assert np.max(np.abs(x64 - x0)) > 1e-5                                                # it moved
+
+
+# ---------------------------------------------------------------------------
 # whole trajectories through the double-buffered context (Algorithm 1 loop)
 # ---------------------------------------------------------------------------
 
