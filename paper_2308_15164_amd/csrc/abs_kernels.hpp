@@ -335,6 +335,65 @@ constexpr int sync_batch()
     return kc < 1 ? 1 : (kc > K ? K : kc);
 }
 
+// One group of ABS_SYNC_ROWS rows starting at vector g0.  WHOLE: the group lies
+// inside the tile and needs no bounds checks.
+template <int K, bool NTX, int RULE, bool WHOLE>
+__device__ __forceinline__ void sync_group(f32x4 *__restrict__ xv, f32x4 *__restrict__ vv,
+                                           f32x4 *__restrict__ pv, const AccPtrs<K> &A, int g0, int nvec,
+                                           int tid, const Hyper &h)
+{
+    constexpr bool S2 = uses_s2<RULE>();
+    constexpr int U = ABS_SYNC_ROWS;
+    constexpr int KC = sync_batch<K, RULE>();
+    f32x4 a[U][KC] = {}, sum[U] = {}, xr[U] = {}, vr[U] = {}, pr[U] = {};
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = g0 + u * BLOCK + tid;
+        if (WHOLE || i < nvec) {
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
+            xr[u] = ld<NTX>(xv + i);
+            vr[u] = ld<NTX>(vv + i);
+            if constexpr (S2) pr[u] = ld<NTX>(pv + i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        sum[u] = a[u][0];
+#pragma unroll
+        for (int k = 1; k < KC; ++k) sum[u] = sum[u] + a[u][k];
+    }
+    // remaining workers in batches of KC, still in ascending order
+#pragma unroll
+    for (int k0 = KC; k0 < K; k0 += KC) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = g0 + u * BLOCK + tid;
+            if (WHOLE || i < nvec) {
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k0 + k < K) a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k0 + k]) + i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k0 + k < K) sum[u] = sum[u] + a[u][k];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = g0 + u * BLOCK + tid;
+        if (WHOLE || i < nvec) {
+            update_vec<RULE>(sum[u], xr[u], vr[u], pr[u], h);
+            st<NTX>(vv + i, vr[u]);
+            if constexpr (S2) st<NTX>(pv + i, pr[u]);
+            st<NTX>(xv + i, xr[u]);
+        }
+    }
+}
+
 // One workgroup, one tile of the fused combine + update; K compile-time.
 // NTX: the traffic of x and the state vectors is streaming.  xp (the rule's
 // second state vector) is only touched by rules that have one.
@@ -346,81 +405,18 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
     constexpr bool S2 = uses_s2<RULE>();
     constexpr int U = ABS_SYNC_ROWS;
     const int tid = threadIdx.x;
-    if (!vec_ok) {
-        for (int i = tid; i < len; i += BLOCK) {
-            float s = A.p[0][i];
-#pragma unroll
-            for (int k = 1; k < K; ++k) s = s + A.p[k][i];
-            float ps = S2 ? xp[i] : 0.f;
-            update_one<RULE>(s, x[i], v[i], ps, h);
-            if constexpr (S2) xp[i] = ps;
-        }
-        return;
+    int done = 0;
+    if (vec_ok) {
+        f32x4 *xv = reinterpret_cast<f32x4 *>(x);
+        f32x4 *vv = reinterpret_cast<f32x4 *>(v);
+        f32x4 *pv = reinterpret_cast<f32x4 *>(xp);
+        const int nvec = len / VEC;
+        int g0 = 0;
+        for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) sync_group<K, NTX, RULE, true>(xv, vv, pv, A, g0, nvec, tid, h);
+        if (g0 < nvec) sync_group<K, NTX, RULE, false>(xv, vv, pv, A, g0, nvec, tid, h);
+        done = nvec * VEC;           // at most VEC-1 trailing elements remain
     }
-    f32x4 *xv = reinterpret_cast<f32x4 *>(x);
-    f32x4 *vv = reinterpret_cast<f32x4 *>(v);
-    f32x4 *pv = reinterpret_cast<f32x4 *>(xp);
-    const int nvec = len / VEC;
-    int g0 = 0;
-    for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK) {
-        constexpr int KC = sync_batch<K, RULE>();
-        f32x4 a[U][KC], sum[U], xr[U], vr[U], pr[U] = {};
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
-            xr[u] = ld<NTX>(xv + i);
-            vr[u] = ld<NTX>(vv + i);
-            if constexpr (S2) pr[u] = ld<NTX>(pv + i);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            sum[u] = a[u][0];
-#pragma unroll
-            for (int k = 1; k < KC; ++k) sum[u] = sum[u] + a[u][k];
-        }
-        // remaining workers in batches of KC, still in ascending order
-#pragma unroll
-        for (int k0 = KC; k0 < K; k0 += KC) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
-#pragma unroll
-                for (int k = 0; k < KC; ++k)
-                    if (k0 + k < K) a[u][k] = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k0 + k]) + i);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int k = 0; k < KC; ++k)
-                    if (k0 + k < K) sum[u] = sum[u] + a[u][k];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
-            f32x4 s = sum[u];
-            update_vec<RULE>(s, xr[u], vr[u], pr[u], h);
-            st<NTX>(vv + i, vr[u]);
-            if constexpr (S2) st<NTX>(pv + i, pr[u]);
-            st<NTX>(xv + i, xr[u]);
-        }
-    }
-    for (int i = g0 + tid; i < nvec; i += BLOCK) {
-        f32x4 s = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[0]) + i);
-#pragma unroll
-        for (int k = 1; k < K; ++k)
-            s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(A.p[k]) + i);
-        f32x4 xr = ld<NTX>(xv + i), vr = ld<NTX>(vv + i), pr = {};
-        if constexpr (S2) pr = ld<NTX>(pv + i);
-        update_vec<RULE>(s, xr, vr, pr, h);
-        st<NTX>(vv + i, vr);
-        if constexpr (S2) st<NTX>(pv + i, pr);
-        st<NTX>(xv + i, xr);
-    }
-    const int i = nvec * VEC + tid;
-    if (i < len) {
+    for (int i = done + tid; i < len; i += BLOCK) {
         float s = A.p[0][i];
 #pragma unroll
         for (int k = 1; k < K; ++k) s = s + A.p[k][i];
