@@ -33,7 +33,12 @@
  * plain SGD; with momentum and weight decay the compensated gradient takes
  * Gbar's place (compensate first, then weight decay, then momentum).  The
  * functions with the suffix _dc keep x_{t-1} in a buffer of their own, as the
- * paper's remark on memory overhead implies.
+ * paper's remark on memory overhead implies.  The functions with the suffix
+ * _dcm state the same correction without that buffer: every applied update is
+ * x_t = x_{t-1} - gamma_{t-1} * v_t, so x_t - x_{t-1} = -gamma_{t-1} * v_t with
+ * v_t the momentum as it stands before this update (gamma_{t-1} = 0 when the
+ * previous iteration applied nothing).  Equal to the _dc form in exact
+ * arithmetic; the CPU tests pin one against the other.
  *
  * Adam variant (the paper's Section "Conclusions and Future Work" names Adam as
  * the next update rule to put behind the delayed synchronous mechanism; the
@@ -175,6 +180,32 @@ int oracle_sync_update_dc(double *x, double *x_prev, double *v, const double *co
         const double d = Gtilde + wd * x[j];
         v[j] = mu * v[j] + d;
         x_prev[j] = x[j];
+        x[j] = x[j] - gamma * v[j];
+    }
+    return 0;
+}
+
+/* Compensation with x_t - x_{t-1} taken from the momentum: gamma_prev is the
+ * step size of the previous applied update, 0 when the previous iteration
+ * applied none (then x_t = x_{t-1}).  Returns 1 and touches nothing when
+ * sum(M) == 0. */
+int oracle_sync_update_dcm(double *x, double *v, const double *const *G, const int64_t *M, int N,
+                           int64_t n_params, double gamma, double mu, double wd, double lambda,
+                           double gamma_prev)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const double Mt = (double)M_total;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < N; ++i) s += G[i][j];
+        const double Gbar = s / Mt;
+        const double diff = -(gamma_prev * v[j]);
+        const double Gtilde = Gbar + lambda * Gbar * Gbar * diff;
+        const double d = Gtilde + wd * x[j];
+        v[j] = mu * v[j] + d;
         x[j] = x[j] - gamma * v[j];
     }
     return 0;
@@ -328,6 +359,40 @@ int oracle32_sync_update_dc(float *x, float *x_prev, float *v, const float *cons
         const float vn = fmaf(mu, v[j], d);
         v[j] = vn;
         x_prev[j] = x[j];
+        x[j] = fmaf(-gamma, vn, x[j]);
+    }
+    return 0;
+}
+
+/* Compensation from the momentum.  Order: Gbar as above; q = Gbar * Gbar;
+ * c = lambda * q; diff = (-gamma_prev) * v; Gtilde = fma(c, diff, Gbar);
+ * d = fma(wd, x, Gtilde); v = fma(mu, v, d); x = fma(-gamma, v, x). */
+int oracle32_sync_update_dcm(float *x, float *v, const float *const *G, const int64_t *M, int N,
+                             int64_t n_params, float gamma, float mu, float wd, float lambda,
+                             float gamma_prev)
+{
+    int64_t M_total = 0;
+    for (int i = 0; i < N; ++i) M_total += M[i];
+    if (M_total == 0) return 1;
+    const float Mt = (float)M_total;
+    const float ngp = -gamma_prev;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_params; ++j) {
+        float s = 0.0f;
+        int seen = 0;
+        for (int i = 0; i < N; ++i) {
+            if (M[i] <= 0) continue;
+            s = seen ? s + G[i][j] : G[i][j];
+            seen = 1;
+        }
+        const float Gbar = s / Mt;
+        const float q = Gbar * Gbar;
+        const float c = lambda * q;
+        const float diff = ngp * v[j];
+        const float Gtilde = fmaf(c, diff, Gbar);
+        const float d = fmaf(wd, x[j], Gtilde);
+        const float vn = fmaf(mu, v[j], d);
+        v[j] = vn;
         x[j] = fmaf(-gamma, vn, x[j]);
     }
     return 0;

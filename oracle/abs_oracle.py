@@ -60,6 +60,10 @@ def lib():
         _lib.oracle32_sync_update_dc.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
                                                  _c_flt, _c_flt, _c_flt, _c_flt]
         _lib.oracle32_sync_update_dc.restype = ctypes.c_int
+        _lib.oracle_sync_update_dcm.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64] + [ctypes.c_double] * 5
+        _lib.oracle_sync_update_dcm.restype = ctypes.c_int
+        _lib.oracle32_sync_update_dcm.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _c_i64] + [ctypes.c_float] * 5
+        _lib.oracle32_sync_update_dcm.restype = ctypes.c_int
         _lib.oracle_sync_update_adam.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _c_i64,
                                                  _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_i64]
         _lib.oracle_sync_update_adam.restype = ctypes.c_int
@@ -162,6 +166,24 @@ def sync_update_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
     return rc == 0
 
 
+def sync_update_dcm(x, v, G_list, M_list, gamma, mu, wd, lam, gamma_prev):
+    """The compensated update with x_t - x_{t-1} = -gamma_prev * v_t taken from the
+    momentum instead of a stored x_{t-1}; gamma_prev = 0 when the previous
+    iteration applied no update."""
+    _check(x, np.float64)
+    _check(v, np.float64)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float64)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    rc = lib().oracle_sync_update_dcm(_ptr(x), _ptr(v), ptrs, _ptr(M), N, x.size, float(gamma),
+                                      float(mu), float(wd), float(lam), float(gamma_prev))
+    return rc == 0
+
+
 def sync_update_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, step):
     """Adam driven by the delayed weighted average (the paper's stated next step);
     step = 1, 2, ... counts the updates actually applied."""
@@ -244,6 +266,22 @@ def sync_update32_dc(x, x_prev, v, G_list, M_list, gamma, mu, wd, lam):
     return rc == 0
 
 
+def sync_update32_dcm(x, v, G_list, M_list, gamma, mu, wd, lam, gamma_prev):
+    _check(x, np.float32)
+    _check(v, np.float32)
+    N = len(G_list)
+    for G in G_list:
+        _check(G, np.float32)
+        if G.size != x.size:
+            raise ValueError("size mismatch")
+    ptrs = (ctypes.c_void_p * N)(*[_ptr(G) for G in G_list])
+    M = np.ascontiguousarray(np.asarray(M_list, dtype=np.int64))
+    f = lambda t: float(np.float32(t))
+    rc = lib().oracle32_sync_update_dcm(_ptr(x), _ptr(v), ptrs, _ptr(M), N, x.size, f(gamma), f(mu),
+                                        f(wd), f(lam), f(gamma_prev))
+    return rc == 0
+
+
 def sync_update32_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, step):
     for a in (x, m, v):
         _check(a, np.float32)
@@ -263,7 +301,7 @@ def sync_update32_adam(x, m, v, G_list, M_list, gamma, beta1, beta2, eps, wd, st
 # ---- Algorithm 1, whole loop --------------------------------------------------
 
 def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam=None, adam=None,
-        lars=None):
+        lars=None, lam_from_momentum=False):
     """Run T iterations of Algorithm 1 on the flat parameter vector x0.
 
     batches(t, i) -> list of mean-gradient vectors (float32 or bf16 bits), one
@@ -279,6 +317,8 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     precision "f64": the definition in double.  "f32": the fixed-order fp32
     restatement.  lam: compensation coefficient lambda; None leaves the
     compensation line of Algorithm 1 out (then no x_{t-1} is kept).
+    lam_from_momentum: form x_t - x_{t-1} as -gamma_{t-1} * v_t instead of from a
+    stored x_{t-1}.
     adam: (beta1, beta2, eps) switches the update rule to Adam (mu is unused,
     the returned "v" is then the pair (m, v)).
     lars: (sizes, eta) switches it to LARS over those layers (double only).
@@ -299,6 +339,7 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     M = [[0] * N for _ in range(2)]   # G_{-1} = 0; its batch sizes are 0
     cur, prev = 0, 1
     history = []
+    gamma_prev = 0.0                   # step size of the previous applied update
     if adam is not None:
         m1 = np.zeros(P, dtype=ft)
         applied = 0
@@ -324,6 +365,9 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
                 applied += 1
         elif lam is None:
             upd_fn(x, v, G[prev], M[prev], gamma, mu, wd)
+        elif lam_from_momentum:
+            fn = sync_update_dcm if precision == "f64" else sync_update32_dcm
+            gamma_prev = gamma if fn(x, v, G[prev], M[prev], gamma, mu, wd, lam, gamma_prev) else 0.0
         elif precision == "f64":
             sync_update_dc(x, x_prev, v, G[prev], M[prev], gamma, mu, wd, lam)
         else:

@@ -500,6 +500,116 @@ def test_compensation_fp32_family_tracks_double_family():
     assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
 
 
+# The same correction with x_t - x_{t-1} read off the momentum (every applied
+# update is x_t = x_{t-1} - gamma_{t-1} v_t).  Pinned against the stored-iterate
+# form, which the pins above tie to Algorithm 1.
+
+def test_compensation_from_momentum_worked_example():
+    """x_t - x_{t-1} = (-0.1, +0.1), given once as stored iterates (the golden
+    example) and once as gamma_prev = 0.1, v = (1, -1)."""
+    gold = _read_golden("worked_example.txt")
+    x = np.array([0.9, -1.9])
+    v = np.array([1.0, -1.0])
+    G = [np.array([0.5, -0.25]) * 64]
+    assert orc.sync_update_dcm(x, v, G, [64], 0.1, 0.0, 0.0, 0.5, 0.1)
+    np.testing.assert_allclose(v, [float(f) for f in gold["dc_gtilde"]], rtol=1e-15)
+    np.testing.assert_allclose(x, [float(f) for f in gold["dc_x_next"]], rtol=1e-15)
+
+
+def test_compensation_from_momentum_equals_stored_iterate_form():
+    """Step by step with a step size that changes every iteration, an iteration
+    that applies nothing in the middle, momentum and weight decay on."""
+    rng = np.random.default_rng(14)
+    P, N = 257, 3
+    x0 = rng.standard_normal(P)
+    xa, xpa, va = x0.copy(), x0.copy(), np.zeros(P)
+    xb, vb = x0.copy(), np.zeros(P)
+    gamma_prev = 0.0
+    moved = 0.0
+    for t in range(9):
+        G = [rng.standard_normal(P) * 40 for _ in range(N)]
+        M = [0, 0, 0] if t == 4 else [32, 64, 32 * (1 + t % 3)]
+        gamma = 0.05 * (1 + t % 4)
+        x_before = xa.copy()
+        ra = orc.sync_update_dc(xa, xpa, va, G, M, gamma, 0.9, 5e-4, 0.5)
+        rb = orc.sync_update_dcm(xb, vb, G, M, gamma, 0.9, 5e-4, 0.5, gamma_prev)
+        assert ra == rb == (t != 4)
+        gamma_prev = gamma if rb else 0.0
+        np.testing.assert_allclose(xb, xa, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(vb, va, rtol=1e-12, atol=1e-13)
+        moved = max(moved, float(np.max(np.abs(xa - x_before))))
+    assert moved > 1e-2
+
+
+def test_compensation_from_momentum_whole_loop_and_no_previous_update():
+    rng = np.random.default_rng(15)
+    P, N, T, M_r = 513, 2, 7, 32
+    m = rng.integers(0, 3, size=(T, N))
+    m[3] = 0                                                    # an iteration with no samples at all
+    pool = [(rng.standard_normal(P) * 0.5).astype(F32) for _ in range(8)]
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+
+    def batches(t, i):
+        return [pool[(3 * t + 5 * i + j) % 8] for j in range(int(m[t, i]))]
+
+    args = (x0, N, T, M_r, F32(0.1), F32(0.9), F32(5e-4), batches)
+    xa, va, _ = orc.run(*args, lam=F32(0.5))
+    xb, vb, _ = orc.run(*args, lam=F32(0.5), lam_from_momentum=True)
+    xn, _, _ = orc.run(*args)
+    assert np.max(np.abs(xa - xn)) > 1e-4
+    np.testing.assert_allclose(xb, xa, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(vb, va, rtol=1e-11, atol=1e-13)
+    # gamma_prev = 0 (nothing applied before): the uncompensated update
+    x1, v1 = x0.astype(np.float64), rng.standard_normal(P)
+    x2, v2 = x1.copy(), v1.copy()
+    G = [pool[0].astype(np.float64) * 32]
+    orc.sync_update(x1, v1, G, [32], 0.1, 0.9, 5e-4)
+    orc.sync_update_dcm(x2, v2, G, [32], 0.1, 0.9, 5e-4, 0.5, 0.0)
+    np.testing.assert_array_equal(x2, x1)
+    np.testing.assert_array_equal(v2, v1)
+    # sum(M) == 0 touches nothing
+    assert orc.sync_update_dcm(x2, v2, G, [0], 0.1, 0.9, 5e-4, 0.5, 0.1) is False
+    np.testing.assert_array_equal(x2, x1)
+    np.testing.assert_array_equal(v2, v1)
+
+
+def test_compensation_from_momentum_fp32_family_tracks_double_family():
+    rng = np.random.default_rng(16)
+    P, N, T, M_r = 2051, 3, 6, 32
+    m = rng.integers(1, 4, size=(T, N))
+    pool = [(rng.standard_normal(P) * 0.5).astype(F32) for _ in range(8)]
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+
+    def batches(t, i):
+        return [pool[(3 * t + 5 * i + j) % 8] for j in range(int(m[t, i]))]
+
+    args = (x0, N, T, M_r, F32(0.1), F32(0.9), F32(5e-4), batches)
+    x64, v64, _ = orc.run(*args, precision="f64", lam=F32(0.5))                      # stored-iterate form, double
+    x32, v32, _ = orc.run(*args, precision="f32", lam=F32(0.5), lam_from_momentum=True)
+    assert np.max(np.abs(x32 - x64)) <= 2e-6 * np.max(np.abs(x64))
+    assert np.max(np.abs(v32 - v64)) <= 2e-6 * np.max(np.abs(v64))
+    # one update whose step size differs from the previous one's
+    g32 = [pool[1] * F32(32), pool[2] * F32(64)]
+    xs, vs = x0.copy(), (pool[3] * F32(4)).astype(F32)
+    xd, vd = xs.astype(np.float64), vs.astype(np.float64)
+    assert orc.sync_update32_dcm(xs, vs, g32, [32, 64], F32(0.1), F32(0.9), F32(5e-4), F32(0.5), F32(0.03))
+    assert orc.sync_update_dcm(xd, vd, [g.astype(np.float64) for g in g32], [32, 64], F32(0.1), F32(0.9),
+                               F32(5e-4), F32(0.5), F32(0.03))
+    xu, vu = x0.astype(np.float64), (pool[3] * F32(4)).astype(np.float64)
+    orc.sync_update(xu, vu, [g.astype(np.float64) for g in g32], [32, 64], F32(0.1), F32(0.9), F32(5e-4))
+    assert np.max(np.abs(vd - vu)) > 1e-3                        # a visible correction
+    assert np.max(np.abs(vs - vd)) <= 1e-6 * np.max(np.abs(vd))
+    assert np.max(np.abs(xs - xd)) <= 1e-6 * np.max(np.abs(xd))
+    # idle workers are skipped, stale buffers and all
+    stale = np.full(P, 1e30, dtype=F32)
+    xa, va = x0.copy(), np.ones(P, dtype=F32)
+    xb, vb = x0.copy(), np.ones(P, dtype=F32)
+    assert orc.sync_update32_dcm(xa, va, [stale, pool[0] * F32(32)], [0, 32], 0.1, 0.9, 5e-4, 0.5, 0.1)
+    assert orc.sync_update32_dcm(xb, vb, [pool[0] * F32(32)], [32], 0.1, 0.9, 5e-4, 0.5, 0.1)
+    np.testing.assert_array_equal(xa, xb)
+    np.testing.assert_array_equal(va, vb)
+
+
 # ---------------------------------------------------------------------------
 # 11. Adam behind the delayed synchronous mechanism (Section "Conclusions and
 #     Future Work" names it; the recursion is the published Adam algorithm)
