@@ -232,6 +232,9 @@ def main():
     ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
                     help="also apply the delayed gradient compensation with this coefficient "
                          "(abs_sync_update_dc; +8 B/param); default: off, the four-part path of the headline metric")
+    ap.add_argument("--compensation-from-momentum", action="store_true",
+                    help="with --compensation: take x_t - x_{t-1} from the momentum (abs_sync_update_dcm; "
+                         "no x_{t-1} buffer, no extra bytes)")
     ap.add_argument("--adam", action="store_true",
                     help="Adam (beta 0.9/0.999, eps 1e-8, lr 1e-3) as the update rule instead of momentum SGD "
                          "(abs_sync_update_adam; +8 B/param)")
@@ -282,11 +285,13 @@ def main():
             plans_wanted.append((f"{n} accumulate streams (workers balanced over them) | sync-update", True, n))
     if args.acc_streams > 1:
         plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
+    dcm = args.compensation is not None and args.compensation_from_momentum
     run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched,
+                    lam_from_momentum=dcm,
                     adam=(0.9, 0.999, 1e-8) if args.adam else None, lars=0.001 if args.lars else None)
     if args.adam:
         run.lr = 1e-3
-    comp = args.compensation is not None or args.adam
+    comp = (args.compensation is not None and not dcm) or args.adam    # a third state vector is moved
     calls = [run.plan_step(t) for t in range(total)]
     timings = {}
     for name, overlap, n_acc in plans_wanted:
@@ -347,7 +352,7 @@ def main():
             "samples_per_microbatch": w.n, "m_k": w.schedule + (str(list(w.ratio)) if w.ratio else ""),
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
             "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
-            "compensation_lambda": args.compensation, "batched_accumulate": args.batched,
+            "compensation_lambda": args.compensation, "compensation_from_momentum": dcm, "batched_accumulate": args.batched,
             "update_rule": "adam" if args.adam else ("lars" if args.lars else "momentum sgd"),
             "streams": best + ", double-buffered",
             "algorithmic_bytes_per_step": step_bytes // K_steps,

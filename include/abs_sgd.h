@@ -160,6 +160,28 @@ int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const
                        float lambda, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (3'm) The same compensation (Algorithm 1, "Compensate delayed gradients")
+ *     without a stored x_{t-1}: every applied update of this family is
+ *     x_t = x_{t-1} - lr_{t-1} * v_t, so x_t - x_{t-1} = -lr_{t-1} * v_t with v_t
+ *     the momentum as it stands on entry.  Equal to abs_sync_update_dc in exact
+ *     arithmetic (in fp32 it differs by the rounding of the previous write of x);
+ *     traffic is that of abs_sync_update, 4K + 16 B/param.
+ *
+ *   Order after Gbar: q = Gbar*Gbar; c = lambda*q; diff = (-lr_prev) * v[i];
+ *     Gtilde = fmaf(c, diff, Gbar); d = fmaf(wd, x[i], Gtilde); v[i] = fmaf(mu, v[i], d);
+ *     x[i] = fmaf(-lr, v[i], x[i]).
+ *
+ *   lr_prev  the lr of the update that produced the current params from the
+ *     previous ones through this family of calls; 0 when there was none, or when
+ *     the previous iteration returned ABS_EMPTY (x_t = x_{t-1}).  Only valid while
+ *     momentum is the v of that previous update, untouched since.
+ *   Other arguments, errors, ABS_EMPTY (no memory touched): as abs_sync_update.
+ * ---------------------------------------------------------------------- */
+int abs_sync_update_dcm(float *params, float *momentum, const float *const *acc,
+                        const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
+                        float lambda, float lr_prev, void *stream);
+
+/* ------------------------------------------------------------------------
  * (3'') Adam behind the delayed synchronous mechanism -- the update rule the
  *     paper's Section "Conclusions and Future Work" names as its next step.
  *     Same read pass over the K delayed accumulators; the state is the first
@@ -239,6 +261,12 @@ int abs_sync_update_dc_mt(abs_layout *layout, const abs_tensorset *params,
                           const abs_tensorset *params_prev, const abs_tensorset *momentum,
                           const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                           float mu, float wd, float lambda, void *stream);
+
+/* abs_sync_update_dcm over every tensor of the layout. */
+int abs_sync_update_dcm_mt(abs_layout *layout, const abs_tensorset *params,
+                           const abs_tensorset *momentum, const abs_tensorset *const *acc,
+                           const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
+                           float lr_prev, void *stream);
 
 /* abs_sync_update_adam over every tensor of the layout. */
 int abs_sync_update_adam_mt(abs_layout *layout, const abs_tensorset *params,
@@ -322,6 +350,16 @@ int abs_ctx_sync_update_dc(abs_ctx *ctx, float *params, float *params_prev, floa
 int abs_ctx_sync_update_dc_mt(abs_ctx *ctx, const abs_tensorset *params,
                               const abs_tensorset *params_prev, const abs_tensorset *momentum,
                               float lr, float mu, float wd, float lambda);
+
+/* Compensation from the momentum (abs_sync_update_dcm).  The context supplies
+ * lr_prev: the lr of its last call of this pair that returned ABS_OK, 0 before
+ * the first and after one that returned ABS_EMPTY.  Calls of the other update
+ * rules on the same context are not tracked. */
+int abs_ctx_sync_update_dcm(abs_ctx *ctx, float *params, float *momentum, float lr, float mu,
+                            float wd, float lambda);
+int abs_ctx_sync_update_dcm_mt(abs_ctx *ctx, const abs_tensorset *params,
+                               const abs_tensorset *momentum, float lr, float mu, float wd,
+                               float lambda);
 
 /* Adam (abs_sync_update_adam) from the PREVIOUS generation. */
 int abs_ctx_sync_update_adam(abs_ctx *ctx, float *params, float *exp_avg, float *exp_avg_sq, float lr,

@@ -46,6 +46,10 @@ SYMBOLS = {
     "abs_accumulate_mt": (_int, [_vp, _vp, _vp, _i64, _pi64, _vp]),
     "abs_accumulate_batch_mt": (_int, [_vp, _vp, _pvp, _int, _pi64, _pi64, _vp]),
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
+    "abs_sync_update_dcm": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _f, _vp]),
+    "abs_sync_update_dcm_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _vp]),
+    "abs_ctx_sync_update_dcm": (_int, [_vp, _vp, _vp, _f, _f, _f, _f]),
+    "abs_ctx_sync_update_dcm_mt": (_int, [_vp, _vp, _vp, _f, _f, _f, _f]),
     "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _i64, _vp]),
     "abs_sync_update_lars_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
@@ -323,6 +327,24 @@ def abs_sync_update_mt(layout, params, momentum, acc, counts, lr, mu, wd, stream
     return _check("abs_sync_update_mt", rc, allow_empty=True)
 
 
+def abs_sync_update_dcm(params, momentum, acc, counts, lr, mu, wd, lam, lr_prev, stream=None, P=None):
+    """Compensated abs_sync_update with x_t - x_{t-1} = -lr_prev * momentum (no x_{t-1} buffer)."""
+    n = params.numel() if P is None else int(P)
+    ptrs = _ptr_array([_dev_ptr(a) for a in acc])
+    rc = lib().abs_sync_update_dcm(_dev_ptr(params), _dev_ptr(momentum), ptrs, _i64_array(counts),
+                                   len(acc), n, float(lr), float(mu), float(wd), float(lam),
+                                   float(lr_prev), _stream_handle(stream))
+    return _check("abs_sync_update_dcm", rc, allow_empty=True)
+
+
+def abs_sync_update_dcm_mt(layout, params, momentum, acc, counts, lr, mu, wd, lam, lr_prev, stream=None):
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_dcm_mt(layout.handle, params.handle, momentum.handle, sets,
+                                      _i64_array(counts), len(acc), float(lr), float(mu), float(wd),
+                                      float(lam), float(lr_prev), _stream_handle(stream))
+    return _check("abs_sync_update_dcm_mt", rc, allow_empty=True)
+
+
 def abs_sync_update_dc_mt(layout, params, params_prev, momentum, acc, counts, lr, mu, wd, lam,
                           stream=None):
     sets = _ptr_array([a.handle.value for a in acc])
@@ -416,6 +438,15 @@ class Context:
                                              momentum.handle, float(lr), float(mu), float(wd), float(lam))
         return _check("abs_ctx_sync_update_dc_mt", rc, allow_empty=True)
 
+    def abs_sync_update_dcm(self, params, momentum, lr, mu, wd, lam):
+        if self.layout is None:
+            rc = lib().abs_ctx_sync_update_dcm(self.handle, _dev_ptr(params), _dev_ptr(momentum), float(lr),
+                                               float(mu), float(wd), float(lam))
+            return _check("abs_ctx_sync_update_dcm", rc, allow_empty=True)
+        rc = lib().abs_ctx_sync_update_dcm_mt(self.handle, params.handle, momentum.handle, float(lr),
+                                              float(mu), float(wd), float(lam))
+        return _check("abs_ctx_sync_update_dcm_mt", rc, allow_empty=True)
+
     def abs_sync_update_adam(self, params, exp_avg, exp_avg_sq, lr, beta1, beta2, eps, wd, step):
         if self.layout is None:
             rc = lib().abs_ctx_sync_update_adam(self.handle, _dev_ptr(params), _dev_ptr(exp_avg),
@@ -458,7 +489,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

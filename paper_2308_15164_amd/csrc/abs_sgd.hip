@@ -233,6 +233,7 @@ int launch_sync_flat(int rule, float *x, float *v, float *xp, const float *const
     case SGD: return launch_sync_flat_r<SGD>(x, v, xp, ptrs, n, P, h, vec_ok, s);
     case SGD_DC: return launch_sync_flat_r<SGD_DC>(x, v, xp, ptrs, n, P, h, vec_ok, s);
     case ADAM: return launch_sync_flat_r<ADAM>(x, v, xp, ptrs, n, P, h, vec_ok, s);
+    case SGD_DCM: return launch_sync_flat_r<SGD_DCM>(x, v, xp, ptrs, n, P, h, vec_ok, s);
     default: return ABS_EINVAL;
     }
 }
@@ -290,6 +291,7 @@ struct abs_ctx {
 
     std::vector<int> slot;               // worker k accumulates on s_acc[slot[k]]
     std::vector<int64_t> launches;       // accumulate launches of worker k in the current step
+    float lr_applied = 0.f;              // step size of the last abs_ctx_sync_update_dcm* call; 0 after an empty one
 
     hipStream_t stream_of(int k) const { return s_acc[(size_t)slot[(size_t)k]]; }
 };
@@ -383,6 +385,7 @@ void launch_sync_ragged(int rule, const abs_layout *L, float *const *xt, float *
     switch (rule) {
     case SGD: launch_sync_ragged_r<SGD>(L, xt, vt, pt, tabs, n, h, s); break;
     case SGD_DC: launch_sync_ragged_r<SGD_DC>(L, xt, vt, pt, tabs, n, h, s); break;
+    case SGD_DCM: launch_sync_ragged_r<SGD_DCM>(L, xt, vt, pt, tabs, n, h, s); break;
     default: launch_sync_ragged_r<ADAM>(L, xt, vt, pt, tabs, n, h, s); break;
     }
 }
@@ -490,10 +493,10 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
 }
 
 // Hyper-parameters of the three rules in one struct.
-static Hyper hyper_sgd(float lr, float mu, float wd, float lambda)
+static Hyper hyper_sgd(float lr, float mu, float wd, float lambda, float lr_prev = 0.f)
 {
     Hyper h = {};
-    h.lr = lr; h.mu = mu; h.wd = wd; h.lambda = lambda;
+    h.lr = lr; h.mu = mu; h.wd = wd; h.lambda = lambda; h.nlr_prev = -lr_prev;
     return h;
 }
 
@@ -515,7 +518,7 @@ static int sync_update_flat_impl(int rule, float *params, float *s1, float *s2, 
                                  const int64_t *counts, int K, int64_t P, Hyper h, void *stream)
 {
     if (!acc || P < 0) return ABS_EINVAL;
-    const bool has2 = rule != SGD;
+    const bool has2 = rule == SGD_DC || rule == ADAM;
     Combine c;
     int rc = plan_combine(counts, K, c);
     if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
@@ -561,6 +564,14 @@ int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const
 {
     return sync_update_flat_impl(SGD_DC, params, momentum, params_prev, acc, counts, K, P,
                                  hyper_sgd(lr, mu, wd, lambda), stream);
+}
+
+int abs_sync_update_dcm(float *params, float *momentum, const float *const *acc, const int64_t *counts,
+                        int K, int64_t P, float lr, float mu, float wd, float lambda, float lr_prev,
+                        void *stream)
+{
+    return sync_update_flat_impl(SGD_DCM, params, momentum, nullptr, acc, counts, K, P,
+                                 hyper_sgd(lr, mu, wd, lambda, lr_prev), stream);
 }
 
 int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const float *const *acc,
@@ -718,7 +729,7 @@ static int sync_update_mt_impl(int rule, abs_layout *L, const abs_tensorset *par
                                const int64_t *counts, int K, Hyper h, void *stream)
 {
     if (!L || !acc) return ABS_EINVAL;
-    const bool has2 = rule != SGD;
+    const bool has2 = rule == SGD_DC || rule == ADAM;
     Combine c;
     int rc = plan_combine(counts, K, c);
     if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
@@ -765,6 +776,14 @@ int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_
 {
     return sync_update_mt_impl(SGD_DC, L, params, momentum, params_prev, acc, counts, K,
                                hyper_sgd(lr, mu, wd, lambda), stream);
+}
+
+int abs_sync_update_dcm_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                           const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
+                           float mu, float wd, float lambda, float lr_prev, void *stream)
+{
+    return sync_update_mt_impl(SGD_DCM, L, params, momentum, nullptr, acc, counts, K,
+                               hyper_sgd(lr, mu, wd, lambda, lr_prev), stream);
 }
 
 int abs_sync_update_adam_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *exp_avg,
@@ -974,6 +993,31 @@ int abs_ctx_sync_update_dc_mt(abs_ctx *C, const abs_tensorset *params, const abs
     const int prev = C->cur ^ 1;
     return abs_sync_update_dc_mt(C->layout, params, params_prev, momentum, C->set[prev].data(),
                                  C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->s_upd);
+}
+
+int abs_ctx_sync_update_dcm(abs_ctx *C, float *params, float *momentum, float lr, float mu, float wd,
+                            float lambda)
+{
+    if (!C || C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    const int rc = abs_sync_update_dcm(params, momentum, C->acc[prev].data(), C->counts[prev].data(), C->K,
+                                       C->P, lr, mu, wd, lambda, C->lr_applied, C->s_upd);
+    if (rc == ABS_OK) C->lr_applied = lr;
+    else if (rc == ABS_EMPTY) C->lr_applied = 0.f;
+    return rc;
+}
+
+int abs_ctx_sync_update_dcm_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *momentum,
+                               float lr, float mu, float wd, float lambda)
+{
+    if (!C || !C->layout) return ABS_EINVAL;
+    const int prev = C->cur ^ 1;
+    const int rc = abs_sync_update_dcm_mt(C->layout, params, momentum, C->set[prev].data(),
+                                          C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->lr_applied,
+                                          C->s_upd);
+    if (rc == ABS_OK) C->lr_applied = lr;
+    else if (rc == ABS_EMPTY) C->lr_applied = 0.f;
+    return rc;
 }
 
 int abs_ctx_sync_update_adam(abs_ctx *C, float *params, float *exp_avg, float *exp_avg_sq, float lr,

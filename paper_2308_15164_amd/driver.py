@@ -27,6 +27,7 @@ class DeviceRun:
     overlap=False: both on one stream, in program order;
     acc_streams=n: the K workers' accumulations spread over n streams;
     lam          : coefficient of the delayed gradient compensation (None: off);
+    lam_from_momentum: take x_t - x_{t-1} from the momentum instead of a stored x_{t-1};
     adam         : (beta1, beta2, eps) switches the update rule to Adam;
     lars         : trust coefficient eta switches it to LARS (one layer per tensor);
     batched=True : a worker's m_k gradients of a step go in one abs_accumulate_batch
@@ -34,7 +35,7 @@ class DeviceRun:
     """
 
     def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False,
-                 adam=None, lars=None):
+                 adam=None, lars=None, lam_from_momentum=False):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
@@ -42,6 +43,7 @@ class DeviceRun:
         self.gdt = ABS_BF16 if w.grad_dtype == "bf16" else ABS_F32
         self.ragged = w.tensor_sizes is not None
         self.lam = None if lam is None else float(lam)   # delayed gradient compensation coefficient
+        self.dcm = self.lam is not None and bool(lam_from_momentum)      # no x_{t-1} buffer then
         self.batched = bool(batched)                     # one accumulate launch per worker and step
         self.adam = None if adam is None else tuple(float(t) for t in adam)   # (beta1, beta2, eps)
         self.adam_step = 0                               # applied Adam updates so far
@@ -58,7 +60,7 @@ class DeviceRun:
                     a.fill_(float("nan"))
             self.pool = [_upload(g) for g in pool]
             self.pool_ptr = [g.data_ptr() for g in self.pool]
-            self.xp = self.x.clone() if self.lam is not None else None    # x_{t-1}; starts equal to x_0
+            self.xp = self.x.clone() if (self.lam is not None and not self.dcm) else None   # x_{t-1}; starts equal to x_0
             if self.adam is not None:
                 self.xp = torch.zeros_like(self.x)                        # second moment
             torch.cuda.synchronize()
@@ -86,7 +88,7 @@ class DeviceRun:
             self.pool_sets = [TensorSet(self.layout, p, dtype=self.gdt) for p in self.pool_t]
             self.x_arg, self.v_arg = self.x_set, self.v_set
             self.xp_arg = None
-            if self.lam is not None or self.adam is not None:
+            if (self.lam is not None and not self.dcm) or self.adam is not None:
                 self.xp_t = [t.clone() if self.adam is None else torch.zeros_like(t) for t in self.x_t]
                 torch.cuda.synchronize()
                 self.xp_arg = TensorSet(self.layout, self.xp_t)
@@ -148,6 +150,8 @@ class DeviceRun:
             return ok
         if self.lam is None:
             return self.ctx.abs_sync_update(self.x_arg, self.v_arg, self.lr, self.mu, self.wd)
+        if self.dcm:
+            return self.ctx.abs_sync_update_dcm(self.x_arg, self.v_arg, self.lr, self.mu, self.wd, self.lam)
         return self.ctx.abs_sync_update_dc(self.x_arg, self.xp_arg, self.v_arg, self.lr, self.mu, self.wd,
                                            self.lam)
 
