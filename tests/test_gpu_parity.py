@@ -863,19 +863,23 @@ def test_trajectory_delay_invariant_on_gpu(absgd):
                                               ("cfg4_vgg16", None, False), ("cfg5_gpt2_ragged_bf16", None, False),
                                               ("cfg2_resnet18", 0.5, False), ("cfg5_gpt2_ragged_bf16", 0.5, False),
                                               ("cfg2_resnet18", None, True), ("cfg3_resnet50_bf16", None, True),
-                                              ("cfg5_gpt2_ragged_bf16", None, True)])
+                                              ("cfg5_gpt2_ragged_bf16", None, True),
+                                              ("cfg2_resnet18", "0.5 from momentum", False),
+                                              ("cfg5_gpt2_ragged_bf16", "0.5 from momentum", True)])
 def test_full_size_sampled(absgd, name, lam, batched):
     """Every output element depends only on the same index of the inputs, so the
     oracle runs on a sample of indices gathered from the very same host arrays."""
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
+    dcm = isinstance(lam, str)                   # compensation with x_t - x_{t-1} taken from the momentum
+    lam = float(lam.split()[0]) if dcm else lam
     print(f"[case] full size {name}: generating inputs", flush=True)
     x0 = wl.initial_params(w)
     R = 4
     pool = wl.gradient_pool(w, pool=R)
     sched = wl.schedule(w)
     print(f"[case] full size {name}: device run, two streams", flush=True)
-    run = DeviceRun(w, x0, pool, sched, overlap=True, lam=lam, batched=batched)
+    run = DeviceRun(w, x0, pool, sched, overlap=True, lam=lam, batched=batched, lam_from_momentum=dcm)
     run.run(w.steps)
     idx = wl.sample_indices(w.P, 200_000, w.seed)
     if w.tensor_sizes is not None:       # both sides of every tensor boundary
@@ -890,8 +894,8 @@ def test_full_size_sampled(absgd, name, lam, batched):
     print(f"[case] full size {name}: oracle on {idx.size} sampled elements", flush=True)
     x0s = np.ascontiguousarray(x0[idx])
     pools = [np.ascontiguousarray(g[idx]) for g in pool]
-    x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R, lam=lam)
-    x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R, lam=lam)
+    x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R, lam=lam, lam_from_momentum=dcm)
+    x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R, lam=lam)   # Algorithm 1 as printed
     assert counts == h32 == h64
     _assert_bitexact(gx, x32, f"{name} sampled x")
     _assert_bitexact(gv, v32, f"{name} sampled v")
@@ -972,13 +976,14 @@ def test_more_than_2_31_elements(absgd):
 # the paper's own setting, long run: drift of the fp32 path against the double oracle
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("name,steps", [("paper_static", 6200), ("paper_dynamic", 1500),
-                                        ("paper_static_dynamic", 1500)])
-def test_paper_setting_long_run(absgd, name, steps):
+@pytest.mark.parametrize("name,steps,dcm", [("paper_static", 6200, False), ("paper_dynamic", 1500, False),
+                                            ("paper_static_dynamic", 1500, False), ("paper_dynamic", 3000, True)])
+def test_paper_setting_long_run(absgd, name, steps, dcm):
     """N = 4 workers, reference batch 32, plain SGD with lr 0.01 and compensation 0.5
     (Section "Hyper-parameters"), the three heterogeneity structures of Section
     "Experiments", full ResNet18-sized vector, the paper's 6,200 iterations for the static
-    cluster.  Sampled elements against both oracles."""
+    cluster.  Sampled elements against both oracles.  dcm: the compensation reads
+    x_t - x_{t-1} off the momentum; the double oracle stays Algorithm 1 as printed."""
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
     lam = 0.5
@@ -987,7 +992,7 @@ def test_paper_setting_long_run(absgd, name, steps):
     R = 8
     pool = wl.gradient_pool(w, pool=R)
     sched = wl.schedule(w, steps)
-    run = DeviceRun(w, x0, pool, sched, overlap=True, acc_streams=2, lam=lam)
+    run = DeviceRun(w, x0, pool, sched, overlap=True, acc_streams=2, lam=lam, lam_from_momentum=dcm)
     print(f"[case] long run {name}: device", flush=True)
     for t in range(steps):
         run.step(t)
@@ -1004,7 +1009,7 @@ def test_paper_setting_long_run(absgd, name, steps):
     print(f"[case] long run {name}: oracle on {idx.size} sampled elements", flush=True)
     x0s = np.ascontiguousarray(x0[idx])
     pools = [np.ascontiguousarray(g[idx]) for g in pool]
-    x32, v32, _ = _oracle_trajectory(w, x0s, pools, sched, steps, "f32", R, lam=lam)
+    x32, v32, _ = _oracle_trajectory(w, x0s, pools, sched, steps, "f32", R, lam=lam, lam_from_momentum=dcm)
     x64, v64, _ = _oracle_trajectory(w, x0s, pools, sched, steps, "f64", R, lam=lam)
     _assert_bitexact(gx, x32, f"{name} long run x")
     _assert_bitexact(gv, v32, f"{name} long run v")
