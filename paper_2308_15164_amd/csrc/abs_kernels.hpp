@@ -656,7 +656,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void copy_ragged(const Chunk *__restrict
 //   1. lars_reduce : Gbar = (sum_k acc_k) / M is formed once, written to a
 //                    workspace, and each workgroup leaves the sums of Gbar^2 and
 //                    x^2 over its chunk (4K + 8 B/param);
-//   2. lars_rates  : one wavefront per tensor adds its chunks' sums and turns
+//   2. lars_rates  : one workgroup per tensor adds its chunks' sums and turns
 //                    them into the tensor's step factor (negligible traffic);
 //   3. lars_update : v = fma(mu, v, step_l * fma(wd, x, Gbar)); x = x - v
 //                    (20 B/param, independent of K).
@@ -769,24 +769,34 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
     }
 }
 
-// One wavefront per tensor: chunk_begin[t] .. chunk_begin[t+1] are its chunks.
+// One workgroup per tensor: chunk_begin[t] .. chunk_begin[t+1] are its chunks
+// (thousands for an embedding matrix, so the reads are spread over the workgroup
+// and issued several at a time; the order of the additions stays fixed).
 //   rate = eta*||x|| / (||g|| + wd*||x||)  (1 if either norm is 0);  step[t] = (float)(lr * rate)
-__global__ __launch_bounds__(64) void lars_rates(const int32_t *__restrict__ chunk_begin,
-                                                const double *__restrict__ partials,
-                                                float *__restrict__ step, double lr, double wd, double eta)
+__global__ __launch_bounds__(ABS_BLOCK) void lars_rates(const int32_t *__restrict__ chunk_begin,
+                                                       const double *__restrict__ partials,
+                                                       float *__restrict__ step, double lr, double wd, double eta)
 {
-    const int t = blockIdx.x, lane = threadIdx.x;
+    const int t = blockIdx.x;
+    const int begin = chunk_begin[t], end = chunk_begin[t + 1];
     double sx = 0.0, sg = 0.0;
-    for (int c = chunk_begin[t] + lane; c < chunk_begin[t + 1]; c += 64) {
+    int c = begin + (int)threadIdx.x;
+    for (; c + 3 * BLOCK < end; c += 4 * BLOCK) {
+        double px[4], pg[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            px[u] = partials[2 * (int64_t)(c + u * BLOCK)];
+            pg[u] = partials[2 * (int64_t)(c + u * BLOCK) + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { sx += px[u]; sg += pg[u]; }
+    }
+    for (; c < end; c += BLOCK) {
         sx += partials[2 * (int64_t)c];
         sg += partials[2 * (int64_t)c + 1];
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        sx += __shfl_down(sx, off);
-        sg += __shfl_down(sg, off);
-    }
-    if (lane == 0) {
+    block_sum2(sx, sg);
+    if (threadIdx.x == 0) {
         const double xn = sqrt(sx), gn = sqrt(sg);
         const double rate = (xn > 0.0 && gn > 0.0) ? eta * xn / (gn + wd * xn) : 1.0;
         step[t] = (float)(lr * rate);

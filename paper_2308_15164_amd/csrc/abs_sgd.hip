@@ -827,7 +827,7 @@ int abs_sync_update_lars_mt(abs_layout *L, const abs_tensorset *params, const ab
     const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
     hipLaunchKernelGGL(lars_reduce_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, gt, tabs, c.n, L->tile,
                        (float)c.M, L->d_partials);
-    hipLaunchKernelGGL(lars_rates, dim3((unsigned)L->sizes.size()), dim3(64), 0, s, L->d_chunk_begin,
+    hipLaunchKernelGGL(lars_rates, dim3((unsigned)L->sizes.size()), dim3(BLOCK), 0, s, L->d_chunk_begin,
                        L->d_partials, L->d_step, (double)lr, (double)wd, (double)eta);
     hipLaunchKernelGGL(lars_update_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, gt, L->d_step,
                        L->tile, mu, wd);
