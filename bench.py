@@ -116,8 +116,9 @@ def kernel_event_pass(run, plans, t0, steps, torch):
 
 
 def probe_ceilings(torch, nbytes=1 << 30, reps=20):
-    """Copy / read / write rates of plain streaming kernels on this machine (context
-    for the roofline fraction; not part of the method)."""
+    """Copy / read / write / triad (a += s*b: the accumulate's two reads and one
+    write) rates of plain streaming kernels on this machine (context for the roofline
+    fraction; not part of the method)."""
     import ctypes
     path = os.path.join(ROOT, "paper_2308_15164_amd", "libabs_probe.so")
     if not os.path.exists(path):
@@ -127,6 +128,7 @@ def probe_ceilings(torch, nbytes=1 << 30, reps=20):
     L.probe_copy.argtypes = [vp, vp, i64, vp]
     L.probe_read.argtypes = [vp, i64, vp, vp]
     L.probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
+    L.probe_triad.argtypes = [vp, vp, i64, ctypes.c_float, vp]
     a = torch.ones(nbytes // 4, device="cuda")
     b = torch.ones(nbytes // 4, device="cuda")
     sink = torch.zeros(4, device="cuda")
@@ -134,7 +136,8 @@ def probe_ceilings(torch, nbytes=1 << 30, reps=20):
     out = {}
     for name, fn, moved in (("copy", lambda: L.probe_copy(a.data_ptr(), b.data_ptr(), nbytes, st), 2 * nbytes),
                             ("read", lambda: L.probe_read(a.data_ptr(), nbytes, sink.data_ptr(), st), nbytes),
-                            ("write", lambda: L.probe_write(a.data_ptr(), nbytes, 1.0, st), nbytes)):
+                            ("write", lambda: L.probe_write(a.data_ptr(), nbytes, 1.0, st), nbytes),
+                            ("triad", lambda: L.probe_triad(a.data_ptr(), b.data_ptr(), nbytes, 0.0, st), 3 * nbytes)):
         for _ in range(3):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -378,6 +381,8 @@ def main():
     }
     if out["box_ceilings"]:
         out["pct_of_box_copy_rate"] = 100.0 * gbs / out["box_ceilings"]["copy_GBs"]
+        # the dominant kernel against a plain kernel of its own read:write mix at 1 GiB per vector
+        out["roofline"]["frac_of_box_triad"] = achieved / out["box_ceilings"]["triad_GBs"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:])
     print(json.dumps(out))

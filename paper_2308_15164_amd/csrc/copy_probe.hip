@@ -1,7 +1,7 @@
 // Plain streaming kernels of known size, separate from the method's library.
 // They serve two purposes in the benchmark: (1) calibrating the profiler's
 // HBM byte counters against a transfer whose size is known, and (2) measuring
-// the copy / read / write ceilings of the box the benchmark runs on, to put the
+// the copy / read / write / triad ceilings of the box the benchmark runs on, to put the
 // method's kernels in context.  Nothing in the method calls them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -53,6 +53,28 @@ __global__ __launch_bounds__(BLOCK) void probe_write_kernel(f32x4 *__restrict__ 
     }
 }
 
+// a = a + s * b in place: two reads and one write per element, the traffic mix
+// of a steady gradient accumulation, with no structure beyond one vector per lane.
+__global__ __launch_bounds__(BLOCK) void probe_triad_kernel(f32x4 *__restrict__ a, const f32x4 *__restrict__ b,
+                                                           int64_t nvec, float s)
+{
+    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+    f32x4 ra[VPT], rb[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) {
+            ra[u] = __builtin_nontemporal_load(a + i);
+            rb[u] = __builtin_nontemporal_load(b + i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) __builtin_nontemporal_store(ra[u] + s * rb[u], a + i);
+    }
+}
+
 inline unsigned grid_for(int64_t nvec) { return (unsigned)((nvec + BLOCK * VPT - 1) / (BLOCK * VPT)); }
 }  // namespace
 
@@ -83,6 +105,16 @@ int probe_write(void *dst, int64_t nbytes, float val, void *stream)
     const int64_t nvec = nbytes / 16;
     hipLaunchKernelGGL(probe_write_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
                        (f32x4 *)dst, nvec, val);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// a (read and written) and b (read): DEVICE, 16-byte aligned, nbytes each.
+int probe_triad(void *a, const void *b, int64_t nbytes, float s, void *stream)
+{
+    if (!a || !b || nbytes <= 0 || (nbytes & 15) || ((uintptr_t)a & 15) || ((uintptr_t)b & 15)) return -1;
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(probe_triad_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
+                       (f32x4 *)a, (const f32x4 *)b, nvec, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
