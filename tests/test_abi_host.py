@@ -165,6 +165,11 @@ def test_update_rule_host_checks():
     # compensation: the previous-iterate buffer must be distinct
     assert L.abs_sync_update_dc(16, 16, 32, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, None) == absgd.ABS_EINVAL
     assert L.abs_sync_update_dc(16, None, 32, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, None) == absgd.ABS_EINVAL
+    # compensation from the momentum: no third vector; an empty step touches nothing and says so
+    assert L.abs_sync_update_dcm(16, 32, arr, zero, 1, 8, 0.1, 0.9, 0.0, 0.5, 0.1, None) == absgd.ABS_EMPTY
+    assert L.abs_sync_update_dcm(16, 16, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, 0.1, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_dcm(None, 32, arr, cnt, 1, 8, 0.1, 0.9, 0.0, 0.5, 0.1, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_dcm(16, 32, arr, cnt, 1, 0, 0.1, 0.9, 0.0, 0.5, 0.1, None) == absgd.ABS_OK   # P == 0
     # Adam: step >= 1, betas in [0, 1), eps >= 0; an empty step is reported before anything else happens
     assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, None) == absgd.ABS_EINVAL
     assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 1.5, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EINVAL
