@@ -176,3 +176,17 @@ def test_update_rule_host_checks():
     assert L.abs_sync_update_adam(16, 32, 48, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, -1.0, 0.0, 1, None) == absgd.ABS_EINVAL
     assert L.abs_sync_update_adam(16, 32, 48, arr, zero, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EMPTY
     assert L.abs_sync_update_adam(16, 32, 32, arr, cnt, 1, 8, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == absgd.ABS_EINVAL
+
+
+def test_header_is_strict_c99_and_the_c_caller_builds():
+    """include/abs_sgd.h compiles as ISO C99 with every warning an error, and the
+    plain-C test program links against the library (no GPU needed to build)."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "abs_sgd.h")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                   check=True, timeout=60)
+    from oracle.abs_oracle import build_oracle
+    from tests.c_abi.build_check import build_abi_check
+    build_oracle()
+    exe = build_abi_check(force=True)
+    assert os.access(exe, os.X_OK)

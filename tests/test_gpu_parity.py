@@ -1021,3 +1021,19 @@ def test_paper_setting_long_run(absgd, name, steps, dcm):
     # fp32 iterate add up like a random walk, far below the linear worst case steps * 2^-24)
     assert drift_x <= 1e-5
     assert drift_v <= 1e-5
+
+
+# ---------------------------------------------------------------------------
+# the C ABI from plain C: no Python binding, no PyTorch in the process
+# ---------------------------------------------------------------------------
+
+def test_c_abi_from_plain_c(absgd):
+    """tests/c_abi/abi_check.c: hipMalloc'ed buffers, the library's calls, the C oracle."""
+    import subprocess
+    from tests.c_abi.build_check import build_abi_check
+    exe = build_abi_check()
+    print(f"[case] {exe}", flush=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(r.stdout, r.stderr, flush=True)
+    assert r.returncode == 0
+    assert r.stdout.strip().endswith("abi_check: OK")
