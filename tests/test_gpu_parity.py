@@ -1024,6 +1024,76 @@ def test_paper_setting_long_run(absgd, name, steps, dcm):
 
 
 # ---------------------------------------------------------------------------
+# special values: subnormals, signed zeros, the largest finite values, infinities, NaN
+# ---------------------------------------------------------------------------
+
+_SPECIALS = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-40, -3e-39, 1.1754944e-38, -1.1754944e-38, 1e-30, -1e-20,
+                      1.0, -1.0, 3.0, 1e20, -1e30, 3.4028235e38, -3.4028235e38, np.inf, -np.inf, np.nan],
+                     dtype=F32)
+
+
+def _assert_same_ieee(got, want, what):
+    """Bit-exact, except that any NaN matches any NaN (payloads are not part of the contract)."""
+    gn, wn = np.isnan(got), np.isnan(want)
+    assert np.array_equal(gn, wn), f"{what}: NaN positions differ"
+    _assert_bitexact(np.where(gn, F32(0), got), np.where(wn, F32(0), want), what)
+
+
+def test_special_values(absgd):
+    """Every pair (and for the update, a sample of triples) of special fp32 values through
+    accumulate and the update rules: IEEE semantics on both sides, subnormals kept."""
+    S = _SPECIALS
+    n = S.size
+    a0, g0 = (t.ravel().astype(F32) for t in np.meshgrid(S, S, indexing="ij"))      # all pairs
+    P = a0.size
+    print(f"[case] special values, {P} pairs", flush=True)
+    with np.errstate(all="ignore"):
+        for nn in (1, 32, 3):
+            for dtype in ("f32", "bf16"):
+                g = g0 if dtype == "f32" else wl.to_bf16_bits(np.where(np.isnan(g0), F32(0), g0))
+                for first in (True, False):
+                    acc_d = _up(a0)
+                    cnt = absgd.Count(0 if first else 32)
+                    absgd.abs_accumulate(acc_d, _up(g), nn, cnt, grad_dtype=absgd.ABS_BF16 if dtype == "bf16" else absgd.ABS_F32)
+                    want = a0.copy()
+                    orc.accumulate32(want, g, nn, first=first)
+                    _assert_same_ieee(acc_d.cpu().numpy(), want, f"accumulate {dtype} n={nn} first={first}")
+        # update rules: x from one axis, the accumulators from the other, v cycling through the table
+        x0, s0 = a0, g0
+        v0 = S[(np.arange(P) * 7 + 3) % n].astype(F32)
+        s1 = S[(np.arange(P) * 11 + 5) % n].astype(F32)
+        for counts in ([32, 64], [1, 0], [3, 5]):
+            x_d, v_d = _up(x0), _up(v0)
+            absgd.abs_sync_update(x_d, v_d, [_up(s0), _up(s1)], counts, 0.1, 0.9, 5e-4)
+            xw, vw = x0.copy(), v0.copy()
+            orc.sync_update32(xw, vw, [s0, s1], counts, 0.1, 0.9, 5e-4)
+            _assert_same_ieee(x_d.cpu().numpy(), xw, f"sync-update x counts={counts}")
+            _assert_same_ieee(v_d.cpu().numpy(), vw, f"sync-update v counts={counts}")
+            x_d, v_d, p_d = _up(x0), _up(v0), _up(s1)
+            absgd.abs_sync_update_dc(x_d, p_d, v_d, [_up(s0), _up(s1)], counts, 0.1, 0.9, 5e-4, 0.5)
+            xw, vw, pw = x0.copy(), v0.copy(), s1.copy()
+            orc.sync_update32_dc(xw, pw, vw, [s0, s1], counts, 0.1, 0.9, 5e-4, 0.5)
+            _assert_same_ieee(x_d.cpu().numpy(), xw, f"dc x counts={counts}")
+            _assert_same_ieee(v_d.cpu().numpy(), vw, f"dc v counts={counts}")
+            _assert_same_ieee(p_d.cpu().numpy(), pw, f"dc x_prev counts={counts}")
+            x_d, v_d = _up(x0), _up(v0)
+            absgd.abs_sync_update_dcm(x_d, v_d, [_up(s0), _up(s1)], counts, 0.1, 0.9, 5e-4, 0.5, 0.07)
+            xw, vw = x0.copy(), v0.copy()
+            orc.sync_update32_dcm(xw, vw, [s0, s1], counts, 0.1, 0.9, 5e-4, 0.5, 0.07)
+            _assert_same_ieee(x_d.cpu().numpy(), xw, f"dcm x counts={counts}")
+            _assert_same_ieee(v_d.cpu().numpy(), vw, f"dcm v counts={counts}")
+            # Adam: second moment must be non-negative for the square root to mean anything
+            m0, q0 = v0, np.abs(s1)
+            x_d, m_d, q_d = _up(x0), _up(m0), _up(q0)
+            absgd.abs_sync_update_adam(x_d, m_d, q_d, [_up(s0), _up(s1)], counts, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 3)
+            xw, mw, qw = x0.copy(), m0.copy(), q0.copy()
+            orc.sync_update32_adam(xw, mw, qw, [s0, s1], counts, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 3)
+            _assert_same_ieee(m_d.cpu().numpy(), mw, f"adam m counts={counts}")
+            _assert_same_ieee(q_d.cpu().numpy(), qw, f"adam v counts={counts}")
+            _assert_same_ieee(x_d.cpu().numpy(), xw, f"adam x counts={counts}")
+
+
+# ---------------------------------------------------------------------------
 # the C ABI from plain C: no Python binding, no PyTorch in the process
 # ---------------------------------------------------------------------------
 
