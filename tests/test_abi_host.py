@@ -190,3 +190,51 @@ def test_header_is_strict_c99_and_the_c_caller_builds():
     build_oracle()
     exe = build_abi_check(force=True)
     assert os.access(exe, os.X_OK)
+
+
+def test_double_buffer_bookkeeping_without_a_gpu():
+    """With P = 0 no kernel is launched, so the context's host side runs anywhere:
+    per-generation sample counts, the flip, the empty first iteration (G_{-1} = 0 has
+    no samples), and the argument checks."""
+    L = absgd.lib()
+    K = 3
+    null = (ctypes.c_void_p * K)()
+    ctx = ctypes.c_void_p()
+    assert L.abs_ctx_create(ctypes.byref(ctx), K, 0, null, null, None, None) == absgd.ABS_OK
+    out = (ctypes.c_int64 * K)()
+
+    def counts(which):
+        assert L.abs_ctx_counts(ctx, which, out) == absgd.ABS_OK
+        return list(out)
+
+    # iteration 0: nothing to apply yet
+    assert L.abs_ctx_sync_update(ctx, None, None, 0.1, 0.9, 0.0) == absgd.ABS_EMPTY
+    for k, m in enumerate((2, 0, 3)):
+        for _ in range(m):
+            assert L.abs_ctx_accumulate(ctx, k, None, absgd.ABS_F32, 32) == absgd.ABS_OK
+    n2 = (ctypes.c_int64 * 2)(16, 48)
+    g2 = (ctypes.c_void_p * 2)()
+    assert L.abs_ctx_accumulate_batch(ctx, 1, g2, absgd.ABS_F32, 2, n2) == absgd.ABS_OK
+    assert counts(0) == [64, 64, 96] and counts(1) == [0, 0, 0]
+    assert L.abs_ctx_accumulate(ctx, K, None, absgd.ABS_F32, 32) == absgd.ABS_EINVAL        # no such worker
+    assert L.abs_ctx_accumulate(ctx, 0, None, absgd.ABS_F32, 0) == absgd.ABS_EINVAL        # a batch has samples
+    assert L.abs_ctx_set_accumulate_streams(ctx, null, 2) == absgd.ABS_EINVAL              # too late: counts moved
+    assert counts(0) == [64, 64, 96]
+    assert L.abs_swap_buffers(ctx) == absgd.ABS_OK
+    # iteration 1: the previous generation is what was accumulated, the current one starts empty
+    assert counts(0) == [0, 0, 0] and counts(1) == [64, 64, 96]
+    assert L.abs_ctx_sync_update(ctx, None, None, 0.1, 0.9, 0.0) == absgd.ABS_OK            # P = 0: nothing to launch
+    assert L.abs_ctx_accumulate(ctx, 2, None, absgd.ABS_BF16, 8) == absgd.ABS_OK
+    assert L.abs_swap_buffers(ctx) == absgd.ABS_OK
+    assert counts(0) == [0, 0, 0] and counts(1) == [0, 0, 8]
+    assert L.abs_swap_buffers(ctx) == absgd.ABS_OK
+    # an iteration in which no worker accumulated anything applies nothing
+    assert counts(1) == [0, 0, 0]
+    assert L.abs_ctx_sync_update(ctx, None, None, 0.1, 0.9, 0.0) == absgd.ABS_EMPTY
+    assert L.abs_ctx_sync_update_dcm(ctx, None, None, 0.1, 0.9, 0.0, 0.5) == absgd.ABS_EMPTY
+    # flat contexts refuse the ragged calls and the other way round
+    assert L.abs_ctx_sync_update_mt(ctx, None, None, 0.1, 0.9, 0.0) == absgd.ABS_EINVAL
+    assert L.abs_ctx_counts(ctx, 2, out) == absgd.ABS_EINVAL
+    assert L.abs_ctx_destroy(ctx) == absgd.ABS_OK
+    assert L.abs_ctx_create(ctypes.byref(ctx), 0, 0, null, null, None, None) == absgd.ABS_EINVAL
+    assert L.abs_ctx_create(ctypes.byref(ctx), 65, 0, null, null, None, None) == absgd.ABS_EINVAL
