@@ -69,12 +69,18 @@ def dominant_kernel(w, batched=False):
     return f"absk::accumulate_{kind}<{bf}, *, {'*' if batched else '1'}>"
 
 
-def time_steps(run, plans, t0, steps, torch):
+HOST_ISSUE = {}    # seconds the host needed to enqueue the last timed region's steps
+
+
+def time_steps(run, plans, t0, steps, torch, tag=None):
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for t in range(t0, t0 + steps):
         run.step(t, plans[t])
+    t_issued = time.perf_counter()
     torch.cuda.synchronize()
+    if tag is not None:
+        HOST_ISSUE[tag] = t_issued - t_start
     return time.perf_counter() - t_start
 
 
@@ -300,7 +306,7 @@ def main():
     for name, overlap, n_acc in plans_wanted:
         run.configure_streams(overlap, n_acc)
         time_steps(run, calls, 0, max(W, 1), torch)        # also refills the delayed generation
-        timings[name] = time_steps(run, calls, W, K_steps, torch)
+        timings[name] = time_steps(run, calls, W, K_steps, torch, tag=name)
     best = min(timings, key=timings.get)
     dt = timings[best]
     dt_serial = timings["one stream"]
@@ -364,6 +370,9 @@ def main():
         "params_per_s": w.P * K_steps / dt,
         "overlap_speedup": dt_serial / dt_overlap,
         "ms_per_step_by_stream_plan": {k: v / K_steps * 1e3 for k, v in timings.items()},
+        # time the host needed to enqueue a step (binding + launches + event joins): when it
+        # approaches ms_per_step the workload is bound by launches, not by the kernels
+        "host_issue_ms_per_step": HOST_ISSUE[best] / K_steps * 1e3,
         "roofline": {
             "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
