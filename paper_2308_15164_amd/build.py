@@ -14,6 +14,9 @@ PROBE_LIB = os.path.join(HERE, "libabs_probe.so")
 # instruction selection is disabled on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-ffp-contract=off", "-fno-fast-math",
+         # the arithmetic contract needs IEEE divide and square root and fp32 subnormals kept:
+         # these are hipcc's defaults, stated here so that a changed default cannot alter results
+         "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-flush-denormals-to-zero",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-parameter"]
 
