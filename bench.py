@@ -384,7 +384,9 @@ def main():
         "sync_update_kernel": {
             "achieved": sync_gbs, "unit": "GB/s", "frac": sync_gbs / HBM_PEAK_GBS,
             "algorithmic_bytes_per_launch": sync_bytes, "avg_launch_ms": sync_avg_ms,
-            "measured": "HIP events around the sync-update launch, one-stream plan, same steps",
+            "measured": "HIP events around the single sync-update launch of each step, one-stream plan, same "
+                        "steps; a bracket around one launch also holds ~5 us of dispatch latency, so this is "
+                        "a lower bound on the kernel's rate (the kernel trace under profiles/ has its own duration)",
         },
         "box_ceilings": probe_ceilings(torch),
     }
