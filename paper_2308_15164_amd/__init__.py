@@ -360,7 +360,7 @@ def abs_sync_update_adam_mt(layout, params, exp_avg, exp_avg_sq, acc, counts, lr
     rc = lib().abs_sync_update_adam_mt(layout.handle, params.handle, exp_avg.handle, exp_avg_sq.handle, sets,
                                        _i64_array(counts), len(acc), float(lr), float(beta1), float(beta2),
                                        float(eps), float(wd), int(step), _stream_handle(stream))
-    return _check("abs_sync_update_adam_mt", "abs_sync_update_lars_mt", rc, allow_empty=True)
+    return _check("abs_sync_update_adam_mt", rc, allow_empty=True)
 
 
 def abs_sync_update_lars_mt(layout, params, momentum, gbar, acc, counts, lr, mu, wd, eta, stream=None):

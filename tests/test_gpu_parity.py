@@ -614,6 +614,146 @@ def test_trajectory_adam(absgd, name):
 
 
 # ---------------------------------------------------------------------------
+# both memory flavours of every kernel (cached / streaming) at sizes with tails: the
+# size-based choice only reaches the streaming flavour above 40 M parameters
+# ---------------------------------------------------------------------------
+
+@pytest.fixture
+def policy(absgd, request):
+    absgd.abs_set_cache_policy(*request.param)
+    yield request.param
+    absgd.abs_set_cache_policy(-1, -1)
+
+
+@pytest.mark.parametrize("policy", [(0, 0), (1, 1), (1, 0), (0, 1)], indirect=True)
+def test_cache_flavours_give_the_same_bits(absgd, policy):
+    print(f"[case] cache policy {policy}", flush=True)
+    for dtype in ("f32", "bf16"):
+        test_accumulate_matches_oracle(absgd, dtype, 3 * 4096 + 1029)
+        test_accumulate_batch_equals_sequential(absgd, dtype, 5)
+    _sync_case(absgd, 4, 100_003, [64, 64, 128, 256], seed=1401)
+    _sync_case(absgd, 18, 4096 + 11, [32] * 18, seed=1402)
+    _sync_dc_case(absgd, 3, 100_003, [32, 64, 32], seed=1403)
+    _sync_dcm_case(absgd, 3, 100_003, [32, 64, 32], seed=1404)
+    _sync_adam_case(absgd, 3, 100_003, [32, 64, 32], seed=1405)
+    _ragged_case(absgd, [4096 + 11, 8192, 4095, 2], [32, 64, 32], seed=1406, dtype="bf16", misalign=True)
+    _lars_case(absgd, [4096 * 3 + 5, 1, 700], [32, 64], seed=1407)
+    _trajectory_case(absgd, "tiny_tail_bf16", lam=0.5)
+
+
+# ---------------------------------------------------------------------------
+# the ragged (_mt) entry points, call by call: every tensor a separate allocation
+# ---------------------------------------------------------------------------
+
+def _ragged_case(absgd, sizes, counts, seed, dtype="f32", misalign=False):
+    """accumulate_mt (overwrite, then on top), accumulate_batch_mt, and every update rule
+    with a fixed-order fp32 restatement over one layout; the oracle sees the concatenation."""
+    rng = np.random.default_rng(seed)
+    P, K, T = int(sum(sizes)), len(counts), len(sizes)
+    off = wl.tensor_offsets(sizes)
+    print(f"[case] ragged T={T} P={P} K={K} {dtype} misalign={misalign}", flush=True)
+
+    def split(a, fill=None):
+        """One allocation per tensor; misalign: start one element into a larger buffer."""
+        out = []
+        for t in range(T):
+            part = np.ascontiguousarray(a[off[t]:off[t + 1]])
+            if misalign and t % 2 == 0:
+                pad = np.zeros(part.size + 3, dtype=part.dtype)
+                pad[1:1 + part.size] = part
+                out.append(_up(pad)[1:1 + part.size])
+            else:
+                out.append(_up(part))
+        return out
+
+    cat = lambda ts: np.concatenate([t.cpu().numpy() for t in ts]) if P else np.zeros(0, dtype=F32)
+    lay = absgd.Layout(sizes)
+    gdt = absgd.ABS_BF16 if dtype == "bf16" else absgd.ABS_F32
+    grads = [_grad(rng, P, dtype) for _ in range(4)]
+    gsets = [absgd.TensorSet(lay, split(g), dtype=gdt) for g in grads]
+
+    # Step 2 into NaN-filled accumulators: overwrite, one on top, then a batch of two
+    acc_t = split(np.full(P, np.nan, dtype=F32))
+    aset = absgd.TensorSet(lay, acc_t)
+    cnt = absgd.Count(0)
+    absgd.abs_accumulate_mt(lay, aset, gsets[0], 32, cnt)
+    absgd.abs_accumulate_mt(lay, aset, gsets[1], 64, cnt)
+    absgd.abs_accumulate_batch_mt(lay, aset, [gsets[2], gsets[3]], [32, 16], cnt)
+    assert cnt.value == 144
+    want = np.zeros(P, dtype=F32)
+    orc.accumulate32(want, grads[0], 32, first=True)
+    for g, n in ((grads[1], 64), (grads[2], 32), (grads[3], 16)):
+        orc.accumulate32(want, g, n, first=False)
+    _assert_bitexact(cat(acc_t), want, "accumulate_mt + accumulate_batch_mt")
+
+    # Step 1 + update, every rule
+    x0 = (rng.standard_normal(P) * 0.05).astype(F32)
+    v0 = (rng.standard_normal(P) * 0.3).astype(F32)
+    p0 = (x0 + rng.standard_normal(P).astype(F32) * F32(0.02)).astype(F32)
+    q0 = np.abs(rng.standard_normal(P) * 1e-4).astype(F32)
+    accs = [(rng.standard_normal(P) * 20.0 * max(c, 1) / 32).astype(F32) for c in counts]
+    asets = [absgd.TensorSet(lay, split(a) if c > 0 else split(np.full(P, np.nan, dtype=F32)))
+             for a, c in zip(accs, counts)]
+
+    def state(*arrays):
+        ts = [split(a) for a in arrays]
+        return ts, [absgd.TensorSet(lay, t) for t in ts]
+
+    (xt, vt), (xs, vs) = state(x0, v0)
+    ok = absgd.abs_sync_update_mt(lay, xs, vs, asets, counts, 0.1, 0.9, 5e-4)
+    xw, vw = x0.copy(), v0.copy()
+    assert ok == orc.sync_update32(xw, vw, accs, counts, 0.1, 0.9, 5e-4)
+    _assert_bitexact(cat(xt), xw, "sync_update_mt x")
+    _assert_bitexact(cat(vt), vw, "sync_update_mt v")
+
+    (xt, pt, vt), (xs, ps, vs) = state(x0, p0, v0)
+    ok = absgd.abs_sync_update_dc_mt(lay, xs, ps, vs, asets, counts, 0.1, 0.9, 5e-4, 0.5)
+    xw, pw, vw = x0.copy(), p0.copy(), v0.copy()
+    assert ok == orc.sync_update32_dc(xw, pw, vw, accs, counts, 0.1, 0.9, 5e-4, 0.5)
+    _assert_bitexact(cat(xt), xw, "sync_update_dc_mt x")
+    _assert_bitexact(cat(vt), vw, "sync_update_dc_mt v")
+    _assert_bitexact(cat(pt), pw, "sync_update_dc_mt x_prev")
+
+    (xt, vt), (xs, vs) = state(x0, v0)
+    ok = absgd.abs_sync_update_dcm_mt(lay, xs, vs, asets, counts, 0.1, 0.9, 5e-4, 0.5, 0.07)
+    xw, vw = x0.copy(), v0.copy()
+    assert ok == orc.sync_update32_dcm(xw, vw, accs, counts, 0.1, 0.9, 5e-4, 0.5, 0.07)
+    _assert_bitexact(cat(xt), xw, "sync_update_dcm_mt x")
+    _assert_bitexact(cat(vt), vw, "sync_update_dcm_mt v")
+
+    (xt, mt, qt), (xs, ms, qs) = state(x0, v0, q0)
+    ok = absgd.abs_sync_update_adam_mt(lay, xs, ms, qs, asets, counts, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 2)
+    xw, mw, qw = x0.copy(), v0.copy(), q0.copy()
+    assert ok == orc.sync_update32_adam(xw, mw, qw, accs, counts, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 2)
+    _assert_bitexact(cat(xt), xw, "sync_update_adam_mt x")
+    _assert_bitexact(cat(mt), mw, "sync_update_adam_mt m")
+    _assert_bitexact(cat(qt), qw, "sync_update_adam_mt v")
+
+
+@pytest.mark.parametrize("K", [1, 2, 5, 16, 17, 40])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_calls_worker_counts(absgd, K, dtype):
+    _ragged_case(absgd, [4096 * 3 + 5, 1, 700, 65_537, 12], [32 * (1 + k % 3) for k in range(K)], seed=1100 + K,
+                 dtype=dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_calls_layouts_and_edges(absgd, dtype):
+    _ragged_case(absgd, [5, 0, 9000, 3], [32, 32], seed=1201, dtype=dtype)                           # an empty tensor
+    _ragged_case(absgd, [1], [32], seed=1202, dtype=dtype)                                           # one element
+    _ragged_case(absgd, [300, 5000, 70], [0, 64, 0, 32], seed=1203, dtype=dtype)                     # idle workers
+    _ragged_case(absgd, [300, 5000, 70], [0, 0, 0], seed=1204, dtype=dtype)                          # nothing to apply
+    _ragged_case(absgd, [4096 + 11, 8192, 4095, 2], [32, 64, 32], seed=1205, dtype=dtype, misalign=True)
+    _ragged_case(absgd, [4096 + 11, 8192, 4095, 2], [32] * 18, seed=1206, dtype=dtype, misalign=True)   # run-time K
+    _ragged_case(absgd, list(wl.WORKLOADS["ragged_odd_f32"].tensor_sizes), [32, 96, 64], seed=1207, dtype=dtype)
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+def test_ragged_calls_multi_row_tiles(absgd, tuned):
+    _ragged_case(absgd, [1_048_576 + 13, 300_007, 5], [32, 64, 32, 32, 96], seed=1300, dtype="bf16")
+
+
+# ---------------------------------------------------------------------------
 # abs_sync_update_lars_mt: per-tensor norms + update.  Double oracle only (the norm
 # reductions have no fixed-order fp32 restatement); results must not depend on timing.
 # ---------------------------------------------------------------------------
