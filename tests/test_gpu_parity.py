@@ -748,6 +748,44 @@ def test_ragged_calls_layouts_and_edges(absgd, dtype):
     _ragged_case(absgd, list(wl.WORKLOADS["ragged_odd_f32"].tensor_sizes), [32, 96, 64], seed=1207, dtype=dtype)
 
 
+def test_ragged_calls_reject_mismatched_arguments(absgd):
+    """Argument errors are reported before anything is launched; the state is untouched."""
+    print("[case] ragged argument errors", flush=True)
+    sizes = [300, 5000, 70]
+    lay, other = absgd.Layout(sizes), absgd.Layout([300, 5000, 71])
+    mk = lambda n=None, dt=torch.float32: [torch.ones(s if n is None else n[i], device="cuda", dtype=dt)
+                                           for i, s in enumerate(sizes)]
+    xt, vt, at, gt = mk(), mk(), mk(), mk()
+    xs, vs, a, g = (absgd.TensorSet(lay, t) for t in (xt, vt, at, gt))
+    foreign = absgd.TensorSet(other, mk(n=[300, 5000, 71]))
+    half = absgd.TensorSet(lay, mk(dt=torch.bfloat16))
+    cnt = absgd.Count(0)
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_mt(lay, a, foreign, 32, cnt)              # gradient set of another layout
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_mt(lay, half, g, 32, cnt)                 # accumulators are fp32
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_mt(lay, a, g, 0, cnt)                     # a batch has samples
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_batch_mt(lay, a, [g, half], [32, 32], cnt)   # one element type per batch
+    assert cnt.value == 0
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_mt(lay, xs, xs, [a], [32], 0.1, 0.9, 0.0)       # params and momentum alias
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_mt(lay, xs, vs, [foreign], [32], 0.1, 0.9, 0.0)
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_mt(lay, xs, vs, [a], [-1], 0.1, 0.9, 0.0)
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_dc_mt(lay, xs, xs, vs, [a], [32], 0.1, 0.9, 0.0, 0.5)   # x_prev aliases x
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_adam_mt(lay, xs, vs, g, [a], [32], 1e-3, 0.9, 0.999, 1e-8, 0.0, 0)   # step >= 1
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_lars_mt(lay, xs, vs, vs, [a], [32], 0.1, 0.9, 0.0, 0.001)   # workspace aliases v
+    torch.cuda.synchronize()
+    for t in xt + vt + at + gt:
+        assert bool((t == 1).all())
+
+
 @pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
 def test_ragged_calls_multi_row_tiles(absgd, tuned):
     _ragged_case(absgd, [1_048_576 + 13, 300_007, 5], [32, 64, 32, 32, 96], seed=1300, dtype="bf16")
