@@ -238,3 +238,34 @@ def test_double_buffer_bookkeeping_without_a_gpu():
     assert L.abs_ctx_destroy(ctx) == absgd.ABS_OK
     assert L.abs_ctx_create(ctypes.byref(ctx), 0, 0, null, null, None, None) == absgd.ABS_EINVAL
     assert L.abs_ctx_create(ctypes.byref(ctx), 65, 0, null, null, None, None) == absgd.ABS_EINVAL
+
+
+def test_python_wrappers_marshal_every_flat_call_without_a_gpu():
+    """P = 0 launches nothing, and the wrappers accept raw integer addresses: every flat
+    wrapper is called once through its Python signature (argument order and count)."""
+    cnt = absgd.Count(0)
+    assert absgd.abs_accumulate(16, 32, 8, cnt, P=0, grad_dtype=absgd.ABS_F32, stream=0) is True
+    assert absgd.abs_accumulate_batch(16, [32, 48], [8, 8], cnt, P=0, grad_dtype=absgd.ABS_BF16, stream=0) is True
+    assert cnt.value == 24
+    acc, counts = [64, 128], [32, 0]
+    assert absgd.abs_sync_update(16, 32, acc, counts, 0.1, 0.9, 5e-4, P=0, stream=0) is True
+    assert absgd.abs_sync_update(16, 32, acc, [0, 0], 0.1, 0.9, 5e-4, P=0, stream=0) is False
+    assert absgd.abs_sync_update_dc(16, 48, 32, acc, counts, 0.1, 0.9, 5e-4, 0.5, P=0, stream=0) is True
+    assert absgd.abs_sync_update_dcm(16, 32, acc, counts, 0.1, 0.9, 5e-4, 0.5, 0.1, P=0, stream=0) is True
+    assert absgd.abs_sync_update_adam(16, 32, 48, acc, counts, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, P=0, stream=0) is True
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_sync_update_adam(16, 32, 48, acc, counts, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, P=0, stream=0)
+    assert absgd.abs_set_cache_policy(-1, -1) is True
+    assert absgd.abs_set_launch_tuning(0, 4) is True
+    ctx = absgd.Context([0, 0], [0, 0], 0, 0, P=0)         # stream handle 0: the null stream
+    assert ctx.abs_sync_update(0, 0, 0.1, 0.9, 0.0) is False
+    assert ctx.abs_accumulate(1, 0, 32, grad_dtype=absgd.ABS_F32) is True
+    assert ctx.abs_accumulate_batch(0, [0, 0], [16, 16], grad_dtype=absgd.ABS_F32) is True
+    assert ctx.counts(0) == [32, 32] and ctx.counts(1) == [0, 0]
+    assert absgd.abs_swap_buffers(ctx) is True
+    assert ctx.counts(1) == [32, 32]
+    assert ctx.abs_sync_update(0, 0, 0.1, 0.9, 0.0) is True
+    assert ctx.abs_sync_update_dc(0, 0, 0, 0.1, 0.9, 0.0, 0.5) is True
+    assert ctx.abs_sync_update_dcm(0, 0, 0.1, 0.9, 0.0, 0.5) is True
+    assert ctx.abs_sync_update_adam(0, 0, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1) is True
+    ctx.close()
