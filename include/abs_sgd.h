@@ -27,6 +27,17 @@
  *     Nothing is thrown across this boundary.
  *   - Arithmetic is fp32 in one fixed order (stated per call) so results are
  *     reproducible bit for bit; sample counts are integers.
+ *   - Threads: calls on different objects (layouts, tensor sets, contexts) and
+ *     the stateless calls may run concurrently from several host threads; one
+ *     object is used by one thread at a time (a layout uploads its tables on
+ *     first use, a context keeps host counts), and the two tuning calls
+ *     (abs_set_launch_tuning, abs_set_cache_policy) change process-wide settings
+ *     and must not run while another thread is inside the library.
+ *   - Devices: everything runs on the HIP device that is current at the call,
+ *     on the caller's streams.  A layout keeps its tables on the device that was
+ *     current at its first use in a ragged call; a ragged call with another
+ *     device current returns ABS_EINVAL.  Create a layout's tensor sets with
+ *     that same device current.
  */
 #ifndef ABS_SGD_H
 #define ABS_SGD_H
