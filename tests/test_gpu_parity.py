@@ -746,6 +746,8 @@ def test_ragged_calls_layouts_and_edges(absgd, dtype):
     _ragged_case(absgd, [4096 + 11, 8192, 4095, 2], [32, 64, 32], seed=1205, dtype=dtype, misalign=True)
     _ragged_case(absgd, [4096 + 11, 8192, 4095, 2], [32] * 18, seed=1206, dtype=dtype, misalign=True)   # run-time K
     _ragged_case(absgd, list(wl.WORKLOADS["ragged_odd_f32"].tensor_sizes), [32, 96, 64], seed=1207, dtype=dtype)
+    many = [int(v) for v in np.random.default_rng(1208).integers(0, 40, size=2000)]                     # 2,000 tiny tensors
+    _ragged_case(absgd, many, [32, 64], seed=1208, dtype=dtype)
 
 
 def test_ragged_calls_reject_mismatched_arguments(absgd):
