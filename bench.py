@@ -121,6 +121,15 @@ def kernel_event_pass(run, plans, t0, steps, torch):
     return [a.elapsed_time(b) for a, b in pairs], launches, [a.elapsed_time(b) for a, b in sync_pairs]
 
 
+def suggested_plan(absgd, w, timings, steps, best):
+    n = absgd.abs_suggest_accumulate_streams(w.P, w.K)
+    name = next((k for k in timings if k.startswith(f"{n} accumulate streams")), None) if n > 1 else "one stream"
+    if name is None:
+        return {"accumulate_streams": n, "name": None}
+    return {"accumulate_streams": n, "name": name, "ms_per_step": timings[name] / steps * 1e3,
+            "is_fastest": name == best, "slower_than_fastest_by": timings[name] / timings[best] - 1.0}
+
+
 def probe_ceilings(torch, nbytes=1 << 30, reps=20):
     """Copy / read / write / triad (a += s*b: the accumulate's two reads and one
     write) rates of plain streaming kernels on this machine (context for the roofline
@@ -373,6 +382,8 @@ def main():
         # time the host needed to enqueue a step (binding + launches + event joins): when it
         # approaches ms_per_step the workload is bound by launches, not by the kernels
         "host_issue_ms_per_step": HOST_ISSUE[best] / K_steps * 1e3,
+        # the plan abs_suggest_accumulate_streams(P, K) stands for, beside the one found fastest here
+        "suggested_plan": suggested_plan(absgd, w, timings, K_steps, best),
         "roofline": {
             "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -337,6 +337,16 @@ int abs_ctx_destroy(abs_ctx *ctx);
  * EINVAL afterwards, or for n < 1, n > ABS_MAX_K.  streams: HOST array. */
 int abs_ctx_set_accumulate_streams(abs_ctx *ctx, void *const *streams, int n);
 
+/* How many accumulate streams to give a context over K workers with P-element
+ * accumulators (Algorithm 1's Step 2 of different workers is independent work):
+ * 2 while 24 MiB <= 4*P <= 112 MiB and K >= 2, else 1.  Measured on MI355X with
+ * the sync-update on a stream of its own: two streams hide launch ramp-up and
+ * drain in that range (+3 to +12 % per step); below it the event joins cost
+ * more than they hide (-3 to -25 %), above it concurrent launches push each
+ * other out of the memory-side cache (-4 %); four streams never beat two.
+ * With 1, accumulate and sync-update are best put on one stream too. */
+int abs_suggest_accumulate_streams(int64_t P, int K);
+
 /* abs_accumulate into worker k's CURRENT accumulator, on that worker's
  * accumulate stream. */
 int abs_ctx_accumulate(abs_ctx *ctx, int k, const void *grad, abs_dtype grad_dtype,

@@ -46,6 +46,7 @@ SYMBOLS = {
     "abs_accumulate_mt": (_int, [_vp, _vp, _vp, _i64, _pi64, _vp]),
     "abs_accumulate_batch_mt": (_int, [_vp, _vp, _pvp, _int, _pi64, _pi64, _vp]),
     "abs_sync_update_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _vp]),
+    "abs_suggest_accumulate_streams": (_int, [_i64, _int]),
     "abs_sync_update_dcm": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _f, _vp]),
     "abs_sync_update_dcm_mt": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _vp]),
     "abs_ctx_sync_update_dcm": (_int, [_vp, _vp, _vp, _f, _f, _f, _f]),
@@ -165,6 +166,11 @@ def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=0):
     """See abs_set_launch_tuning in abs_sgd.h."""
     return _check("abs_set_launch_tuning",
                   lib().abs_set_launch_tuning(int(blocks_per_cu), int(max_rows_per_tile)))
+
+
+def abs_suggest_accumulate_streams(P, K):
+    """1 or 2: accumulate streams that pay for K workers with P-element accumulators."""
+    return int(lib().abs_suggest_accumulate_streams(int(P), int(K)))
 
 
 def abs_set_cache_policy(accumulate_mode=-1, update_mode=-1):
@@ -488,7 +494,7 @@ def abs_swap_buffers(ctx):
     return ctx.abs_swap_buffers()
 
 
-__all__ = ["abs_swap_buffers", "abs_set_cache_policy", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
+__all__ = ["abs_swap_buffers", "abs_set_cache_policy", "abs_suggest_accumulate_streams", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
            "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",

@@ -952,6 +952,12 @@ int abs_ctx_set_accumulate_streams(abs_ctx *C, void *const *streams, int n)
     return ctx_set_streams(C, s.data(), n);
 }
 
+int abs_suggest_accumulate_streams(int64_t P, int K)
+{
+    const int64_t bytes = 4 * P;
+    return (K >= 2 && bytes >= (int64_t(24) << 20) && bytes <= (int64_t(112) << 20)) ? 2 : 1;
+}
+
 int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
 {
     if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;

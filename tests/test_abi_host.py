@@ -269,3 +269,14 @@ def test_python_wrappers_marshal_every_flat_call_without_a_gpu():
     assert ctx.abs_sync_update_dcm(0, 0, 0.1, 0.9, 0.0, 0.5) is True
     assert ctx.abs_sync_update_adam(0, 0, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1) is True
     ctx.close()
+
+
+def test_suggested_accumulate_streams_for_the_stated_configurations():
+    import abs_workloads as wl
+    want = {"cfg1_small": 1, "cfg2_resnet18": 2, "cfg3_resnet50_bf16": 2, "cfg4_vgg16": 1,
+            "cfg5_gpt2_ragged_bf16": 1, "paper_static": 2}
+    for name, n in want.items():
+        w = wl.WORKLOADS[name]
+        assert absgd.abs_suggest_accumulate_streams(w.P, w.K) == n, name
+    assert absgd.abs_suggest_accumulate_streams(11_689_512, 1) == 1        # one worker: nothing to spread
+    assert absgd.abs_suggest_accumulate_streams(0, 4) == 1
