@@ -190,7 +190,7 @@ def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
     M = [[0] * K for _ in range(2)]
     cur, prev = 0, 1
     R = len(pool)
-    done_bytes, done_steps = 0, 0
+    done_bytes, done_steps, own_bytes = 0, 0, 0
     t_start = time.perf_counter()
     t = -1
     while True:
@@ -205,10 +205,14 @@ def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
         cur, prev = prev, cur
         a, s = bytes_per_param(w, sched[t])
         done_bytes += (a + s) * P
+        # what the oracle itself moves: double accumulators (zero pass, then read + write per
+        # reference batch), all K of them read by the update, x and v in double
+        gb = 4 if w.grad_dtype == "f32" else 2
+        own_bytes += (8 * K + sum(int(m) for m in sched[t]) * (gb + 16) + 8 * K + 32) * P
         done_steps += 1
         if time.perf_counter() - t_start > budget_s:
             break
-    return done_bytes, done_steps, time.perf_counter() - t_start
+    return done_bytes, done_steps, time.perf_counter() - t_start, own_bytes
 
 
 def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
@@ -221,14 +225,16 @@ def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
 
     threads = orc.max_threads()
     P = x0.size
-    nbytes, steps, dt = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s)
+    nbytes, steps, dt, own = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s)
     orc.set_threads(1)
-    b1, s1, dt1 = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s / 4)
+    b1, s1, dt1, _ = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s / 4)
     orc.set_threads(threads)
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{steps} whole steps of {w.name} at full P={P} (same inputs and m_k), "
                       f"{dt:.1f} s wall, OpenMP over the parameter index",
             "ms_per_step": dt / steps * 1e3, "params_per_s": P * steps / dt,
+            # `value` uses the method's algorithmic bytes (as for the GPU); this is the oracle's own traffic
+            "own_bytes_GBs": own / dt / 1e9,
             "single_thread": {"value": b1 / dt1 / 1e9, "unit": "GB/s", "ms_per_step": dt1 / s1 * 1e3,
                               "sample": f"{s1} whole steps, {dt1:.1f} s wall"}}
 
