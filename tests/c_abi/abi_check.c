@@ -9,7 +9,9 @@
  * Covered: abs_accumulate (fp32 and bf16 gradients, overwrite-on-first),
  * abs_accumulate_batch, abs_sync_update, and Algorithm 1's loop through the
  * double-buffer context (abs_ctx_create / abs_ctx_accumulate /
- * abs_ctx_sync_update / abs_swap_buffers) on two streams.
+ * abs_ctx_sync_update / abs_swap_buffers) on two streams, and the ragged forms
+ * (abs_layout, abs_tensorset, abs_accumulate[_batch]_mt, abs_sync_update_mt)
+ * over separately allocated tensors, one of them empty.
  *
  * Exit status 0 and a last line "abi_check: OK" on success.
  */
@@ -291,6 +293,81 @@ static int check_loop(int64_t P)
     return ok;
 }
 
+/* ---- case 3: the ragged forms: one hipMalloc per tensor, pointer tables, one launch per call ---- */
+static int check_ragged(void)
+{
+    enum { T = 4, K = 2 };
+    static const int64_t sizes[T] = {5, 9001, 0, 4096 * 2 + 3};
+    int64_t off[T + 1] = {0}, P;
+    int ok = 1;
+    for (int t = 0; t < T; ++t) off[t + 1] = off[t] + sizes[t];
+    P = off[T];
+    printf("[case] ragged forms, %d tensors, %lld elements, K = %d\n", T, (long long)P, K);
+    fflush(stdout);
+    float *x = malloc((size_t)P * 4), *v = malloc((size_t)P * 4), *g32 = malloc((size_t)P * 4);
+    uint16_t *gbf = malloc((size_t)P * 2);
+    fill_f32(x, P, 0.1f); fill_f32(v, P, 0.01f); fill_f32(g32, P, 0.02f); fill_bf16(gbf, P, 0.02f);
+
+    abs_layout *L = NULL;
+    CHECK_ABS(abs_layout_create(&L, T, sizes), ABS_OK);
+    if (abs_layout_total(L) != P || abs_layout_num_tensors(L) != T) { fprintf(stderr, "layout totals\n"); ok = 0; }
+    void *dx[T], *dv[T], *dg32[T], *dgbf[T], *da[K][T];
+    for (int t = 0; t < T; ++t) {
+        const size_t n = (size_t)sizes[t];
+        if (n == 0) { dx[t] = dv[t] = dg32[t] = dgbf[t] = da[0][t] = da[1][t] = NULL; continue; }   /* an empty tensor has no storage */
+        dx[t] = to_device(x + off[t], n * 4); dv[t] = to_device(v + off[t], n * 4);
+        dg32[t] = to_device(g32 + off[t], n * 4); dgbf[t] = to_device(gbf + off[t], n * 2);
+        for (int k = 0; k < K; ++k) da[k][t] = device_garbage(n * 4);
+    }
+    abs_tensorset *sx, *sv, *sg32, *sgbf, *sa[K];
+    CHECK_ABS(abs_tensorset_create(&sx, L, dx, ABS_F32), ABS_OK);
+    CHECK_ABS(abs_tensorset_create(&sv, L, dv, ABS_F32), ABS_OK);
+    CHECK_ABS(abs_tensorset_create(&sg32, L, dg32, ABS_F32), ABS_OK);
+    CHECK_ABS(abs_tensorset_create(&sgbf, L, dgbf, ABS_BF16), ABS_OK);
+    for (int k = 0; k < K; ++k) CHECK_ABS(abs_tensorset_create(&sa[k], L, da[k], ABS_F32), ABS_OK);
+
+    int64_t counts[K] = {0, 0};
+    CHECK_ABS(abs_accumulate_mt(L, sa[0], sgbf, 32, &counts[0], NULL), ABS_OK);
+    CHECK_ABS(abs_accumulate_mt(L, sa[0], sg32, 64, &counts[0], NULL), ABS_OK);
+    const abs_tensorset *two[2] = {sg32, sg32};
+    const int64_t ns[2] = {16, 48};
+    CHECK_ABS(abs_accumulate_batch_mt(L, sa[1], two, 2, ns, &counts[1], NULL), ABS_OK);
+    const abs_tensorset *accs[K] = {sa[0], sa[1]};
+    CHECK_ABS(abs_sync_update_mt(L, sx, sv, accs, counts, K, 0.1f, 0.9f, 5e-4f, NULL), ABS_OK);
+    CHECK_HIP(hipDeviceSynchronize());
+
+    float *G0 = malloc((size_t)P * 4), *G1 = malloc((size_t)P * 4), *x32 = malloc((size_t)P * 4), *v32 = malloc((size_t)P * 4);
+    oracle32_accumulate_bf16(G0, gbf, P, 32, 1);
+    oracle32_accumulate_f32(G0, g32, P, 64, 0);
+    oracle32_accumulate_f32(G1, g32, P, 16, 1);
+    oracle32_accumulate_f32(G1, g32, P, 48, 0);
+    memcpy(x32, x, (size_t)P * 4); memcpy(v32, v, (size_t)P * 4);
+    const float *G32[K] = {G0, G1};
+    if (counts[0] != 96 || counts[1] != 64) { fprintf(stderr, "ragged counts\n"); ok = 0; }
+    if (oracle32_sync_update(x32, v32, G32, counts, K, P, 0.1f, 0.9f, 5e-4f) != 0) ok = 0;
+    float *out = malloc((size_t)P * 4);
+    for (int t = 0; t < T; ++t)
+        if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], dx[t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
+    ok &= same_bits(out, x32, P, "ragged x");
+    for (int t = 0; t < T; ++t)
+        if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], dv[t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
+    ok &= same_bits(out, v32, P, "ragged v");
+    for (int t = 0; t < T; ++t)
+        if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], da[1][t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
+    ok &= same_bits(out, G1, P, "ragged accumulator (batched)");
+
+    abs_tensorset_destroy(sx); abs_tensorset_destroy(sv); abs_tensorset_destroy(sg32); abs_tensorset_destroy(sgbf);
+    for (int k = 0; k < K; ++k) abs_tensorset_destroy(sa[k]);
+    abs_layout_destroy(L);
+    for (int t = 0; t < T; ++t) {
+        if (!sizes[t]) continue;
+        CHECK_HIP(hipFree(dx[t])); CHECK_HIP(hipFree(dv[t])); CHECK_HIP(hipFree(dg32[t])); CHECK_HIP(hipFree(dgbf[t]));
+        for (int k = 0; k < K; ++k) CHECK_HIP(hipFree(da[k][t]));
+    }
+    free(x); free(v); free(g32); free(gbf); free(G0); free(G1); free(x32); free(v32); free(out);
+    return ok;
+}
+
 int main(void)
 {
     int n_dev = 0;
@@ -303,6 +380,7 @@ int main(void)
     ok &= check_calls(3 * 4096 + 1029);        /* several tiles and a ragged tail */
     ok &= check_calls(5);                      /* shorter than one vector */
     ok &= check_loop(200003);
+    ok &= check_ragged();
     if (!ok) {
         fprintf(stderr, "abi_check: FAILED\n");
         return 1;
