@@ -334,8 +334,8 @@ __device__ __forceinline__ void update_vec(f32x4 s, f32x4 &x, f32x4 &s1, f32x4 &
 template <int K> struct AccPtrs { const float *p[K]; };
 
 // Workers whose accumulators are loaded together.  A group always spans
-// ABS_SYNC_ROWS rows, so every wavefront reads ABS_SYNC_ROWS KiB of consecutive
-// memory per stream; with many workers the K-way read is cut into batches of KC
+// ABS_SYNC_ROWS rows, so a workgroup reads ABS_SYNC_ROWS x 4 KiB of consecutive
+// memory per stream at a time (each wavefront 1 KiB of every row); with many workers the K-way read is cut into batches of KC
 // so that about ABS_SYNC_INFLIGHT loads are outstanding per lane.  Measured at
 // P = 1.2e8, K = 16: 4 rows x 4 workers at a time reach 5.8 TB/s, 1 row x 16
 // workers 5.1 TB/s.  The sum still runs over the workers in ascending order.
