@@ -58,6 +58,18 @@ constexpr int BLOCK = ABS_BLOCK;
 constexpr int VEC = 4;                 // elements per lane per access
 constexpr int ROW = BLOCK * VEC;       // elements per workgroup row; tiles are whole rows
 
+// Vector index of (row u, lane tid) in a group of U rows starting at g0.  Two
+// layouts, both covering [g0, g0 + U*BLOCK) exactly once:
+//   row-major      : a row is BLOCK consecutive vectors, one per lane;
+//   wave-contiguous: each wavefront owns U*64 consecutive vectors (U KiB per
+//                    stream), row u being its u-th 64-vector piece.
+#ifndef ABS_WAVE_CONTIG
+#define ABS_WAVE_CONTIG 1      // 0 disables the wave-contiguous layout everywhere
+#endif
+#define GIDX(g0, u, tid, U, wc)                                                              \
+    (((wc) && ABS_WAVE_CONTIG) ? ((g0) + ((((tid) >> 6) * (U)) + (u)) * 64 + ((tid) & 63))   \
+                               : ((g0) + (u) * BLOCK + (tid)))
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -173,10 +185,11 @@ __device__ __forceinline__ void accumulate_group(f32x4 *__restrict__ av, const G
     typedef typename GradT<BF16>::vec gvec;
     constexpr int U = acc_rows<J>();
     constexpr int JC = acc_batch<J>();
+    constexpr bool wc = false;     // wave-contiguous: within noise for fp32, -3 to -7 % for bf16 at P = 1.2e7
     f32x4 g[U][JC] = {}, r[U] = {};
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int i = g0 + u * BLOCK + tid;
+        const int i = GIDX(g0, u, tid, U, wc);
         if (WHOLE || i < nvec) {
 #pragma unroll
             for (int j = 0; j < JC; ++j) g[u][j] = load_grad_vec<BF16>(reinterpret_cast<const gvec *>(G.g[j]) + i);
@@ -185,7 +198,7 @@ __device__ __forceinline__ void accumulate_group(f32x4 *__restrict__ av, const G
     if (!first) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
+            const int i = GIDX(g0, u, tid, U, wc);
             if (WHOLE || i < nvec) r[u] = ld<NTA>(av + i);
         }
     }
@@ -200,7 +213,7 @@ __device__ __forceinline__ void accumulate_group(f32x4 *__restrict__ av, const G
     for (int j0 = JC; j0 < J; j0 += JC) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
+            const int i = GIDX(g0, u, tid, U, wc);
             if (WHOLE || i < nvec) {
 #pragma unroll
                 for (int j = 0; j < JC; ++j)
@@ -215,7 +228,7 @@ __device__ __forceinline__ void accumulate_group(f32x4 *__restrict__ av, const G
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int i = g0 + u * BLOCK + tid;
+        const int i = GIDX(g0, u, tid, U, wc);
         if (WHOLE || i < nvec) st<NTA>(av + i, r[u]);
     }
 }
@@ -356,10 +369,13 @@ __device__ __forceinline__ void sync_group(f32x4 *__restrict__ xv, f32x4 *__rest
     constexpr bool S2 = uses_s2<RULE>();
     constexpr int U = ABS_SYNC_ROWS;
     constexpr int KC = sync_batch<K, RULE>();
+    // wave-contiguous pays when the K workers are read in exactly two batches (K = 5..8:
+    // +3 % at P >= 6e7); one batch is indifferent, more lose a quarter of the rate (K = 16)
+    constexpr bool WC = K > KC && K <= 2 * KC;
     f32x4 a[U][KC] = {}, sum[U] = {}, xr[U] = {}, vr[U] = {}, pr[U] = {};
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int i = g0 + u * BLOCK + tid;
+        const int i = GIDX(g0, u, tid, U, WC);
         if (WHOLE || i < nvec) {
 #pragma unroll
             for (int k = 0; k < KC; ++k)
@@ -380,7 +396,7 @@ __device__ __forceinline__ void sync_group(f32x4 *__restrict__ xv, f32x4 *__rest
     for (int k0 = KC; k0 < K; k0 += KC) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = g0 + u * BLOCK + tid;
+            const int i = GIDX(g0, u, tid, U, WC);
             if (WHOLE || i < nvec) {
 #pragma unroll
                 for (int k = 0; k < KC; ++k)
@@ -395,7 +411,7 @@ __device__ __forceinline__ void sync_group(f32x4 *__restrict__ xv, f32x4 *__rest
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int i = g0 + u * BLOCK + tid;
+        const int i = GIDX(g0, u, tid, U, WC);
         if (WHOLE || i < nvec) {
             update_vec<RULE>(sum[u], xr[u], vr[u], pr[u], h);
             st<NTX>(vv + i, vr[u]);
@@ -716,7 +732,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
             f32x4 sum[U] = {}, xr[U] = {};
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
+                const int i = GIDX(g0, u, tid, U, false);
                 if (i < nvec) xr[u] = xv[i];
             }
             for (int k0 = 0; k0 < K; k0 += KC) {
@@ -727,7 +743,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
                         const f32x4 *ap = reinterpret_cast<const f32x4 *>(tabs.t[k0 + kk][c.tensor] + base);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
-                            const int i = g0 + u * BLOCK + tid;
+                            const int i = GIDX(g0, u, tid, U, false);
                             if (i < nvec) a[u][kk] = ld<ABS_NT_SYNC_ACC != 0>(ap + i);
                         }
                     }
@@ -742,7 +758,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
+                const int i = GIDX(g0, u, tid, U, false);
                 if (i < nvec) {
                     f32x4 g;
                     g.x = sum[u].x / M; g.y = sum[u].y / M; g.z = sum[u].z / M; g.w = sum[u].w / M;
@@ -832,12 +848,12 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_update_ragged(const Chunk *__r
             f32x4 g[U] = {}, xr[U] = {}, vr[U] = {};
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
+                const int i = GIDX(g0, u, tid, U, false);
                 if (i < nvec) { g[u] = ld<true>(gv + i); xr[u] = xv[i]; vr[u] = vv[i]; }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = g0 + u * BLOCK + tid;
+                const int i = GIDX(g0, u, tid, U, false);
                 if (i < nvec) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
