@@ -121,7 +121,7 @@ def kernel_event_pass(run, plans, t0, steps, torch):
     return [a.elapsed_time(b) for a, b in pairs], launches, [a.elapsed_time(b) for a, b in sync_pairs]
 
 
-def probe_ceilings(torch, nbytes=1 << 30, reps=20):
+def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
     """Copy / read / write / triad (a += s*b: the accumulate's two reads and one
     write) rates of plain streaming kernels on this machine (context for the roofline
     fraction; not part of the method)."""
@@ -153,6 +153,22 @@ def probe_ceilings(torch, nbytes=1 << 30, reps=20):
         e1.record()
         torch.cuda.synchronize()
         out[name + "_GBs"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    if K in (4, 8, 16):
+        # a plain kernel with the sync-update's traffic: K + 2 vectors read, two of them written
+        del a, b
+        R, nb = K + 2, 1 << 28
+        L.probe_mix.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp]
+        bufs = [torch.zeros(nb // 4, device="cuda") for _ in range(2 * R)]      # two sets, used in turn
+        sets = [(vp * R)(*[t.data_ptr() for t in bufs[i * R:(i + 1) * R]]) for i in range(2)]
+        for i in range(4):
+            assert L.probe_mix(sets[i % 2], R, nb, st) == 0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            L.probe_mix(sets[i % 2], R, nb, st)
+        e1.record()
+        torch.cuda.synchronize()
+        out[f"mix_{K}_workers_GBs"] = (R + 2) * nb * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
     return out
 
 
@@ -402,12 +418,15 @@ def main():
                         "steps; a bracket around one launch also holds ~5 us of dispatch latency, so this is "
                         "a lower bound on the kernel's rate (the kernel trace under profiles/ has its own duration)",
         },
-        "box_ceilings": probe_ceilings(torch),
+        "box_ceilings": probe_ceilings(torch, w.K),
     }
     if out["box_ceilings"]:
         out["pct_of_box_copy_rate"] = 100.0 * gbs / out["box_ceilings"]["copy_GBs"]
         # the dominant kernel against a plain kernel of its own read:write mix at 1 GiB per vector
         out["roofline"]["frac_of_box_triad"] = achieved / out["box_ceilings"]["triad_GBs"]
+        mix = out["box_ceilings"].get(f"mix_{w.K}_workers_GBs")
+        if mix:
+            out["sync_update_kernel"]["frac_of_box_mix"] = sync_gbs / mix
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:])
     print(json.dumps(out))

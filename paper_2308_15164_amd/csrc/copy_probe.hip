@@ -75,7 +75,40 @@ __global__ __launch_bounds__(BLOCK) void probe_triad_kernel(f32x4 *__restrict__ 
     }
 }
 
+// R vectors read, the first two also written in place (p0 = sum, p1 = sum / 2): the
+// traffic mix of a fused combine + update over R - 2 workers, one vector per lane
+// and stream, VPT rows at a time, nothing else.
+template <int R> struct MixPtrs { f32x4 *p[R]; };
+
+template <int R>
+__global__ __launch_bounds__(BLOCK) void probe_mix_kernel(MixPtrs<R> P, int64_t nvec)
+{
+    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t i = base + u * BLOCK;
+        if (i < nvec) {
+            f32x4 s = __builtin_nontemporal_load(P.p[0] + i);
+#pragma unroll
+            for (int r = 1; r < R; ++r) s += __builtin_nontemporal_load(P.p[r] + i);
+            __builtin_nontemporal_store(s, P.p[0] + i);
+            __builtin_nontemporal_store(s * 0.5f, P.p[1] + i);
+        }
+    }
+}
+
+template <int R>
+int launch_mix(void *const *ptrs, int64_t nvec, hipStream_t stream);
+
 inline unsigned grid_for(int64_t nvec) { return (unsigned)((nvec + BLOCK * VPT - 1) / (BLOCK * VPT)); }
+template <int R>
+int launch_mix(void *const *ptrs, int64_t nvec, hipStream_t stream)
+{
+    MixPtrs<R> P;
+    for (int r = 0; r < R; ++r) P.p[r] = (f32x4 *)ptrs[r];
+    hipLaunchKernelGGL(probe_mix_kernel<R>, dim3(grid_for(nvec)), dim3(BLOCK), 0, stream, P, nvec);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
 }  // namespace
 
 extern "C" {
@@ -116,6 +149,22 @@ int probe_triad(void *a, const void *b, int64_t nbytes, float s, void *stream)
     hipLaunchKernelGGL(probe_triad_kernel, dim3(grid_for(nvec)), dim3(BLOCK), 0, (hipStream_t)stream,
                        (f32x4 *)a, (const f32x4 *)b, nvec, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// ptrs: HOST array of R DEVICE pointers (R = 6, 10 or 18: the shapes of K = 4, 8, 16
+// workers), 16-byte aligned, nbytes each; the first two are read and written.
+int probe_mix(void *const *ptrs, int R, int64_t nbytes, void *stream)
+{
+    if (!ptrs || nbytes <= 0 || (nbytes & 15)) return -1;
+    for (int r = 0; r < R && r < 18; ++r)
+        if (!ptrs[r] || ((uintptr_t)ptrs[r] & 15)) return -1;
+    const int64_t nvec = nbytes / 16;
+    switch (R) {
+    case 6: return launch_mix<6>(ptrs, nvec, (hipStream_t)stream);
+    case 10: return launch_mix<10>(ptrs, nvec, (hipStream_t)stream);
+    case 18: return launch_mix<18>(ptrs, nvec, (hipStream_t)stream);
+    default: return -1;
+    }
 }
 
 }  // extern "C"
