@@ -1,7 +1,7 @@
 // Plain streaming kernels of known size, separate from the method's library.
 // They serve two purposes in the benchmark: (1) calibrating the profiler's
 // HBM byte counters against a transfer whose size is known, and (2) measuring
-// the copy / read / write / triad ceilings of the box the benchmark runs on, to put the
+// the copy / read / write / triad / K-way-mix ceilings of the box the benchmark runs on, to put the
 // method's kernels in context.  Nothing in the method calls them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
