@@ -346,7 +346,11 @@ def run(x0, N, T, M_r, gamma, mu, wd, batches, precision="f64", record=None, lam
     for t in range(T):
         # Step 2: accumulate generation t (at x_t)
         for i in range(N):
-            G[cur][i][:] = 0
+            # initialisation G_t^i = 0, M_t^i = 0.  The double family zeroes the
+            # accumulator; the fp32 family's first reference batch overwrites it
+            # instead (`first`), so whatever the buffer still holds is never read.
+            if precision == "f64":
+                zero(G[cur][i])
             M[cur][i] = 0
             for g in batches(t, i):
                 if precision == "f64":

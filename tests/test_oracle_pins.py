@@ -299,6 +299,53 @@ def test_brute_force_per_sample_rational(seed):
 
 
 # ---------------------------------------------------------------------------
+# 7b. Step 2's initialisation G_t^i = 0 (Algorithm 1, Step 2, "Initialization")
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [0, 1, 2, 7, 1000, 100_003])
+def test_zero_clears_every_element_and_nothing_else(n):
+    """Whatever the accumulator holds (NaN, infinities, old sums), every one of its
+    n elements is +0.0 afterwards, the last one included; the memory on either
+    side of it is untouched; n = 0 touches nothing."""
+    guard = 3
+    buf = np.empty(n + 2 * guard)
+    buf[:] = np.nan
+    buf[guard + n // 2:] = -np.inf
+    buf[:guard] = [11.0, 12.0, 13.0]
+    buf[guard + n:] = [21.0, 22.0, 23.0]
+    G = buf[guard:guard + n]
+    orc.zero(G)
+    assert G.size == n
+    assert np.array_equal(G.view(np.uint64), np.zeros(n, dtype=np.uint64))      # +0.0 bit patterns
+    assert buf[:guard].tolist() == [11.0, 12.0, 13.0]
+    assert buf[guard + n:].tolist() == [21.0, 22.0, 23.0]
+
+
+def test_zero_makes_the_generation_forget_the_one_before_last():
+    """Algorithm 1 re-initialises G_t^i at the start of every Step 2, so what a worker
+    summed two iterations ago (the same buffer, with two generations alive) must not
+    reach Step 1 when that worker sits an iteration out.  Checked against the
+    definition written out with fresh arrays, not against the oracle's own loop."""
+    P, N, T, M_r = 6, 2, 5, 8
+    rng = np.random.default_rng(77)
+    g = (rng.integers(-64, 65, size=(T, N, P)) / 32.0).astype(F32)      # exact in fp32
+    m = np.array([[1, 1], [1, 1], [1, 0], [0, 1], [1, 1]])               # worker 1 idle at t=2, worker 0 at t=3
+    x0 = (rng.integers(-32, 33, size=P) / 16.0).astype(F32)
+
+    def batches(t, i):
+        return [g[t, i]] * int(m[t, i])
+
+    x_o, _, hist = orc.run(x0, N, T, M_r, 0.25, 0.0, 0.0, batches)
+    x = x0.astype(np.float64)
+    for t in range(1, T):                                                # plain delayed SGD on the weighted mean
+        tot = int(m[t - 1].sum()) * M_r
+        s = sum(float(M_r) * g[t - 1, i].astype(np.float64) for i in range(N) if m[t - 1, i])
+        x = x - 0.25 * (s / tot)
+    np.testing.assert_allclose(x_o, x, rtol=0, atol=1e-15)
+    assert hist == [[int(a) * M_r for a in row] for row in m]
+
+
+# ---------------------------------------------------------------------------
 # 8. bf16 gradients widen exactly
 # ---------------------------------------------------------------------------
 
