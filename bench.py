@@ -126,7 +126,7 @@ def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
     write) rates of plain streaming kernels on this machine (context for the roofline
     fraction; not part of the method)."""
     import ctypes
-    path = os.path.join(ROOT, "paper_2308_15164_amd", "libabs_probe.so")
+    path = os.path.join(ROOT, "bench_probe", "libabs_probe.so")
     if not os.path.exists(path):
         return None
     L = ctypes.CDLL(path)
@@ -175,7 +175,7 @@ def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
 def calibrate_copy(torch, nbytes=1 << 30, reps=10):
     """Only a plain copy of known size, for scaling the profiler's byte counters."""
     import ctypes
-    L = ctypes.CDLL(os.path.join(ROOT, "paper_2308_15164_amd", "libabs_probe.so"))
+    L = ctypes.CDLL(os.path.join(ROOT, "bench_probe", "libabs_probe.so"))
     L.probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     a = torch.ones(nbytes // 4, device="cuda")
     b = torch.ones(nbytes // 4, device="cuda")

@@ -21,6 +21,11 @@
  *   - fp32 buffers must be 4-byte aligned, bf16 buffers 2-byte aligned; 16-byte
  *     aligned bases take the 128-bit path, others a slower element-wise path
  *     with identical results.
+ *   - No overlap: a buffer a call writes (an accumulator, params, momentum and
+ *     the other state vectors) must not share a byte with any other buffer of
+ *     the same call.  The flat calls check the ranges and return ABS_EINVAL; the
+ *     ragged calls check only that the tensor sets are distinct objects, the
+ *     tensors behind them are the caller's to keep apart.
  *   - Return value: ABS_OK (0); ABS_EMPTY (1): nothing to apply, no memory
  *     touched, not an error; ABS_EINVAL (-1): bad argument, nothing enqueued;
  *     ABS_EHIP (-2): a HIP runtime call failed, abs_last_hip_error() has its code.
@@ -29,15 +34,20 @@
  *     reproducible bit for bit; sample counts are integers.
  *   - Threads: calls on different objects (layouts, tensor sets, contexts) and
  *     the stateless calls may run concurrently from several host threads; one
- *     object is used by one thread at a time (a layout uploads its tables on
- *     first use, a context keeps host counts), and the two tuning calls
- *     (abs_set_launch_tuning, abs_set_cache_policy) change process-wide settings
- *     and must not run while another thread is inside the library.
+ *     object is used by one thread at a time (a context keeps host counts; a
+ *     layout is uploaded by the first tensor set made over it).  The two
+ *     process-wide tuning calls (abs_set_launch_tuning, abs_set_cache_policy)
+ *     may run at any time: a call in flight works with the settings it read at
+ *     its start.  A context can carry settings of its own.
  *   - Devices: everything runs on the HIP device that is current at the call,
  *     on the caller's streams.  A layout keeps its tables on the device that was
- *     current at its first use in a ragged call; a ragged call with another
- *     device current returns ABS_EINVAL.  Create a layout's tensor sets with
- *     that same device current.
+ *     current when it was uploaded (abs_layout_upload, or the first
+ *     abs_tensorset_create over it); a ragged call with another device current
+ *     returns ABS_EINVAL.
+ *   - Allocation: only abs_layout_upload / abs_tensorset_create (device tables,
+ *     blocking copies) and the abs_*_create calls (host objects, HIP events)
+ *     allocate.  No accumulate, sync-update or swap call allocates, frees or
+ *     waits for the device.
  */
 #ifndef ABS_SGD_H
 #define ABS_SGD_H
@@ -70,7 +80,8 @@ int64_t abs_row_elems(void);
  * blocks_per_cu: resident workgroups per CU to plan for (0 = default: what the
  * kernel's register use allows).  max_rows_per_tile: cap on the tile (default 4;
  * 0 = none: one round, each workgroup walks one long run).  Affects later launches and
- * later abs_layout_create calls; results never change.  Process-wide. */
+ * later abs_layout_create calls (a layout keeps the tile it was created with);
+ * results never change.  Process-wide default; see abs_ctx_set_launch_tuning. */
 int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile);
 
 /* Cache policy of the kernels.  Accumulators, x and v are re-read soon after a
@@ -78,8 +89,8 @@ int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile);
  * and a streaming one (non-temporal accesses to those buffers); results are
  * identical.  Mode -1 (default) picks per launch from the buffer sizes: cached
  * while the working set fits the GPU's memory-side cache, streaming beyond.
- * 0 forces cached, 1 forces streaming.  Process-wide; not thread-safe against
- * concurrent launches.  EINVAL for other values. */
+ * 0 forces cached, 1 forces streaming.  Process-wide default; see
+ * abs_ctx_set_cache_policy.  EINVAL for other values. */
 int abs_set_cache_policy(int accumulate_mode, int update_mode);
 
 /* ------------------------------------------------------------------------
@@ -114,10 +125,42 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
  *   grads      HOST array of J DEVICE pointers, each P elements of grad_dtype
  *   n_samples  HOST array of J sample counts (each > 0);  *count += their sum
  *   Errors as abs_accumulate; J < 1 is EINVAL.  If a HIP error stops a call that
- *   needed several launches, earlier launches have already been enqueued and
- *   *count is left unchanged: treat the accumulator as undefined. */
+ *   needed several launches, *count has advanced by the samples of the launches
+ *   already enqueued, so count and accumulator still agree. */
 int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dtype, int J,
                          int64_t P, const int64_t *n_samples, int64_t *count, void *stream);
+
+/* (1'') Job list: Step 2 of SEVERAL workers in one launch -- in Algorithm 1 all N
+ *     workers run Step 2 at the same time, each into its own G_t^i.  Job w is one
+ *     worker's share: its accumulator, its count and the J_w gradients it has
+ *     ready (J_w >= 0; the adaptive batch size makes J_w differ from worker to
+ *     worker).  For every job the result equals abs_accumulate_batch on that
+ *     job alone, bit for bit.
+ *
+ *     fold (1..ABS_MAX_BATCH) is the most gradients of one job a launch folds in:
+ *     launch r = 0, 1, ... carries, for every job that still has some, its
+ *     gradients r*fold .. r*fold + fold - 1, so the call enqueues
+ *     ceil(max_w J_w / fold) launches (times ceil(njobs / 16): a launch carries at
+ *     most 16 jobs).  fold = 1 keeps the traffic of one abs_accumulate per
+ *     gradient (g_b + 8 bytes per parameter and gradient, g_b + 4 for a first one)
+ *     with max_w J_w launches instead of sum_w J_w; fold = 8 is the batched traffic
+ *     (J*g_b + 8 per job) in one launch.  A launch streams its jobs through the
+ *     GPU back to back, with no ramp-up or drain between workers.
+ *
+ *   jobs   HOST array of njobs (1..ABS_MAX_K) entries; the accumulators must be
+ *          distinct buffers and the counts distinct integers
+ *   Errors as abs_accumulate_batch, checked for all jobs before anything is
+ *   enqueued; if a HIP error stops the call, every count has advanced by what
+ *   was enqueued for its job. */
+typedef struct abs_job {
+    float *acc;               /* DEVICE, P floats */
+    const void *const *grads; /* HOST array of J DEVICE pointers, P elements of grad_dtype each */
+    const int64_t *n_samples; /* HOST array of J sample counts (each > 0) */
+    int J;                    /* gradients ready for this worker; 0 = it sits this call out */
+    int64_t *count;           /* HOST, read and advanced as by abs_accumulate */
+} abs_job;
+int abs_accumulate_jobs(const abs_job *jobs, int njobs, abs_dtype grad_dtype, int64_t P, int fold,
+                        void *stream);
 
 /* ------------------------------------------------------------------------
  * (2)+(3) Weighted combination of the K delayed accumulators and the delayed
@@ -147,8 +190,8 @@ int abs_sync_update(float *params, float *momentum, const float *const *acc,
                     void *stream);
 
 /* ------------------------------------------------------------------------
- * (3') The same with delayed gradient compensation -- Algorithm 1, "Compensate
- *     delayed gradients" (third mechanism of Section "Algorithm"):
+ * (3') The same with delayed gradient compensation -- Algorithm 1, the
+ *     compensation line (third mechanism of Section "Algorithm"):
  *       Gtilde = Gbar + lambda * Gbar (.) Gbar (.) (x_t - x_{t-1})   element-wise,
  *     used in place of Gbar.  The previous iterate x_{t-1} lives in a caller-owned
  *     buffer (the memory overhead the paper mentions): +8 B/param of traffic.
@@ -171,7 +214,7 @@ int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const
                        float lambda, void *stream);
 
 /* ------------------------------------------------------------------------
- * (3'm) The same compensation (Algorithm 1, "Compensate delayed gradients")
+ * (3'm) The same compensation (Algorithm 1, the compensation line)
  *     without a stored x_{t-1}: every applied update of this family is
  *     x_t = x_{t-1} - lr_{t-1} * v_t, so x_t - x_{t-1} = -lr_{t-1} * v_t with v_t
  *     the momentum as it stands on entry.  Equal to abs_sync_update_dc in exact
@@ -220,8 +263,10 @@ int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const
  *
  * abs_layout    sizes only; built on the host (needs no GPU).  It cuts every
  *               tensor into chunks of abs_layout_tile() elements, one per
- *               workgroup; the chunk table is copied to the device the first
- *               time a launch needs it.
+ *               workgroup.  abs_layout_upload copies the chunk table to the
+ *               current device and allocates the small per-chunk scratch of the
+ *               LARS rule (16 bytes per chunk); the first abs_tensorset_create
+ *               over a layout does it if the caller has not.
  * abs_tensorset T DEVICE base pointers for one logical vector (x, v, one
  *               worker's accumulator, one gradient) laid out per the layout;
  *               the pointer table is copied to device memory at creation.
@@ -232,6 +277,9 @@ typedef struct abs_tensorset abs_tensorset;
 
 /* sizes: HOST array of T element counts (each >= 0; T >= 1). */
 int abs_layout_create(abs_layout **out, int T, const int64_t *sizes);
+/* Puts the layout's tables on the current device (blocking; allocates).  Idempotent;
+ * ABS_EINVAL if the layout already lives on another device. */
+int abs_layout_upload(const abs_layout *layout);
 int abs_layout_destroy(abs_layout *layout);
 int abs_layout_num_tensors(const abs_layout *layout);
 int64_t abs_layout_total(const abs_layout *layout);
@@ -259,6 +307,18 @@ int abs_accumulate_mt(abs_layout *layout, const abs_tensorset *acc,
 int abs_accumulate_batch_mt(abs_layout *layout, const abs_tensorset *acc,
                             const abs_tensorset *const *grads, int J, const int64_t *n_samples,
                             int64_t *count, void *stream);
+
+/* abs_accumulate_jobs over every tensor of the layout: one launch covers all
+ * tensors of all jobs.  All gradient sets of a call have one element type. */
+typedef struct abs_job_mt {
+    const abs_tensorset *acc;           /* an ABS_F32 set */
+    const abs_tensorset *const *grads;  /* HOST array of J sets */
+    const int64_t *n_samples;           /* HOST array of J sample counts */
+    int J;
+    int64_t *count;                     /* HOST */
+} abs_job_mt;
+int abs_accumulate_jobs_mt(abs_layout *layout, const abs_job_mt *jobs, int njobs, int fold,
+                           void *stream);
 
 /* Same arithmetic as abs_sync_update over every tensor of the layout.
  * acc: HOST array of K sets; counts: HOST array of K int64. */
@@ -297,7 +357,7 @@ int abs_sync_update_adam_mt(abs_layout *layout, const abs_tensorset *params,
  *   gbar  an ABS_F32 set over the layout, caller-owned workspace: it receives Gbar
  *         and must differ from every other set of the call.
  *   The per-chunk sums and per-tensor rates live in device memory owned by the
- *   layout (allocated on the first LARS call): two LARS calls on one layout must
+ *   layout (allocated by abs_layout_upload): two LARS calls on one layout must
  *   not overlap in time.  A flat vector is a layout of one tensor.
  *   Other arguments, ABS_EMPTY and errors: as abs_sync_update_mt. */
 int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
@@ -306,8 +366,8 @@ int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
                             float mu, float wd, float eta, void *stream);
 
 /* ------------------------------------------------------------------------
- * (4) Double buffer -- Algorithm 1, "Run Step 1 and Step 2 in parallel": two
- *     generations of (K accumulators, K counts).  Accumulation of batch t runs
+ * (4) Double buffer -- Algorithm 1, the line that runs Step 1 and Step 2 side
+ *     by side: two generations of (K accumulators, K counts).  Accumulation of batch t runs
  *     on stream_acc into the CURRENT generation while the sync-update of batch
  *     t-1 runs on stream_upd from the PREVIOUS one.
  *
@@ -317,7 +377,8 @@ int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
  * ---------------------------------------------------------------------- */
 typedef struct abs_ctx abs_ctx;
 
-/* acc_A, acc_B: HOST arrays of K DEVICE pointers, P floats each. */
+/* acc_A, acc_B: HOST arrays of K DEVICE pointers, P floats each; the 2K buffers
+ * must not overlap one another. */
 int abs_ctx_create(abs_ctx **out, int K, int64_t P, float *const *acc_A, float *const *acc_B,
                    void *stream_acc, void *stream_upd);
 /* Ragged form: acc_A, acc_B are HOST arrays of K ABS_F32 sets over `layout`. */
@@ -325,6 +386,12 @@ int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *layout,
                       const abs_tensorset *const *acc_A, const abs_tensorset *const *acc_B,
                       void *stream_acc, void *stream_upd);
 int abs_ctx_destroy(abs_ctx *ctx);
+
+/* Settings of this context's own calls, in place of the process-wide defaults
+ * (abs_set_launch_tuning, abs_set_cache_policy; same arguments and errors).  A
+ * ragged context's tile is its layout's; only the cache policy applies to it. */
+int abs_ctx_set_launch_tuning(abs_ctx *ctx, int blocks_per_cu, int max_rows_per_tile);
+int abs_ctx_set_cache_policy(abs_ctx *ctx, int accumulate_mode, int update_mode);
 
 /* Optional: spread accumulation over n streams, worker k on streams[k % n]
  * (replaces stream_acc).  The K workers of Algorithm 1 compute at the same
@@ -357,6 +424,17 @@ int abs_ctx_accumulate_batch(abs_ctx *ctx, int k, const void *const *grads, abs_
                              int J, const int64_t *n_samples);
 int abs_ctx_accumulate_batch_mt(abs_ctx *ctx, int k, const abs_tensorset *const *grads, int J,
                                 const int64_t *n_samples);
+
+/* Step 2 of ALL K workers of an iteration in one call (abs_accumulate_jobs into
+ * the CURRENT generation): worker k contributes m[k] >= 0 gradients.  grads and
+ * n_samples list them worker by worker (worker 0's m[0] entries, then worker 1's,
+ * ...; sum_k m[k] entries each).  With fold = 8 an iteration is this call, one
+ * sync-update and the swap: two launches.  Runs on stream_acc; contexts that
+ * spread accumulation over several streams return ABS_EINVAL. */
+int abs_ctx_accumulate_step(abs_ctx *ctx, const void *const *grads, const int *m,
+                            const int64_t *n_samples, abs_dtype grad_dtype, int fold);
+int abs_ctx_accumulate_step_mt(abs_ctx *ctx, const abs_tensorset *const *grads, const int *m,
+                               const int64_t *n_samples, int fold);
 
 /* abs_sync_update from the PREVIOUS generation, on stream_upd.  ABS_EMPTY in
  * the first iteration. */

@@ -27,7 +27,7 @@
  * gradients is M_r * g.
  *
  * Delayed gradient compensation (Section "Algorithm", third mechanism; the
- * "Compensate delayed gradients" line of Algorithm 1):
+ * compensation line of Algorithm 1):
  *       Gtilde_t = Gbar_{t-1} + lambda * Gbar_{t-1} (.) Gbar_{t-1} (.) (x_t - x_{t-1})
  * element-wise, applied in place of Gbar in the update.  The paper states it for
  * plain SGD; with momentum and weight decay the compensated gradient takes

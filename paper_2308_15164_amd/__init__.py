@@ -31,6 +31,13 @@ SYMBOLS = {
     "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
     "abs_accumulate_batch": (_int, [_vp, _pvp, _int, _int, _i64, _pi64, _pi64, _vp]),
+    "abs_accumulate_jobs": (_int, [_vp, _int, _int, _i64, _int, _vp]),
+    "abs_accumulate_jobs_mt": (_int, [_vp, _vp, _int, _int, _vp]),
+    "abs_layout_upload": (_int, [_vp]),
+    "abs_ctx_set_launch_tuning": (_int, [_vp, _int, _int]),
+    "abs_ctx_set_cache_policy": (_int, [_vp, _int, _int]),
+    "abs_ctx_accumulate_step": (_int, [_vp, _pvp, ctypes.POINTER(ctypes.c_int), _pi64, _int, _int]),
+    "abs_ctx_accumulate_step_mt": (_int, [_vp, _pvp, ctypes.POINTER(ctypes.c_int), _pi64, _int]),
     "abs_sync_update": (_int, [_vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _vp]),
     "abs_sync_update_dc": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _vp]),
     "abs_sync_update_adam": (_int, [_vp, _vp, _vp, _pvp, _pi64, _int, _i64, _f, _f, _f, _f, _f, _i64, _vp]),
@@ -162,8 +169,8 @@ def abs_row_elems():
     return lib().abs_row_elems()
 
 
-def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=0):
-    """See abs_set_launch_tuning in abs_sgd.h."""
+def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=4):
+    """See abs_set_launch_tuning in abs_sgd.h; the defaults are the library's own."""
     return _check("abs_set_launch_tuning",
                   lib().abs_set_launch_tuning(int(blocks_per_cu), int(max_rows_per_tile)))
 
@@ -208,6 +215,44 @@ def abs_accumulate_batch(acc, grads, n_samples, count, stream=None, P=None, grad
                                     _dtype_of(grads[0], grad_dtype), len(grads), n, _i64_array(n_samples),
                                     ctypes.byref(count._c), _stream_handle(stream))
     return _check("abs_accumulate_batch", rc)
+
+
+class _JobC(ctypes.Structure):
+    """struct abs_job / abs_job_mt (the two have the same layout: five pointer-sized or int fields)."""
+    _fields_ = [("acc", ctypes.c_void_p), ("grads", ctypes.c_void_p), ("n_samples", ctypes.c_void_p),
+                ("J", ctypes.c_int), ("count", ctypes.c_void_p)]
+
+
+def _job_array(accs, grads, n_samples, counts):
+    """accs[w], grads[w][j], n_samples[w][j], counts[w] (Count) -> (array of abs_job, keep-alive list)."""
+    keep, arr = [], (_JobC * len(accs))()
+    for w, (a, gs, ns, c) in enumerate(zip(accs, grads, n_samples, counts)):
+        gp, np_ = _ptr_array(list(gs)) if len(gs) else None, _i64_array(ns) if len(ns) else None
+        keep += [gp, np_]
+        arr[w] = _JobC(a, ctypes.cast(gp, ctypes.c_void_p) if gp is not None else None,
+                       ctypes.cast(np_, ctypes.c_void_p) if np_ is not None else None, len(gs),
+                       ctypes.cast(ctypes.pointer(c._c), ctypes.c_void_p))
+    return arr, keep
+
+
+def abs_accumulate_jobs(accs, grads, n_samples, counts, fold=8, stream=None, P=None, grad_dtype=None):
+    """One launch sequence for several workers: job w folds grads[w] (sample counts
+    n_samples[w]) into accs[w] and advances counts[w].  See abs_accumulate_jobs in abs_sgd.h."""
+    n = accs[0].numel() if P is None else int(P)
+    first = next((g for gs in grads for g in gs), None)
+    dt = grad_dtype if grad_dtype is not None else _dtype_of(first)
+    arr, keep = _job_array([_dev_ptr(a) for a in accs], [[_dev_ptr(g) for g in gs] for gs in grads],
+                           n_samples, counts)
+    rc = lib().abs_accumulate_jobs(arr, len(accs), dt, n, int(fold), _stream_handle(stream))
+    return _check("abs_accumulate_jobs", rc)
+
+
+def abs_accumulate_jobs_mt(layout, accs, grads, n_samples, counts, fold=8, stream=None):
+    """abs_accumulate_jobs over a ragged layout: accs[w] and grads[w][j] are TensorSets."""
+    arr, keep = _job_array([a.handle.value for a in accs], [[g.handle.value for g in gs] for gs in grads],
+                           n_samples, counts)
+    rc = lib().abs_accumulate_jobs_mt(layout.handle, arr, len(accs), int(fold), _stream_handle(stream))
+    return _check("abs_accumulate_jobs_mt", rc)
 
 
 def abs_sync_update(params, momentum, acc, counts, lr, mu, wd, stream=None, P=None):
@@ -262,6 +307,9 @@ class Layout:
 
     def tile(self):
         return lib().abs_layout_tile(self.handle)
+
+    def upload(self):
+        return _check("abs_layout_upload", lib().abs_layout_upload(self.handle))
 
     def chunk(self, c):
         t, off, ln = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
@@ -407,6 +455,28 @@ class Context:
         return _check("abs_ctx_set_accumulate_streams",
                       lib().abs_ctx_set_accumulate_streams(self.handle, arr, len(streams)))
 
+    def abs_set_launch_tuning(self, blocks_per_cu=0, max_rows_per_tile=4):
+        return _check("abs_ctx_set_launch_tuning",
+                      lib().abs_ctx_set_launch_tuning(self.handle, int(blocks_per_cu), int(max_rows_per_tile)))
+
+    def abs_set_cache_policy(self, accumulate_mode=-1, update_mode=-1):
+        return _check("abs_ctx_set_cache_policy",
+                      lib().abs_ctx_set_cache_policy(self.handle, int(accumulate_mode), int(update_mode)))
+
+    def abs_accumulate_step(self, grads, m, n_samples, fold=8, grad_dtype=None):
+        """Step 2 of all K workers in one call: grads / n_samples list worker 0's m[0]
+        gradients, then worker 1's m[1], ... (device pointers, or TensorSets for a ragged context)."""
+        mc = (ctypes.c_int * len(m))(*[int(v) for v in m])
+        if self.layout is None:
+            first = grads[0] if len(grads) else None
+            dt = grad_dtype if grad_dtype is not None else _dtype_of(first)
+            rc = lib().abs_ctx_accumulate_step(self.handle, _ptr_array([_dev_ptr(g) for g in grads]), mc,
+                                               _i64_array(n_samples), dt, int(fold))
+            return _check("abs_ctx_accumulate_step", rc)
+        rc = lib().abs_ctx_accumulate_step_mt(self.handle, _ptr_array([g.handle.value for g in grads]), mc,
+                                              _i64_array(n_samples), int(fold))
+        return _check("abs_ctx_accumulate_step_mt", rc)
+
     def abs_accumulate(self, k, grad, n_samples, grad_dtype=None):
         if self.layout is None:
             rc = lib().abs_ctx_accumulate(self.handle, int(k), _dev_ptr(grad),
@@ -495,7 +565,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "abs_suggest_accumulate_streams", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_accumulate_jobs", "abs_accumulate_jobs_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

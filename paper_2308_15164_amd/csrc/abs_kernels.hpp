@@ -33,9 +33,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#ifndef ABS_BLOCK
-#define ABS_BLOCK 256          // threads per workgroup (4 wavefronts)
-#endif
+#include "abs_types.hpp"
+
+#define ABS_BLOCK 256          // threads per workgroup (4 wavefronts); literal for __launch_bounds__
 #ifndef ABS_ACC_UNROLL
 #define ABS_ACC_UNROLL 4       // rows per group in accumulate (2 loads per row in flight)
 #endif
@@ -54,9 +54,9 @@
 
 namespace absk {
 
-constexpr int BLOCK = ABS_BLOCK;
+static_assert(BLOCK == ABS_BLOCK, "the host plans launches for this workgroup size");
 constexpr int VEC = 4;                 // elements per lane per access
-constexpr int ROW = BLOCK * VEC;       // elements per workgroup row; tiles are whole rows
+static_assert(ROW == BLOCK * VEC, "a workgroup row is one 128-bit vector per lane");
 
 // Vector index of (row u, lane tid) in a group of U rows starting at g0.  Two
 // layouts, both covering [g0, g0 + U*BLOCK) exactly once:
@@ -266,26 +266,8 @@ __device__ __forceinline__ void accumulate_tile(float *__restrict__ acc, const G
 
 // --------------------------------------------------------------- sync-update
 
-// Update rules of the fused combine + update pass.  Each keeps, besides x, up
-// to two more per-parameter state vectors (s1, s2):
-//   SGD   : s1 = momentum v                                   (s2 unused)
-//   SGD_DC: s1 = momentum v,        s2 = previous iterate x_{t-1}
-//   ADAM  : s1 = first moment m,    s2 = second moment v
-//   SGD_DCM: s1 = momentum v; the compensation of SGD_DC with x_t - x_{t-1}
-//            taken as -lr_{t-1} * v, which is what the previous update
-//            subtracted from x (s2 unused, 8 bytes per parameter less traffic)
-enum Rule { SGD = 0, SGD_DC = 1, ADAM = 2, SGD_DCM = 3 };
-
-template <int RULE> constexpr bool uses_s2() { return RULE == SGD_DC || RULE == ADAM; }
-
-struct Hyper {
-    float M, lr, wd;
-    float mu, lambda;                        // SGD, SGD_DC, SGD_DCM
-    float nlr_prev;                          // SGD_DCM: minus the step size of the previous applied update
-    float beta1, beta2, omb1, omb2, eps;     // ADAM: omb = 1 - beta (rounded to fp32 on the host)
-    float bc1, bc2;                          // ADAM: 1 - beta^t, computed in double on the host
-};
-
+// The update rules (enum Rule) and their hyper-parameters (Hyper) are in abs_types.hpp.
+//
 // One element.  s = sum of the workers' accumulators.  Orders (every operation
 // rounded to fp32, fused where written as fma):
 //   Gbar = s / M
@@ -492,23 +474,6 @@ __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__re
     }
 }
 
-// dst[0..len) = src[0..len): keeps the previous-iterate buffer current on a step
-// that applies nothing.
-__device__ __forceinline__ void copy_tile(float *__restrict__ dst, const float *__restrict__ src, int len,
-                                          bool vec_ok)
-{
-    const int tid = threadIdx.x;
-    if (vec_ok) {
-        const int nvec = len / VEC;
-        for (int i = tid; i < nvec; i += BLOCK)
-            reinterpret_cast<f32x4 *>(dst)[i] = reinterpret_cast<const f32x4 *>(src)[i];
-        const int i = nvec * VEC + tid;
-        if (i < len) dst[i] = src[i];
-        return;
-    }
-    for (int i = tid; i < len; i += BLOCK) dst[i] = src[i];
-}
-
 struct AccPtrsAny { const float *p[64]; };
 
 // -------------------------------------------------------------------- kernels
@@ -561,18 +526,9 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restr
                         [&](int k) { return A.p[k] + base; }, K, tile_len(P, base, tile), h, vec_ok != 0);
 }
 
-__global__ __launch_bounds__(ABS_BLOCK) void copy_flat(float *__restrict__ dst,
-                                                      const float *__restrict__ src, int64_t P,
-                                                      int tile, int vec_ok)
-{
-    const int64_t base = (int64_t)blockIdx.x * tile;
-    copy_tile(dst + base, src + base, tile_len(P, base, tile), vec_ok != 0);
-}
-
 // Ragged layout: workgroup b looks its (tensor, tile index) up in a table; the
 // per-tensor base pointers come from device-resident pointer tables.  All of
 // these reads are uniform across the workgroup (scalar loads).
-struct Chunk { int32_t tensor; int32_t index; };
 
 // J gradient pointer tables (one per micro-batch) and their sample counts.
 template <int J>
@@ -600,6 +556,62 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__re
         vec_ok = vec_ok && (BF16 ? aligned8(G.g[j]) : aligned16(G.g[j]));
     }
     accumulate_tile<BF16, NTA, J>(acc, G, tile_len(sizes[c.tensor], base, tile), first != 0, vec_ok);
+}
+
+// ---------------------------------------------------------------- job lists
+//
+// One launch for several workers: job w is one worker's share of the launch, its
+// accumulator and the J_w <= 8 gradients folded into it, in order, with the
+// roundings of J_w single launches.  Workgroup (x, y) owns tile x of job y; the
+// hardware hands out x fastest, so the jobs stream through the chip one after
+// the other with no ramp-up or drain between them, and a launch lasts as long
+// as all of them together.  The job table travels in the kernel arguments and
+// is read with scalar loads (y is uniform over the workgroup).
+// JMAX bounds the J of every job of the launch (the host instantiates 1, 2, 4, 8), so
+// that a launch of single gradients does not carry the registers of an 8-gradient one.
+template <bool BF16, bool NTA, int JMAX, int J = 1>
+__device__ __forceinline__ void accumulate_job_tile(float *__restrict__ acc, const Job &jb, int64_t base,
+                                                    const void *const *gp, int len)
+{
+    typedef typename GradT<BF16>::elem gelem;
+    if (jb.J == J) {
+        GradArgs<BF16, J> G;
+        bool vec_ok = aligned16(acc);
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            G.g[j] = static_cast<const gelem *>(gp[j]) + base;
+            G.n[j] = jb.n[j];
+            vec_ok = vec_ok && (BF16 ? aligned8(G.g[j]) : aligned16(G.g[j]));
+        }
+        accumulate_tile<BF16, NTA, J>(acc, G, len, jb.first != 0, vec_ok);
+        return;
+    }
+    if constexpr (J < JMAX) accumulate_job_tile<BF16, NTA, JMAX, J + 1>(acc, jb, base, gp, len);
+}
+
+template <bool BF16, bool NTA, int JMAX>
+__global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_flat(JobList L, int64_t P, int tile)
+{
+    const Job &jb = L.job[blockIdx.y];
+    const int64_t base = (int64_t)blockIdx.x * tile;
+    accumulate_job_tile<BF16, NTA, JMAX>(static_cast<float *>(jb.acc) + base, jb, base, jb.g,
+                                         tile_len(P, base, tile));
+}
+
+template <bool BF16, bool NTA, int JMAX>
+__global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_ragged(const Chunk *__restrict__ chunks,
+                                                                   const int64_t *__restrict__ sizes,
+                                                                   JobList L, int tile)
+{
+    const Job &jb = L.job[blockIdx.y];
+    const Chunk c = chunks[blockIdx.x];
+    const int64_t base = (int64_t)c.index * tile;
+    const void *gp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        gp[j] = (j < JMAX && j < jb.J) ? static_cast<const void *const *>(jb.g[j])[c.tensor] : nullptr;
+    accumulate_job_tile<BF16, NTA, JMAX>(static_cast<float *const *>(jb.acc)[c.tensor] + base, jb, base, gp,
+                                         tile_len(sizes[c.tensor], base, tile));
 }
 
 template <int K> struct TabPtrs { const float *const *t[K]; };
@@ -650,231 +662,6 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk 
     for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned16(tabs.t[k][c.tensor] + base);
     sync_tile_any<RULE>(x, v, xp, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
                         tile_len(sizes[c.tensor], base, tile), h, vec_ok);
-}
-
-__global__ __launch_bounds__(ABS_BLOCK) void copy_ragged(const Chunk *__restrict__ chunks,
-                                                        const int64_t *__restrict__ sizes,
-                                                        float *const *__restrict__ dst_tab,
-                                                        float *const *__restrict__ src_tab, int tile)
-{
-    const Chunk c = chunks[blockIdx.x];
-    const int64_t base = (int64_t)c.index * tile;
-    float *dst = dst_tab[c.tensor] + base;
-    const float *src = src_tab[c.tensor] + base;
-    copy_tile(dst, src, tile_len(sizes[c.tensor], base, tile), aligned16(dst) && aligned16(src));
-}
-
-
-// ----------------------------------------------------------------------- LARS
-//
-// Layer-wise adaptive rate scaling needs two Euclidean norms per tensor before
-// any element can be updated, so it takes three launches over the ragged layout:
-//   1. lars_reduce : Gbar = (sum_k acc_k) / M is formed once, written to a
-//                    workspace, and each workgroup leaves the sums of Gbar^2 and
-//                    x^2 over its chunk (4K + 8 B/param);
-//   2. lars_rates  : one workgroup per tensor adds its chunks' sums and turns
-//                    them into the tensor's step factor (negligible traffic);
-//   3. lars_update : v = fma(mu, v, step_l * fma(wd, x, Gbar)); x = x - v
-//                    (20 B/param, independent of K).
-// Sums are carried in double and added in a fixed order (lane, wavefront,
-// workgroup, chunk), so results do not depend on timing.
-
-// Sums a and b over the workgroup; the totals are valid in thread 0.
-__device__ __forceinline__ void block_sum2(double &a, double &b)
-{
-    __shared__ double sm[2][BLOCK / 64];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        a += __shfl_down(a, off);
-        b += __shfl_down(b, off);
-    }
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) { sm[0][wave] = a; sm[1][wave] = b; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a = sm[0][0];
-        b = sm[1][0];
-        for (int w = 1; w < BLOCK / 64; ++w) { a += sm[0][w]; b += sm[1][w]; }
-    }
-}
-
-__device__ __forceinline__ void add_squares(double &acc, f32x4 q)
-{
-    acc += (double)q.x * (double)q.x;
-    acc += (double)q.y * (double)q.y;
-    acc += (double)q.z * (double)q.z;
-    acc += (double)q.w * (double)q.w;
-}
-
-__global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__restrict__ chunks,
-                                                               const int64_t *__restrict__ sizes,
-                                                               float *const *__restrict__ x_tab,
-                                                               float *const *__restrict__ g_tab,
-                                                               TabPtrsAny tabs, int K, int tile, float M,
-                                                               double *__restrict__ partials)
-{
-    constexpr int U = 4, KC = 4;
-    const Chunk c = chunks[blockIdx.x];
-    const int64_t base = (int64_t)c.index * tile;
-    const int len = tile_len(sizes[c.tensor], base, tile);
-    const float *__restrict__ x = x_tab[c.tensor] + base;
-    float *__restrict__ gb = g_tab[c.tensor] + base;
-    bool vec_ok = aligned16(x) && aligned16(gb);
-    for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned16(tabs.t[k][c.tensor] + base);
-    const int tid = threadIdx.x;
-    double sx = 0.0, sg = 0.0;
-    int done = 0;
-    if (vec_ok) {
-        const int nvec = len / VEC;
-        const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
-        f32x4 *gv = reinterpret_cast<f32x4 *>(gb);
-        for (int g0 = 0; g0 < nvec; g0 += U * BLOCK) {
-            f32x4 sum[U] = {}, xr[U] = {};
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = GIDX(g0, u, tid, U, false);
-                if (i < nvec) xr[u] = xv[i];
-            }
-            for (int k0 = 0; k0 < K; k0 += KC) {
-                f32x4 a[U][KC] = {};
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk) {
-                    if (k0 + kk < K) {
-                        const f32x4 *ap = reinterpret_cast<const f32x4 *>(tabs.t[k0 + kk][c.tensor] + base);
-#pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            const int i = GIDX(g0, u, tid, U, false);
-                            if (i < nvec) a[u][kk] = ld<ABS_NT_SYNC_ACC != 0>(ap + i);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk) {
-                    if (k0 + kk < K) {
-#pragma unroll
-                        for (int u = 0; u < U; ++u) sum[u] = (k0 + kk == 0) ? a[u][kk] : sum[u] + a[u][kk];
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = GIDX(g0, u, tid, U, false);
-                if (i < nvec) {
-                    f32x4 g;
-                    g.x = sum[u].x / M; g.y = sum[u].y / M; g.z = sum[u].z / M; g.w = sum[u].w / M;
-                    gv[i] = g;
-                    add_squares(sg, g);
-                    add_squares(sx, xr[u]);
-                }
-            }
-        }
-        done = nvec * VEC;
-    }
-    for (int i = done + tid; i < len; i += BLOCK) {
-        float s = tabs.t[0][c.tensor][base + i];
-        for (int k = 1; k < K; ++k) s = s + tabs.t[k][c.tensor][base + i];
-        const float g = s / M;
-        gb[i] = g;
-        sg += (double)g * (double)g;
-        sx += (double)x[i] * (double)x[i];
-    }
-    block_sum2(sx, sg);
-    if (tid == 0) {
-        partials[2 * (int64_t)blockIdx.x] = sx;
-        partials[2 * (int64_t)blockIdx.x + 1] = sg;
-    }
-}
-
-// One workgroup per tensor: chunk_begin[t] .. chunk_begin[t+1] are its chunks
-// (thousands for an embedding matrix, so the reads are spread over the workgroup
-// and issued several at a time; the order of the additions stays fixed).
-//   rate = eta*||x|| / (||g|| + wd*||x||)  (1 if either norm is 0);  step[t] = (float)(lr * rate)
-__global__ __launch_bounds__(ABS_BLOCK) void lars_rates(const int32_t *__restrict__ chunk_begin,
-                                                       const double *__restrict__ partials,
-                                                       float *__restrict__ step, double lr, double wd, double eta)
-{
-    const int t = blockIdx.x;
-    const int begin = chunk_begin[t], end = chunk_begin[t + 1];
-    double sx = 0.0, sg = 0.0;
-    int c = begin + (int)threadIdx.x;
-    for (; c + 3 * BLOCK < end; c += 4 * BLOCK) {
-        double px[4], pg[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            px[u] = partials[2 * (int64_t)(c + u * BLOCK)];
-            pg[u] = partials[2 * (int64_t)(c + u * BLOCK) + 1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { sx += px[u]; sg += pg[u]; }
-    }
-    for (; c < end; c += BLOCK) {
-        sx += partials[2 * (int64_t)c];
-        sg += partials[2 * (int64_t)c + 1];
-    }
-    block_sum2(sx, sg);
-    if (threadIdx.x == 0) {
-        const double xn = sqrt(sx), gn = sqrt(sg);
-        const double rate = (xn > 0.0 && gn > 0.0) ? eta * xn / (gn + wd * xn) : 1.0;
-        step[t] = (float)(lr * rate);
-    }
-}
-
-// d = fma(wd, x, Gbar); v = fma(mu, v, step_l * d); x = x - v.
-__global__ __launch_bounds__(ABS_BLOCK) void lars_update_ragged(const Chunk *__restrict__ chunks,
-                                                               const int64_t *__restrict__ sizes,
-                                                               float *const *__restrict__ x_tab,
-                                                               float *const *__restrict__ v_tab,
-                                                               float *const *__restrict__ g_tab,
-                                                               const float *__restrict__ step, int tile,
-                                                               float mu, float wd)
-{
-    constexpr int U = 4;
-    const Chunk c = chunks[blockIdx.x];
-    const int64_t base = (int64_t)c.index * tile;
-    const int len = tile_len(sizes[c.tensor], base, tile);
-    float *__restrict__ x = x_tab[c.tensor] + base;
-    float *__restrict__ v = v_tab[c.tensor] + base;
-    const float *__restrict__ gb = g_tab[c.tensor] + base;
-    const float st_l = step[c.tensor];
-    const bool vec_ok = aligned16(x) && aligned16(v) && aligned16(gb);
-    const int tid = threadIdx.x;
-    int done = 0;
-    if (vec_ok) {
-        const int nvec = len / VEC;
-        f32x4 *xv = reinterpret_cast<f32x4 *>(x);
-        f32x4 *vv = reinterpret_cast<f32x4 *>(v);
-        const f32x4 *gv = reinterpret_cast<const f32x4 *>(gb);
-        for (int g0 = 0; g0 < nvec; g0 += U * BLOCK) {
-            f32x4 g[U] = {}, xr[U] = {}, vr[U] = {};
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = GIDX(g0, u, tid, U, false);
-                if (i < nvec) { g[u] = ld<true>(gv + i); xr[u] = xv[i]; vr[u] = vv[i]; }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = GIDX(g0, u, tid, U, false);
-                if (i < nvec) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float d = __builtin_fmaf(wd, xr[u][e], g[u][e]);
-                        const float vn = __builtin_fmaf(mu, vr[u][e], st_l * d);
-                        vr[u][e] = vn;
-                        xr[u][e] = xr[u][e] - vn;
-                    }
-                    vv[i] = vr[u];
-                    xv[i] = xr[u];
-                }
-            }
-        }
-        done = nvec * VEC;
-    }
-    for (int i = done + tid; i < len; i += BLOCK) {
-        const float d = __builtin_fmaf(wd, x[i], gb[i]);
-        const float vn = __builtin_fmaf(mu, v[i], st_l * d);
-        v[i] = vn;
-        x[i] = x[i] - vn;
-    }
 }
 
 }  // namespace absk

@@ -1,31 +1,24 @@
 // Host side of the ABS-SGD hot-path library: argument checks, the ragged
-// layout's chunk table, the double-buffer context, and kernel launches.
+// layout's chunk table, the double-buffer context, and the C ABI.  The kernels
+// and their launch functions live in the launch_*.hip units (abs_host.hpp).
 // The C ABI and the arithmetic contract are stated in include/abs_sgd.h.
-#include "abs_kernels.hpp"
-
-#include <hip/hip_runtime.h>
+#include "abs_host.hpp"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
-#include <cstdint>
 #include <cstring>
 #include <limits>
 #include <new>
 #include <vector>
 
-#include "abs_sgd.h"
-
-#ifndef ABS_ACC_STREAM_BYTES
-#define ABS_ACC_STREAM_BYTES (int64_t(160) << 20)
-#endif
-#ifndef ABS_MAX_ROWS
-#define ABS_MAX_ROWS 4
-#endif
-#ifndef ABS_UPD_STREAM_BYTES
-#define ABS_UPD_STREAM_BYTES (int64_t(256) << 20)
-#endif
-
-using namespace absk;
+using namespace absh;
+using absk::ADAM;
+using absk::Job;
+using absk::MAX_JOBS;
+using absk::SGD;
+using absk::SGD_DC;
+using absk::SGD_DCM;
 
 namespace {
 
@@ -45,6 +38,13 @@ inline int hip_fail(hipError_t e)
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Do [a, a + an) and [b, b + bn) share a byte?
+inline bool overlap(const void *a, int64_t an, const void *b, int64_t bn)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return an > 0 && bn > 0 && a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
+}
+
 inline int launch_status()
 {
     hipError_t e = hipGetLastError();
@@ -52,65 +52,19 @@ inline int launch_status()
     return ABS_OK;
 }
 
-constexpr int64_t kMaxGrid = 0x7fffffff;
-constexpr int64_t kMaxTile = int64_t(1) << 30;   // tile sizes travel as int
+// Process-wide defaults; a context may carry settings of its own.  Atomics, so that
+// a launch racing with one of the setters reads either the old or the new value.
+std::atomic<int> g_blocks_per_cu{0}, g_max_rows{ABS_MAX_ROWS};
+std::atomic<int> g_policy_acc{-1}, g_policy_upd{-1};
 
-// ------------------------------------------------------------ launch shape
-//
-// A launch should fill the chip in whole rounds: with `resident` workgroups
-// able to run at once, the tile is the smallest whole number of rows that
-// covers n rows in `rounds` rounds, rounds being the fewest that keep a tile
-// within g_max_rows rows (0 = no limit: always one round, every workgroup
-// walks one long run of memory).  Measured on MI355X: short tiles (<= 4 rows,
-// many rounds) beat long per-workgroup runs by 15-20 % at P >= 1e8, because all
-// resident workgroups then sweep one compact window of memory.
-int g_blocks_per_cu = 0;                  // 0 = what each kernel's register use allows
-int g_max_rows = ABS_MAX_ROWS;
-
-// Compute units of the current device; 256 (MI355X) when no device can be asked,
-// e.g. when a layout is built on a host without a GPU.
-int cu_count()
+inline Tuning process_tuning()
 {
-    static const int n = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-            return cus;
-        (void)hipGetLastError();
-        return 256;
-    }();
-    return n;
+    return Tuning{g_blocks_per_cu.load(std::memory_order_relaxed), g_max_rows.load(std::memory_order_relaxed),
+                  g_policy_acc.load(std::memory_order_relaxed), g_policy_upd.load(std::memory_order_relaxed)};
 }
 
-inline int64_t rows_of(int64_t P) { return (P + ROW - 1) / ROW; }
-
-int64_t choose_tile(int64_t rows, int resident)
-{
-    if (rows <= resident) return ROW;
-    int64_t rounds = 1;
-    if (g_max_rows > 0) rounds = (rows + (int64_t)resident * g_max_rows - 1) / ((int64_t)resident * g_max_rows);
-    const int64_t slots = (int64_t)resident * rounds;
-    return ((rows + slots - 1) / slots) * ROW;
-}
-
-inline int64_t tiles_for(int64_t P, int64_t tile) { return (P + tile - 1) / tile; }
-
-// Workgroups of `kernel` one CU can hold, from the runtime's occupancy calculator.
-template <class Kernel>
-int occupancy_per_cu(Kernel kernel, int fallback)
-{
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, BLOCK, 0) == hipSuccess && n > 0) return n;
-    (void)hipGetLastError();
-    return fallback;
-}
-
-// Workgroups resident on the whole chip, with the caller's override applied.
-inline int resident(int per_cu) { return (g_blocks_per_cu > 0 ? g_blocks_per_cu : per_cu) * cu_count(); }
-
-// The accumulate kernels need few registers: 8 workgroups of 4 wavefronts per CU.
-constexpr int kAccBlocksPerCU = 8;
-inline int acc_resident() { return resident(kAccBlocksPerCU); }
+inline bool tuning_ok(int blocks_per_cu, int max_rows) { return blocks_per_cu >= 0 && blocks_per_cu <= 32 && max_rows >= 0; }
+inline bool policy_ok(int a, int u) { return a >= -1 && a <= 1 && u >= -1 && u <= 1; }
 
 // counts -> compacted list of non-empty workers and their total.
 struct Combine {
@@ -133,119 +87,48 @@ int plan_combine(const int64_t *counts, int K, Combine &c)
     return c.M == 0 ? ABS_EMPTY : ABS_OK;
 }
 
-// ------------------------------------------------------------ cache policy
-//
-// Accumulators, x and v are touched again soon after a kernel ends.  When they
-// fit the memory-side cache (256 MiB on this part) keeping them cached pays;
-// when they do not, streaming (non-temporal) accesses avoid allocating lines
-// that are evicted before their reuse.  -1 = decide from the sizes.
-int g_policy_acc = -1, g_policy_upd = -1;
-constexpr int64_t kAccStreamBytes = ABS_ACC_STREAM_BYTES;   // accumulator bytes above which accumulate streams
-constexpr int64_t kUpdStreamBytes = ABS_UPD_STREAM_BYTES;   // bytes of x + v (+ previous x) above which sync-update streams
-
-inline bool stream_acc(int64_t P) { return g_policy_acc < 0 ? 4 * P > kAccStreamBytes : g_policy_acc != 0; }
-inline bool stream_upd(int64_t P, int vectors = 2) { return g_policy_upd < 0 ? 4 * vectors * P > kUpdStreamBytes : g_policy_upd != 0; }
-
-// ------------------------------------------------------------ flat launches
-
-template <bool BF16, int J>
-void launch_accumulate_flat_j(float *acc, const void *const *grads, const float *nf, int64_t P, int tile,
-                              unsigned nblocks, int first, int vec_ok, bool nta, hipStream_t s)
+// Hyper-parameters of the rules in one struct.
+Hyper hyper_sgd(float lr, float mu, float wd, float lambda, float lr_prev = 0.f)
 {
-    GradArgs<BF16, J> G;
-    for (int j = 0; j < J; ++j) {
-        G.g[j] = static_cast<const typename GradT<BF16>::elem *>(grads[j]);
-        G.n[j] = nf[j];
-    }
-    const dim3 grid(nblocks), block(BLOCK);
-    if (nta) hipLaunchKernelGGL((accumulate_flat<BF16, true, J>), grid, block, 0, s, acc, G, P, tile, first, vec_ok);
-    else hipLaunchKernelGGL((accumulate_flat<BF16, false, J>), grid, block, 0, s, acc, G, P, tile, first, vec_ok);
+    Hyper h = {};
+    h.lr = lr; h.mu = mu; h.wd = wd; h.lambda = lambda; h.nlr_prev = -lr_prev;
+    return h;
 }
 
-// One launch: J <= ABS_MAX_BATCH gradients into one accumulator.
-int launch_accumulate_flat(float *acc, const void *const *grads, const float *nf, int J, abs_dtype dt,
-                           int64_t P, int first, int vec_ok, hipStream_t s)
+int hyper_adam(Hyper &h, float lr, float beta1, float beta2, float eps, float wd, int64_t step)
 {
-    const int64_t tile64 = choose_tile(rows_of(P), acc_resident());
-    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
-    const int tile = (int)tile64;
-    const unsigned nb = (unsigned)tiles_for(P, tile64);
-    const bool bf = dt == ABS_BF16, nta = stream_acc(P);
-    switch (J) {
-#define ABS_CASE(N)                                                                                     \
-    case N:                                                                                             \
-        if (bf) launch_accumulate_flat_j<true, N>(acc, grads, nf, P, tile, nb, first, vec_ok, nta, s);  \
-        else launch_accumulate_flat_j<false, N>(acc, grads, nf, P, tile, nb, first, vec_ok, nta, s);    \
-        break;
-        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-#undef ABS_CASE
-    default: return ABS_EINVAL;
-    }
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return ABS_EINVAL;
+    h = Hyper{};
+    h.lr = lr; h.wd = wd; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps;
+    h.omb1 = 1.0f - beta1;
+    h.omb2 = 1.0f - beta2;
+    h.bc1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    h.bc2 = (float)(1.0 - std::pow((double)beta2, (double)step));
     return ABS_OK;
 }
 
-template <int K, int RULE>
-int launch_sync_flat_kr(float *x, float *v, float *xp, const float *const *ptrs, int64_t P, const Hyper &h,
-                        int vec_ok, hipStream_t s)
-{
-    static const int per_cu = occupancy_per_cu(sync_update_flat<K, false, RULE>, 4);
-    const int64_t tile64 = choose_tile(rows_of(P), resident(per_cu));
-    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
-    const int tile = (int)tile64;
-    AccPtrs<K> A;
-    for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
-    const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
-    // x and each state vector are re-read one iteration later
-    if (stream_upd(P, uses_s2<RULE>() ? 3 : 2))
-        hipLaunchKernelGGL((sync_update_flat<K, true, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    else
-        hipLaunchKernelGGL((sync_update_flat<K, false, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    return ABS_OK;
-}
-
-template <int RULE>
-int launch_sync_flat_r(float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P,
-                       const Hyper &h, int vec_ok, hipStream_t s)
-{
-    switch (n) {
-#define ABS_CASE(K) case K: return launch_sync_flat_kr<K, RULE>(x, v, xp, ptrs, P, h, vec_ok, s);
-        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
-        ABS_CASE(16)
-#undef ABS_CASE
-    default: {
-        const int64_t tile64 = choose_tile(rows_of(P), resident(4));
-        if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
-        AccPtrsAny A;
-        std::memset(&A, 0, sizeof A);
-        for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
-        hipLaunchKernelGGL(sync_update_flat_any<RULE>, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0,
-                           s, x, v, xp, A, n, P, (int)tile64, h, vec_ok);
-        return ABS_OK;
-    }
-    }
-}
-
-int launch_sync_flat(int rule, float *x, float *v, float *xp, const float *const *ptrs, int n, int64_t P,
-                     const Hyper &h, int vec_ok, hipStream_t s)
+int launch_sync_flat(const Tuning &tu, int rule, float *x, float *s1, float *s2, const float *const *ptrs, int n,
+                     int64_t P, const Hyper &h, int vec_ok, hipStream_t s)
 {
     switch (rule) {
-    case SGD: return launch_sync_flat_r<SGD>(x, v, xp, ptrs, n, P, h, vec_ok, s);
-    case SGD_DC: return launch_sync_flat_r<SGD_DC>(x, v, xp, ptrs, n, P, h, vec_ok, s);
-    case ADAM: return launch_sync_flat_r<ADAM>(x, v, xp, ptrs, n, P, h, vec_ok, s);
-    case SGD_DCM: return launch_sync_flat_r<SGD_DCM>(x, v, xp, ptrs, n, P, h, vec_ok, s);
+    case SGD: return launch_sync_flat_r<SGD>(tu, x, s1, s2, ptrs, n, P, h, vec_ok, s);
+    case SGD_DC: return launch_sync_flat_r<SGD_DC>(tu, x, s1, s2, ptrs, n, P, h, vec_ok, s);
+    case ADAM: return launch_sync_flat_r<ADAM>(tu, x, s1, s2, ptrs, n, P, h, vec_ok, s);
+    case SGD_DCM: return launch_sync_flat_r<SGD_DCM>(tu, x, s1, s2, ptrs, n, P, h, vec_ok, s);
     default: return ABS_EINVAL;
     }
 }
 
-int launch_copy_flat(float *dst, const float *src, int64_t P, hipStream_t s)
+int launch_sync_ragged(const Tuning &tu, int rule, const RaggedView &L, float *const *xt, float *const *s1t,
+                       float *const *s2t, const float *const *const *tabs, int n, const Hyper &h, hipStream_t s)
 {
-    const int64_t tile64 = choose_tile(rows_of(P), acc_resident());
-    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
-    const int vec_ok = aligned_to(dst, 16) && aligned_to(src, 16);
-    hipLaunchKernelGGL(copy_flat, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s, dst, src, P,
-                       (int)tile64, vec_ok);
-    return ABS_OK;
+    switch (rule) {
+    case SGD: return launch_sync_ragged_r<SGD>(tu, L, xt, s1t, s2t, tabs, n, h, s);
+    case SGD_DC: return launch_sync_ragged_r<SGD_DC>(tu, L, xt, s1t, s2t, tabs, n, h, s);
+    case ADAM: return launch_sync_ragged_r<ADAM>(tu, L, xt, s1t, s2t, tabs, n, h, s);
+    case SGD_DCM: return launch_sync_ragged_r<SGD_DCM>(tu, L, xt, s1t, s2t, tabs, n, h, s);
+    default: return ABS_EINVAL;
+    }
 }
 
 }  // namespace
@@ -257,15 +140,15 @@ struct abs_layout {
     std::vector<Chunk> chunks;
     int64_t total = 0;
     int tile = ROW;                      // elements per chunk, a multiple of ROW
-    // device copies, made on first use
-    Chunk *d_chunks = nullptr;
-    int64_t *d_sizes = nullptr;
-    int device = -1;
-    // LARS only, made on its first use: first chunk of every tensor (T + 1 entries),
-    // per-chunk sums of squares, per-tensor step factors
-    int32_t *d_chunk_begin = nullptr;
-    double *d_partials = nullptr;
-    float *d_step = nullptr;
+    // Device copies and the LARS scratch (first chunk of every tensor, T + 1 entries;
+    // per-chunk sums of squares; per-tensor step factors): made by abs_layout_upload,
+    // which creating a tensor set over the layout calls, so no launch ever allocates.
+    mutable Chunk *d_chunks = nullptr;
+    mutable int64_t *d_sizes = nullptr;
+    mutable int32_t *d_chunk_begin = nullptr;
+    mutable double *d_partials = nullptr;
+    mutable float *d_step = nullptr;
+    mutable int device = -1;             // -1: not uploaded
 };
 
 struct abs_tensorset {
@@ -283,7 +166,7 @@ struct abs_ctx {
     std::vector<const abs_tensorset *> set[2];
     std::vector<int64_t> counts[2];
     int cur = 0;
-    std::vector<hipStream_t> s_acc;      // worker k accumulates on s_acc[k % size]
+    std::vector<hipStream_t> s_acc;      // worker k accumulates on s_acc[slot[k]]
     hipStream_t s_upd = nullptr;
     std::vector<hipEvent_t> ev_acc;      // one per accumulate stream
     hipEvent_t ev_upd = nullptr;
@@ -293,120 +176,434 @@ struct abs_ctx {
     std::vector<int64_t> launches;       // accumulate launches of worker k in the current step
     float lr_applied = 0.f;              // step size of the last abs_ctx_sync_update_dcm* call; 0 after an empty one
 
+    // settings of this context's calls; where not set, the process-wide ones at the time of the call
+    bool own_shape = false, own_policy = false;
+    int blocks_per_cu = 0, max_rows = ABS_MAX_ROWS, policy_acc = -1, policy_upd = -1;
+
     hipStream_t stream_of(int k) const { return s_acc[(size_t)slot[(size_t)k]]; }
+
+    Tuning tuning() const
+    {
+        Tuning t = process_tuning();
+        if (own_shape) { t.blocks_per_cu = blocks_per_cu; t.max_rows = max_rows; }
+        if (own_policy) { t.policy_acc = policy_acc; t.policy_upd = policy_upd; }
+        return t;
+    }
 };
 
 namespace {
 
-int layout_to_device(abs_layout *L)
+void layout_free_device(const abs_layout *L)
+{
+    if (L->d_chunks) (void)hipFree(L->d_chunks);
+    if (L->d_sizes) (void)hipFree(L->d_sizes);
+    if (L->d_chunk_begin) (void)hipFree(L->d_chunk_begin);
+    if (L->d_partials) (void)hipFree(L->d_partials);
+    if (L->d_step) (void)hipFree(L->d_step);
+    L->d_chunks = nullptr;
+    L->d_sizes = nullptr;
+    L->d_chunk_begin = nullptr;
+    L->d_partials = nullptr;
+    L->d_step = nullptr;
+    L->device = -1;
+}
+
+// Copies the tables to the current device and allocates the LARS scratch.  Blocking;
+// called when a tensor set is created (or explicitly), never from a launch.
+int layout_upload(const abs_layout *L)
 {
     int dev = 0;
     ABS_HIP(hipGetDevice(&dev));
-    if (L->d_chunks) return L->device == dev ? ABS_OK : ABS_EINVAL;
-    if (L->chunks.empty()) { L->device = dev; return ABS_OK; }
-    Chunk *dc = nullptr;
-    int64_t *ds = nullptr;
-    ABS_HIP(hipMalloc(&dc, L->chunks.size() * sizeof(Chunk)));
-    hipError_t e = hipMalloc(&ds, L->sizes.size() * sizeof(int64_t));
-    if (e == hipSuccess) e = hipMemcpy(dc, L->chunks.data(), L->chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ds, L->sizes.data(), L->sizes.size() * sizeof(int64_t), hipMemcpyHostToDevice);
+    if (L->device >= 0) return L->device == dev ? ABS_OK : ABS_EINVAL;
+    const size_t T = L->sizes.size(), C = L->chunks.size();
+    std::vector<int32_t> begin(T + 1, 0);
+    for (const Chunk &c : L->chunks) begin[(size_t)c.tensor + 1] += 1;
+    for (size_t t = 0; t < T; ++t) begin[t + 1] += begin[t];
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&L->d_sizes), T * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&L->d_chunk_begin), (T + 1) * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&L->d_step), T * sizeof(float));
+    if (e == hipSuccess && C > 0) e = hipMalloc(reinterpret_cast<void **>(&L->d_chunks), C * sizeof(Chunk));
+    if (e == hipSuccess && C > 0) e = hipMalloc(reinterpret_cast<void **>(&L->d_partials), 2 * C * sizeof(double));
+    if (e == hipSuccess) e = hipMemcpy(L->d_sizes, L->sizes.data(), T * sizeof(int64_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(L->d_chunk_begin, begin.data(), (T + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess && C > 0) e = hipMemcpy(L->d_chunks, L->chunks.data(), C * sizeof(Chunk), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
-        (void)hipFree(dc);
-        if (ds) (void)hipFree(ds);
+        layout_free_device(L);
         return hip_fail(e);
     }
-    L->d_chunks = dc;
-    L->d_sizes = ds;
     L->device = dev;
     return ABS_OK;
 }
 
-int layout_lars_scratch(abs_layout *L)
+// The layout's device tables for a launch on the current device.  Never allocates:
+// a layout that no tensor set was ever made over cannot reach a launch.
+int layout_view(const abs_layout *L, RaggedView &v)
 {
-    if (L->d_partials) return ABS_OK;
-    std::vector<int32_t> begin(L->sizes.size() + 1, 0);
-    for (const Chunk &c : L->chunks) begin[(size_t)c.tensor + 1] += 1;
-    for (size_t t = 0; t < L->sizes.size(); ++t) begin[t + 1] += begin[t];
-    int32_t *db = nullptr;
-    double *dp = nullptr;
-    float *ds = nullptr;
-    hipError_t e = hipMalloc(&db, begin.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(&dp, 2 * L->chunks.size() * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc(&ds, L->sizes.size() * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(db, begin.data(), begin.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        if (db) (void)hipFree(db);
-        if (dp) (void)hipFree(dp);
-        if (ds) (void)hipFree(ds);
-        return hip_fail(e);
-    }
-    L->d_chunk_begin = db;
-    L->d_partials = dp;
-    L->d_step = ds;
+    int dev = 0;
+    ABS_HIP(hipGetDevice(&dev));
+    if (L->device != dev) return ABS_EINVAL;
+    v.chunks = L->d_chunks;
+    v.sizes = L->d_sizes;
+    v.nchunks = (unsigned)L->chunks.size();
+    v.ntensors = (int)L->sizes.size();
+    v.tile = L->tile;
+    v.total = L->total;
     return ABS_OK;
 }
 
-template <int K, int RULE>
-void launch_sync_ragged_kr(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
-                           const float *const *const *tabs, const Hyper &h, hipStream_t s)
-{
-    TabPtrs<K> T;
-    for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
-    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-    if (stream_upd(L->total, uses_s2<RULE>() ? 3 : 2))
-        hipLaunchKernelGGL((sync_update_ragged<K, true, RULE>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
-    else
-        hipLaunchKernelGGL((sync_update_ragged<K, false, RULE>), grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, pt, T, L->tile, h);
-}
-
-template <int RULE>
-void launch_sync_ragged_r(const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
-                          const float *const *const *tabs, int n, const Hyper &h, hipStream_t s)
-{
-    switch (n) {
-#define ABS_CASE(K) case K: launch_sync_ragged_kr<K, RULE>(L, xt, vt, pt, tabs, h, s); break;
-        ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
-        ABS_CASE(16)
-#undef ABS_CASE
-    default: {
-        TabPtrsAny T;
-        std::memset(&T, 0, sizeof T);
-        for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
-        hipLaunchKernelGGL(sync_update_ragged_any<RULE>, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s,
-                           L->d_chunks, L->d_sizes, xt, vt, pt, T, n, L->tile, h);
-    }
-    }
-}
-
-void launch_sync_ragged(int rule, const abs_layout *L, float *const *xt, float *const *vt, float *const *pt,
-                        const float *const *const *tabs, int n, const Hyper &h, hipStream_t s)
-{
-    switch (rule) {
-    case SGD: launch_sync_ragged_r<SGD>(L, xt, vt, pt, tabs, n, h, s); break;
-    case SGD_DC: launch_sync_ragged_r<SGD_DC>(L, xt, vt, pt, tabs, n, h, s); break;
-    case SGD_DCM: launch_sync_ragged_r<SGD_DCM>(L, xt, vt, pt, tabs, n, h, s); break;
-    default: launch_sync_ragged_r<ADAM>(L, xt, vt, pt, tabs, n, h, s); break;
-    }
-}
-
-template <int J>
-void launch_accumulate_ragged_j(const abs_layout *L, float *const *at, const void *const *const *gt,
-                                       const float *nf, int first, bool bf, bool nta, hipStream_t s)
-{
-    GradTabs<J> T;
-    for (int j = 0; j < J; ++j) {
-        T.t[j] = gt[j];
-        T.n[j] = nf[j];
-    }
-    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-    if (bf && nta) hipLaunchKernelGGL((accumulate_ragged<true, true, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
-    else if (bf) hipLaunchKernelGGL((accumulate_ragged<true, false, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
-    else if (nta) hipLaunchKernelGGL((accumulate_ragged<false, true, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
-    else hipLaunchKernelGGL((accumulate_ragged<false, false, J>), grid, block, 0, s, L->d_chunks, L->d_sizes, at, T, L->tile, first);
-}
-
 bool set_ok(const abs_tensorset *s, const abs_layout *L) { return s && s->layout == L; }
+
+// ------------------------------------------------------------------ flat
+
+// If a HIP error stops a call that needs several launches, *count has advanced by
+// the samples of the launches already enqueued.
+int accumulate_batch_flat(const Tuning &tu, float *acc, const void *const *grads, abs_dtype grad_dtype, int J,
+                          int64_t P, const int64_t *n_samples, int64_t *count, hipStream_t s)
+{
+    if (!count || !grads || !n_samples || J < 1 || P < 0 || *count < 0) return ABS_EINVAL;
+    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
+    int64_t total = *count;
+    for (int j = 0; j < J; ++j) {
+        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
+        total += n_samples[j];
+    }
+    if (P == 0) {
+        *count = total;
+        return ABS_OK;
+    }
+    if (!acc || !aligned_to(acc, 4)) return ABS_EINVAL;
+    const int64_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
+    int vec_ok = aligned_to(acc, 16);
+    for (int j = 0; j < J; ++j) {
+        if (!grads[j] || !aligned_to(grads[j], (uintptr_t)gsz)) return ABS_EINVAL;
+        if (overlap(acc, 4 * P, grads[j], gsz * P)) return ABS_EINVAL;
+        vec_ok = vec_ok && aligned_to(grads[j], grad_dtype == ABS_BF16 ? 8 : 16);
+    }
+    for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
+        const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
+        float nf[ABS_MAX_BATCH];
+        int64_t samples = 0;
+        for (int j = 0; j < jn; ++j) {
+            nf[j] = (float)n_samples[j0 + j];
+            samples += n_samples[j0 + j];
+        }
+        int rc = launch_accumulate_flat(tu, acc, grads + j0, nf, jn, grad_dtype, P, *count == 0 ? 1 : 0, vec_ok, s);
+        if (rc != ABS_OK) return rc;
+        rc = launch_status();
+        if (rc != ABS_OK) return rc;
+        *count += samples;
+    }
+    return ABS_OK;
+}
+
+// s1: momentum (SGD rules) or first moment (ADAM); s2: previous iterate (SGD_DC)
+// or second moment (ADAM), unused otherwise.
+int sync_update_flat(const Tuning &tu, int rule, float *params, float *s1, float *s2, const float *const *acc,
+                     const int64_t *counts, int K, int64_t P, Hyper h, hipStream_t s)
+{
+    if (!acc || P < 0) return ABS_EINVAL;
+    const bool has2 = rule == SGD_DC || rule == ADAM;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
+    const bool empty = rc == ABS_EMPTY;
+    if (empty && rule != SGD_DC) return ABS_EMPTY;
+    if (P == 0) return empty ? ABS_EMPTY : ABS_OK;
+    if (!params || !s1 || !aligned_to(params, 4) || !aligned_to(s1, 4)) return ABS_EINVAL;
+    if (has2 && (!s2 || !aligned_to(s2, 4))) return ABS_EINVAL;
+    const int64_t nb = 4 * P;
+    if (overlap(params, nb, s1, nb)) return ABS_EINVAL;
+    if (has2 && (overlap(s2, nb, params, nb) || overlap(s2, nb, s1, nb))) return ABS_EINVAL;
+    if (empty) {
+        // x_{t+1} = x_t: the previous-iterate buffer must still advance
+        rc = launch_copy_flat(tu, s2, params, P, s);
+        if (rc != ABS_OK) return rc;
+        rc = launch_status();
+        return rc == ABS_OK ? ABS_EMPTY : rc;
+    }
+    const float *ptrs[ABS_MAX_K];
+    bool vec = aligned_to(params, 16) && aligned_to(s1, 16) && (!has2 || aligned_to(s2, 16));
+    for (int j = 0; j < c.n; ++j) {
+        const float *p = acc[c.idx[j]];
+        if (!p || !aligned_to(p, 4)) return ABS_EINVAL;
+        // what the pass writes must not be what it reads of another vector
+        if (overlap(p, nb, params, nb) || overlap(p, nb, s1, nb) || (has2 && overlap(p, nb, s2, nb))) return ABS_EINVAL;
+        vec = vec && aligned_to(p, 16);
+        ptrs[j] = p;
+    }
+    h.M = (float)c.M;
+    rc = launch_sync_flat(tu, rule, params, s1, has2 ? s2 : nullptr, ptrs, c.n, P, h, vec ? 1 : 0, s);
+    if (rc != ABS_OK) return rc;
+    return launch_status();
+}
+
+// ---------------------------------------------------------------- ragged
+
+int accumulate_batch_mt(const Tuning &tu, const abs_layout *L, const abs_tensorset *acc,
+                        const abs_tensorset *const *grads, int J, const int64_t *n_samples, int64_t *count,
+                        hipStream_t s)
+{
+    if (!L || !set_ok(acc, L) || acc->elem != ABS_F32 || !grads || !n_samples || J < 1) return ABS_EINVAL;
+    if (!count || *count < 0) return ABS_EINVAL;
+    int64_t total = *count;
+    for (int j = 0; j < J; ++j) {
+        if (!set_ok(grads[j], L) || grads[j]->elem != grads[0]->elem || grads[j] == acc) return ABS_EINVAL;
+        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
+        total += n_samples[j];
+    }
+    if (L->chunks.empty()) {
+        *count = total;
+        return ABS_OK;
+    }
+    RaggedView V;
+    int rc = layout_view(L, V);
+    if (rc != ABS_OK) return rc;
+    float *const *at = reinterpret_cast<float *const *>(acc->d_tab);
+    for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
+        const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
+        float nf[ABS_MAX_BATCH];
+        const void *const *gt[ABS_MAX_BATCH];
+        int64_t samples = 0;
+        for (int j = 0; j < jn; ++j) {
+            nf[j] = (float)n_samples[j0 + j];
+            samples += n_samples[j0 + j];
+            gt[j] = reinterpret_cast<const void *const *>(grads[j0 + j]->d_tab);
+        }
+        rc = launch_accumulate_ragged(tu, V, at, gt, nf, jn, grads[0]->elem, *count == 0 ? 1 : 0, s);
+        if (rc != ABS_OK) return rc;
+        rc = launch_status();
+        if (rc != ABS_OK) return rc;
+        *count += samples;
+    }
+    return ABS_OK;
+}
+
+int sync_update_mt(const Tuning &tu, int rule, const abs_layout *L, const abs_tensorset *params,
+                   const abs_tensorset *s1, const abs_tensorset *s2, const abs_tensorset *const *acc,
+                   const int64_t *counts, int K, Hyper h, hipStream_t s)
+{
+    if (!L || !acc) return ABS_EINVAL;
+    const bool has2 = rule == SGD_DC || rule == ADAM;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
+    const bool empty = rc == ABS_EMPTY;
+    if (empty && rule != SGD_DC) return ABS_EMPTY;
+    if (!set_ok(params, L) || !set_ok(s1, L) || params == s1) return ABS_EINVAL;
+    if (params->elem != ABS_F32 || s1->elem != ABS_F32) return ABS_EINVAL;
+    if (has2 && (!set_ok(s2, L) || s2 == params || s2 == s1 || s2->elem != ABS_F32)) return ABS_EINVAL;
+    const float *const *tabs[ABS_MAX_K];
+    for (int j = 0; j < c.n; ++j) {
+        const abs_tensorset *a = acc[c.idx[j]];
+        if (!set_ok(a, L) || a->elem != ABS_F32 || a == params || a == s1 || (has2 && a == s2)) return ABS_EINVAL;
+        tabs[j] = reinterpret_cast<const float *const *>(a->d_tab);
+    }
+    if (L->chunks.empty()) return empty ? ABS_EMPTY : ABS_OK;
+    RaggedView V;
+    rc = layout_view(L, V);
+    if (rc != ABS_OK) return rc;
+    float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
+    float *const *pt = has2 ? reinterpret_cast<float *const *>(s2->d_tab) : nullptr;
+    if (empty) {
+        rc = launch_copy_ragged(V, pt, xt, s);
+        if (rc == ABS_OK) rc = launch_status();
+        return rc == ABS_OK ? ABS_EMPTY : rc;
+    }
+    h.M = (float)c.M;
+    rc = launch_sync_ragged(tu, rule, V, xt, reinterpret_cast<float *const *>(s1->d_tab), pt, tabs, c.n, h, s);
+    if (rc != ABS_OK) return rc;
+    return launch_status();
+}
+
+// LARS with its scratch taken from `sc`; when begin_on_device, the first-chunk table
+// is first rebuilt in sc.chunk_begin from the chunk table (one small launch).
+int sync_update_lars(const abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                     const abs_tensorset *gbar, const abs_tensorset *const *acc, const int64_t *counts, int K,
+                     float lr, float mu, float wd, float eta, const LarsScratch *sc, bool begin_on_device,
+                     hipStream_t s)
+{
+    if (!L || !acc) return ABS_EINVAL;
+    Combine c;
+    int rc = plan_combine(counts, K, c);
+    if (rc != ABS_OK) return rc;
+    if (!set_ok(params, L) || !set_ok(momentum, L) || !set_ok(gbar, L)) return ABS_EINVAL;
+    if (params == momentum || gbar == params || gbar == momentum) return ABS_EINVAL;
+    if (params->elem != ABS_F32 || momentum->elem != ABS_F32 || gbar->elem != ABS_F32) return ABS_EINVAL;
+    const float *const *tabs[ABS_MAX_K];
+    for (int j = 0; j < c.n; ++j) {
+        const abs_tensorset *a = acc[c.idx[j]];
+        if (!set_ok(a, L) || a->elem != ABS_F32 || a == gbar || a == params || a == momentum) return ABS_EINVAL;
+        tabs[j] = reinterpret_cast<const float *const *>(a->d_tab);
+    }
+    if (L->chunks.empty()) return ABS_OK;
+    RaggedView V;
+    rc = layout_view(L, V);
+    if (rc != ABS_OK) return rc;
+    LarsScratch own{L->d_partials, L->d_step, L->d_chunk_begin};
+    if (!sc) sc = &own;
+    if (begin_on_device) {
+        rc = launch_lars_chunk_begin(V, sc->chunk_begin, s);
+        if (rc == ABS_OK) rc = launch_status();
+        if (rc != ABS_OK) return rc;
+    }
+    rc = launch_lars(V, reinterpret_cast<float *const *>(params->d_tab),
+                     reinterpret_cast<float *const *>(momentum->d_tab),
+                     reinterpret_cast<float *const *>(gbar->d_tab), tabs, c.n, (float)c.M, lr, mu, wd, eta, *sc, s);
+    if (rc != ABS_OK) return rc;
+    return launch_status();
+}
+
+// ------------------------------------------------------------- job lists
+//
+// One worker's share of a step, in device terms (flat: buffers; ragged: pointer tables).
+struct Work {
+    void *acc;
+    const void *const *g;          // HOST array of J device pointers (flat) or pointer tables (ragged)
+    const int64_t *n;
+    int J;
+    int64_t *count;
+};
+
+// Launch r carries, for every job that still has gradients, its next `fold` of them;
+// at most MAX_JOBS jobs travel in one launch.  Per job the gradients are applied in
+// order with the roundings of single launches, whatever `fold` is.
+template <class Launch>
+int run_jobs(const Work *w, int nw, int fold, Launch launch)
+{
+    int maxJ = 0;
+    for (int i = 0; i < nw; ++i) maxJ = std::max(maxJ, w[i].J);
+    for (int j0 = 0; j0 < maxJ; j0 += fold) {
+        int i = 0;
+        while (i < nw) {
+            JobList list;
+            std::memset(&list, 0, sizeof list);
+            int64_t samples[MAX_JOBS];
+            int owner[MAX_JOBS];
+            int nj = 0, jmax = 0;
+            for (; i < nw && nj < MAX_JOBS; ++i) {
+                const int jn = std::min(fold, w[i].J - j0);
+                if (jn <= 0) continue;
+                Job &jb = list.job[nj];
+                jb.acc = w[i].acc;
+                jb.J = jn;
+                jb.first = *w[i].count == 0 ? 1 : 0;
+                samples[nj] = 0;
+                for (int j = 0; j < jn; ++j) {
+                    jb.g[j] = w[i].g[j0 + j];
+                    jb.n[j] = (float)w[i].n[j0 + j];
+                    samples[nj] += w[i].n[j0 + j];
+                }
+                owner[nj] = i;
+                jmax = std::max(jmax, jn);
+                ++nj;
+            }
+            if (nj == 0) continue;
+            int rc = launch(list, nj, jmax);
+            if (rc != ABS_OK) return rc;
+            rc = launch_status();
+            if (rc != ABS_OK) return rc;
+            for (int q = 0; q < nj; ++q) *w[owner[q]].count += samples[q];
+        }
+    }
+    return ABS_OK;
+}
+
+// Checks shared by the flat and ragged job lists; counts may not overflow.
+int check_job_counts(int J, const int64_t *n_samples, const int64_t *count)
+{
+    if (J < 0 || !count || *count < 0 || (J > 0 && !n_samples)) return ABS_EINVAL;
+    int64_t total = *count;
+    for (int j = 0; j < J; ++j) {
+        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
+        total += n_samples[j];
+    }
+    return ABS_OK;
+}
+
+int accumulate_jobs_flat(const Tuning &tu, const abs_job *jobs, int njobs, abs_dtype grad_dtype, int64_t P,
+                         int fold, hipStream_t s)
+{
+    if (!jobs || njobs < 1 || njobs > ABS_MAX_K || P < 0 || fold < 1 || fold > ABS_MAX_BATCH) return ABS_EINVAL;
+    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
+    const int64_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
+    Work w[ABS_MAX_K];
+    for (int i = 0; i < njobs; ++i) {
+        const abs_job &jb = jobs[i];
+        int rc = check_job_counts(jb.J, jb.n_samples, jb.count);
+        if (rc != ABS_OK) return rc;
+        if (jb.J > 0 && !jb.grads) return ABS_EINVAL;
+        for (int q = 0; q < i; ++q)
+            if (jobs[q].count == jb.count) return ABS_EINVAL;
+        if (P > 0 && jb.J > 0) {
+            if (!jb.acc || !aligned_to(jb.acc, 4)) return ABS_EINVAL;
+            for (int j = 0; j < jb.J; ++j)
+                if (!jb.grads[j] || !aligned_to(jb.grads[j], (uintptr_t)gsz)) return ABS_EINVAL;
+        }
+        w[i] = Work{jb.acc, jb.grads, jb.n_samples, jb.J, jb.count};
+    }
+    if (P > 0) {
+        // every accumulator is written: none may share bytes with another job's or with any gradient
+        for (int i = 0; i < njobs; ++i) {
+            if (jobs[i].J == 0) continue;
+            for (int q = 0; q < njobs; ++q) {
+                if (jobs[q].J == 0) continue;
+                if (q < i && overlap(jobs[i].acc, 4 * P, jobs[q].acc, 4 * P)) return ABS_EINVAL;
+                for (int j = 0; j < jobs[q].J; ++j)
+                    if (overlap(jobs[i].acc, 4 * P, jobs[q].grads[j], gsz * P)) return ABS_EINVAL;
+            }
+        }
+    }
+    if (P == 0) {
+        for (int i = 0; i < njobs; ++i)
+            for (int j = 0; j < jobs[i].J; ++j) *jobs[i].count += jobs[i].n_samples[j];
+        return ABS_OK;
+    }
+    return run_jobs(w, njobs, fold, [&](const JobList &list, int nj, int jmax) {
+        return launch_accumulate_jobs_flat(tu, list, nj, jmax, grad_dtype, P, s);
+    });
+}
+
+int accumulate_jobs_mt(const Tuning &tu, const abs_layout *L, const abs_job_mt *jobs, int njobs, int fold,
+                       hipStream_t s)
+{
+    if (!L || !jobs || njobs < 1 || njobs > ABS_MAX_K || fold < 1 || fold > ABS_MAX_BATCH) return ABS_EINVAL;
+    Work w[ABS_MAX_K];
+    std::vector<const void *> tabs;          // per job, its gradients' device pointer tables
+    size_t ngrads = 0;
+    for (int i = 0; i < njobs; ++i) ngrads += jobs[i].J > 0 ? (size_t)jobs[i].J : 0;
+    tabs.reserve(ngrads);
+    int elem = -1;
+    for (int i = 0; i < njobs; ++i) {
+        const abs_job_mt &jb = jobs[i];
+        int rc = check_job_counts(jb.J, jb.n_samples, jb.count);
+        if (rc != ABS_OK) return rc;
+        if (jb.J > 0 && (!jb.grads || !set_ok(jb.acc, L) || jb.acc->elem != ABS_F32)) return ABS_EINVAL;
+        for (int q = 0; q < i; ++q)
+            if (jobs[q].count == jb.count || (jb.J > 0 && jobs[q].J > 0 && jobs[q].acc == jb.acc)) return ABS_EINVAL;
+        const size_t first_tab = tabs.size();
+        for (int j = 0; j < jb.J; ++j) {
+            const abs_tensorset *g = jb.grads[j];
+            if (!set_ok(g, L)) return ABS_EINVAL;
+            if (elem < 0) elem = (int)g->elem;
+            if ((int)g->elem != elem) return ABS_EINVAL;
+            for (int q = 0; q < njobs; ++q)
+                if (jobs[q].J > 0 && jobs[q].acc == g) return ABS_EINVAL;
+            tabs.push_back(g->d_tab);
+        }
+        w[i] = Work{jb.J > 0 ? jb.acc->d_tab : nullptr, tabs.data() + first_tab, jb.n_samples, jb.J, jb.count};
+    }
+    if (L->chunks.empty() || elem < 0) {
+        for (int i = 0; i < njobs; ++i)
+            for (int j = 0; j < jobs[i].J; ++j) *jobs[i].count += jobs[i].n_samples[j];
+        return ABS_OK;
+    }
+    RaggedView V;
+    int rc = layout_view(L, V);
+    if (rc != ABS_OK) return rc;
+    return run_jobs(w, njobs, fold, [&](const JobList &list, int nj, int jmax) {
+        return launch_accumulate_jobs_ragged(tu, V, list, nj, jmax, (abs_dtype)elem, s);
+    });
+}
 
 }  // namespace
 
@@ -415,7 +612,7 @@ bool set_ok(const abs_tensorset *s, const abs_layout *L) { return s && s->layout
 // =========================================================================
 extern "C" {
 
-int abs_version(void) { return 100; }
+int abs_version(void) { return 200; }
 
 int abs_last_hip_error(void) { return g_last_hip_error; }
 
@@ -434,17 +631,17 @@ int64_t abs_row_elems(void) { return ROW; }
 
 int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile)
 {
-    if (blocks_per_cu < 0 || blocks_per_cu > 32 || max_rows_per_tile < 0) return ABS_EINVAL;
-    g_blocks_per_cu = blocks_per_cu;
-    g_max_rows = max_rows_per_tile;
+    if (!tuning_ok(blocks_per_cu, max_rows_per_tile)) return ABS_EINVAL;
+    g_blocks_per_cu.store(blocks_per_cu, std::memory_order_relaxed);
+    g_max_rows.store(max_rows_per_tile, std::memory_order_relaxed);
     return ABS_OK;
 }
 
 int abs_set_cache_policy(int accumulate_mode, int update_mode)
 {
-    if (accumulate_mode < -1 || accumulate_mode > 1 || update_mode < -1 || update_mode > 1) return ABS_EINVAL;
-    g_policy_acc = accumulate_mode;
-    g_policy_upd = update_mode;
+    if (!policy_ok(accumulate_mode, update_mode)) return ABS_EINVAL;
+    g_policy_acc.store(accumulate_mode, std::memory_order_relaxed);
+    g_policy_upd.store(update_mode, std::memory_order_relaxed);
     return ABS_OK;
 }
 
@@ -453,36 +650,8 @@ int abs_set_cache_policy(int accumulate_mode, int update_mode)
 int abs_accumulate_batch(float *acc, const void *const *grads, abs_dtype grad_dtype, int J, int64_t P,
                          const int64_t *n_samples, int64_t *count, void *stream)
 {
-    if (!count || !grads || !n_samples || J < 1 || P < 0 || *count < 0) return ABS_EINVAL;
-    if (grad_dtype != ABS_F32 && grad_dtype != ABS_BF16) return ABS_EINVAL;
-    int64_t total = *count;
-    for (int j = 0; j < J; ++j) {
-        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
-        total += n_samples[j];
-    }
-    if (P > 0) {
-        if (!acc || !aligned_to(acc, 4)) return ABS_EINVAL;
-        const uintptr_t gsz = grad_dtype == ABS_BF16 ? 2 : 4;
-        int vec_ok = aligned_to(acc, 16);
-        for (int j = 0; j < J; ++j) {
-            if (!grads[j] || !aligned_to(grads[j], gsz)) return ABS_EINVAL;
-            vec_ok = vec_ok && aligned_to(grads[j], grad_dtype == ABS_BF16 ? 8 : 16);
-        }
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        int first = *count == 0 ? 1 : 0;
-        for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
-            const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
-            float nf[ABS_MAX_BATCH];
-            for (int j = 0; j < jn; ++j) nf[j] = (float)n_samples[j0 + j];
-            int rc = launch_accumulate_flat(acc, grads + j0, nf, jn, grad_dtype, P, first, vec_ok, s);
-            if (rc != ABS_OK) return rc;
-            rc = launch_status();
-            if (rc != ABS_OK) return rc;
-            first = 0;
-        }
-    }
-    *count = total;
-    return ABS_OK;
+    return accumulate_batch_flat(process_tuning(), acc, grads, grad_dtype, J, P, n_samples, count,
+                                 static_cast<hipStream_t>(stream));
 }
 
 int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P,
@@ -492,86 +661,33 @@ int abs_accumulate(float *acc, const void *grad, abs_dtype grad_dtype, int64_t P
     return abs_accumulate_batch(acc, grads, grad_dtype, 1, P, &n_samples, count, stream);
 }
 
-// Hyper-parameters of the three rules in one struct.
-static Hyper hyper_sgd(float lr, float mu, float wd, float lambda, float lr_prev = 0.f)
+int abs_accumulate_jobs(const abs_job *jobs, int njobs, abs_dtype grad_dtype, int64_t P, int fold, void *stream)
 {
-    Hyper h = {};
-    h.lr = lr; h.mu = mu; h.wd = wd; h.lambda = lambda; h.nlr_prev = -lr_prev;
-    return h;
-}
-
-static int hyper_adam(Hyper &h, float lr, float beta1, float beta2, float eps, float wd, int64_t step)
-{
-    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return ABS_EINVAL;
-    h = Hyper{};
-    h.lr = lr; h.wd = wd; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps;
-    h.omb1 = 1.0f - beta1;
-    h.omb2 = 1.0f - beta2;
-    h.bc1 = (float)(1.0 - std::pow((double)beta1, (double)step));
-    h.bc2 = (float)(1.0 - std::pow((double)beta2, (double)step));
-    return ABS_OK;
-}
-
-// s1: momentum (SGD rules) or first moment (ADAM); s2: previous iterate (SGD_DC)
-// or second moment (ADAM), unused for SGD.
-static int sync_update_flat_impl(int rule, float *params, float *s1, float *s2, const float *const *acc,
-                                 const int64_t *counts, int K, int64_t P, Hyper h, void *stream)
-{
-    if (!acc || P < 0) return ABS_EINVAL;
-    const bool has2 = rule == SGD_DC || rule == ADAM;
-    Combine c;
-    int rc = plan_combine(counts, K, c);
-    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
-    const bool empty = rc == ABS_EMPTY;
-    if (empty && rule != SGD_DC) return ABS_EMPTY;
-    if (P == 0) return empty ? ABS_EMPTY : ABS_OK;
-    if (!params || !s1 || params == s1) return ABS_EINVAL;
-    if (!aligned_to(params, 4) || !aligned_to(s1, 4)) return ABS_EINVAL;
-    if (has2 && (!s2 || s2 == params || s2 == s1 || !aligned_to(s2, 4))) return ABS_EINVAL;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (empty) {
-        // x_{t+1} = x_t: the previous-iterate buffer must still advance
-        rc = launch_copy_flat(s2, params, P, s);
-        if (rc != ABS_OK) return rc;
-        rc = launch_status();
-        return rc == ABS_OK ? ABS_EMPTY : rc;
-    }
-    const float *ptrs[ABS_MAX_K];
-    bool vec = aligned_to(params, 16) && aligned_to(s1, 16) && (!has2 || aligned_to(s2, 16));
-    for (int j = 0; j < c.n; ++j) {
-        const float *p = acc[c.idx[j]];
-        if (!p || !aligned_to(p, 4)) return ABS_EINVAL;
-        vec = vec && aligned_to(p, 16);
-        ptrs[j] = p;
-    }
-    h.M = (float)c.M;
-    rc = launch_sync_flat(rule, params, s1, has2 ? s2 : nullptr, ptrs, c.n, P, h, vec ? 1 : 0, s);
-    if (rc != ABS_OK) return rc;
-    return launch_status();
+    return accumulate_jobs_flat(process_tuning(), jobs, njobs, grad_dtype, P, fold, static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update(float *params, float *momentum, const float *const *acc,
                     const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
                     void *stream)
 {
-    return sync_update_flat_impl(SGD, params, momentum, nullptr, acc, counts, K, P, hyper_sgd(lr, mu, wd, 0.f),
-                                 stream);
+    return sync_update_flat(process_tuning(), SGD, params, momentum, nullptr, acc, counts, K, P,
+                            hyper_sgd(lr, mu, wd, 0.f), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_dc(float *params, float *params_prev, float *momentum, const float *const *acc,
                        const int64_t *counts, int K, int64_t P, float lr, float mu, float wd,
                        float lambda, void *stream)
 {
-    return sync_update_flat_impl(SGD_DC, params, momentum, params_prev, acc, counts, K, P,
-                                 hyper_sgd(lr, mu, wd, lambda), stream);
+    return sync_update_flat(process_tuning(), SGD_DC, params, momentum, params_prev, acc, counts, K, P,
+                            hyper_sgd(lr, mu, wd, lambda), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_dcm(float *params, float *momentum, const float *const *acc, const int64_t *counts,
                         int K, int64_t P, float lr, float mu, float wd, float lambda, float lr_prev,
                         void *stream)
 {
-    return sync_update_flat_impl(SGD_DCM, params, momentum, nullptr, acc, counts, K, P,
-                                 hyper_sgd(lr, mu, wd, lambda, lr_prev), stream);
+    return sync_update_flat(process_tuning(), SGD_DCM, params, momentum, nullptr, acc, counts, K, P,
+                            hyper_sgd(lr, mu, wd, lambda, lr_prev), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const float *const *acc,
@@ -581,7 +697,8 @@ int abs_sync_update_adam(float *params, float *exp_avg, float *exp_avg_sq, const
     Hyper h;
     int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
     if (rc != ABS_OK) return rc;
-    return sync_update_flat_impl(ADAM, params, exp_avg, exp_avg_sq, acc, counts, K, P, h, stream);
+    return sync_update_flat(process_tuning(), ADAM, params, exp_avg, exp_avg_sq, acc, counts, K, P, h,
+                            static_cast<hipStream_t>(stream));
 }
 
 // ---------------------------------------------------------------- ragged
@@ -601,7 +718,8 @@ int abs_layout_create(abs_layout **out, int T, const int64_t *sizes)
         rows += rows_of(sizes[t]);
     }
     // one tile size for the whole layout, from the accumulate kernel's residency
-    const int64_t tile = choose_tile(rows, acc_resident());
+    const Tuning tu = process_tuning();
+    const int64_t tile = choose_tile(rows, acc_resident(tu), tu.max_rows);
     int64_t nchunks = 0;
     for (int t = 0; t < T; ++t) nchunks += tiles_for(sizes[t], tile);
     if (tile > kMaxTile || nchunks > kMaxGrid) { delete L; return ABS_EINVAL; }
@@ -617,14 +735,16 @@ int abs_layout_create(abs_layout **out, int T, const int64_t *sizes)
     return ABS_OK;
 }
 
+int abs_layout_upload(const abs_layout *L)
+{
+    if (!L) return ABS_EINVAL;
+    return layout_upload(L);
+}
+
 int abs_layout_destroy(abs_layout *L)
 {
     if (!L) return ABS_EINVAL;
-    if (L->d_chunks) (void)hipFree(L->d_chunks);
-    if (L->d_sizes) (void)hipFree(L->d_sizes);
-    if (L->d_chunk_begin) (void)hipFree(L->d_chunk_begin);
-    if (L->d_partials) (void)hipFree(L->d_partials);
-    if (L->d_step) (void)hipFree(L->d_step);
+    layout_free_device(L);
     delete L;
     return ABS_OK;
 }
@@ -654,6 +774,8 @@ int abs_tensorset_create(abs_tensorset **out, const abs_layout *L, void *const *
     for (size_t t = 0; t < T; ++t) {
         if (L->sizes[t] > 0 && (!ptrs[t] || !aligned_to(ptrs[t], esz))) return ABS_EINVAL;
     }
+    int rc = layout_upload(L);           // the first set over a layout puts its tables on the device
+    if (rc != ABS_OK) return rc;
     abs_tensorset *S = new (std::nothrow) abs_tensorset;
     if (!S) return ABS_EINVAL;
     S->layout = L;
@@ -681,41 +803,7 @@ int abs_tensorset_destroy(abs_tensorset *S)
 int abs_accumulate_batch_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *const *grads,
                             int J, const int64_t *n_samples, int64_t *count, void *stream)
 {
-    if (!L || !set_ok(acc, L) || acc->elem != ABS_F32 || !grads || !n_samples || J < 1) return ABS_EINVAL;
-    if (!count || *count < 0) return ABS_EINVAL;
-    int64_t total = *count;
-    for (int j = 0; j < J; ++j) {
-        if (!set_ok(grads[j], L) || grads[j]->elem != grads[0]->elem) return ABS_EINVAL;
-        if (n_samples[j] <= 0 || total > std::numeric_limits<int64_t>::max() - n_samples[j]) return ABS_EINVAL;
-        total += n_samples[j];
-    }
-    if (!L->chunks.empty()) {
-        int rc = layout_to_device(L);
-        if (rc != ABS_OK) return rc;
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        float *const *at = reinterpret_cast<float *const *>(acc->d_tab);
-        const bool bf = grads[0]->elem == ABS_BF16, nta = stream_acc(L->total);
-        int first = *count == 0 ? 1 : 0;
-        for (int j0 = 0; j0 < J; j0 += ABS_MAX_BATCH) {
-            const int jn = J - j0 < ABS_MAX_BATCH ? J - j0 : ABS_MAX_BATCH;
-            float nf[ABS_MAX_BATCH];
-            const void *const *gt[ABS_MAX_BATCH];
-            for (int j = 0; j < jn; ++j) {
-                nf[j] = (float)n_samples[j0 + j];
-                gt[j] = reinterpret_cast<const void *const *>(grads[j0 + j]->d_tab);
-            }
-            switch (jn) {
-#define ABS_CASE(N) case N: launch_accumulate_ragged_j<N>(L, at, gt, nf, first, bf, nta, s); break;
-                ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-#undef ABS_CASE
-            }
-            rc = launch_status();
-            if (rc != ABS_OK) return rc;
-            first = 0;
-        }
-    }
-    *count = total;
-    return ABS_OK;
+    return accumulate_batch_mt(process_tuning(), L, acc, grads, J, n_samples, count, static_cast<hipStream_t>(stream));
 }
 
 int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensorset *grad,
@@ -724,49 +812,17 @@ int abs_accumulate_mt(abs_layout *L, const abs_tensorset *acc, const abs_tensors
     return abs_accumulate_batch_mt(L, acc, &grad, 1, &n_samples, count, stream);
 }
 
-static int sync_update_mt_impl(int rule, abs_layout *L, const abs_tensorset *params, const abs_tensorset *s1,
-                               const abs_tensorset *s2, const abs_tensorset *const *acc,
-                               const int64_t *counts, int K, Hyper h, void *stream)
+int abs_accumulate_jobs_mt(abs_layout *L, const abs_job_mt *jobs, int njobs, int fold, void *stream)
 {
-    if (!L || !acc) return ABS_EINVAL;
-    const bool has2 = rule == SGD_DC || rule == ADAM;
-    Combine c;
-    int rc = plan_combine(counts, K, c);
-    if (rc != ABS_OK && rc != ABS_EMPTY) return rc;
-    const bool empty = rc == ABS_EMPTY;
-    if (empty && rule != SGD_DC) return ABS_EMPTY;
-    if (!set_ok(params, L) || !set_ok(s1, L) || params == s1) return ABS_EINVAL;
-    if (params->elem != ABS_F32 || s1->elem != ABS_F32) return ABS_EINVAL;
-    if (has2 && (!set_ok(s2, L) || s2 == params || s2 == s1 || s2->elem != ABS_F32)) return ABS_EINVAL;
-    const float *const *tabs[ABS_MAX_K];
-    for (int j = 0; j < c.n; ++j) {
-        const abs_tensorset *s = acc[c.idx[j]];
-        if (!set_ok(s, L) || s->elem != ABS_F32) return ABS_EINVAL;
-        tabs[j] = reinterpret_cast<const float *const *>(s->d_tab);
-    }
-    if (L->chunks.empty()) return empty ? ABS_EMPTY : ABS_OK;
-    rc = layout_to_device(L);
-    if (rc != ABS_OK) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
-    float *const *pt = has2 ? reinterpret_cast<float *const *>(s2->d_tab) : nullptr;
-    if (empty) {
-        hipLaunchKernelGGL(copy_ragged, dim3((unsigned)L->chunks.size()), dim3(BLOCK), 0, s, L->d_chunks,
-                           L->d_sizes, pt, xt, L->tile);
-        rc = launch_status();
-        return rc == ABS_OK ? ABS_EMPTY : rc;
-    }
-    h.M = (float)c.M;
-    launch_sync_ragged(rule, L, xt, reinterpret_cast<float *const *>(s1->d_tab), pt, tabs, c.n, h, s);
-    return launch_status();
+    return accumulate_jobs_mt(process_tuning(), L, jobs, njobs, fold, static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
                        const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                        float mu, float wd, void *stream)
 {
-    return sync_update_mt_impl(SGD, L, params, momentum, nullptr, acc, counts, K, hyper_sgd(lr, mu, wd, 0.f),
-                               stream);
+    return sync_update_mt(process_tuning(), SGD, L, params, momentum, nullptr, acc, counts, K,
+                          hyper_sgd(lr, mu, wd, 0.f), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *params_prev,
@@ -774,16 +830,16 @@ int abs_sync_update_dc_mt(abs_layout *L, const abs_tensorset *params, const abs_
                           const int64_t *counts, int K, float lr, float mu, float wd, float lambda,
                           void *stream)
 {
-    return sync_update_mt_impl(SGD_DC, L, params, momentum, params_prev, acc, counts, K,
-                               hyper_sgd(lr, mu, wd, lambda), stream);
+    return sync_update_mt(process_tuning(), SGD_DC, L, params, momentum, params_prev, acc, counts, K,
+                          hyper_sgd(lr, mu, wd, lambda), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_dcm_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
                            const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                            float mu, float wd, float lambda, float lr_prev, void *stream)
 {
-    return sync_update_mt_impl(SGD_DCM, L, params, momentum, nullptr, acc, counts, K,
-                               hyper_sgd(lr, mu, wd, lambda, lr_prev), stream);
+    return sync_update_mt(process_tuning(), SGD_DCM, L, params, momentum, nullptr, acc, counts, K,
+                          hyper_sgd(lr, mu, wd, lambda, lr_prev), static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_adam_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *exp_avg,
@@ -794,7 +850,8 @@ int abs_sync_update_adam_mt(abs_layout *L, const abs_tensorset *params, const ab
     Hyper h;
     int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
     if (rc != ABS_OK) return rc;
-    return sync_update_mt_impl(ADAM, L, params, exp_avg, exp_avg_sq, acc, counts, K, h, stream);
+    return sync_update_mt(process_tuning(), ADAM, L, params, exp_avg, exp_avg_sq, acc, counts, K, h,
+                          static_cast<hipStream_t>(stream));
 }
 
 int abs_sync_update_lars_mt(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
@@ -802,36 +859,8 @@ int abs_sync_update_lars_mt(abs_layout *L, const abs_tensorset *params, const ab
                             const int64_t *counts, int K, float lr, float mu, float wd, float eta,
                             void *stream)
 {
-    if (!L || !acc) return ABS_EINVAL;
-    Combine c;
-    int rc = plan_combine(counts, K, c);
-    if (rc != ABS_OK) return rc;
-    if (!set_ok(params, L) || !set_ok(momentum, L) || !set_ok(gbar, L)) return ABS_EINVAL;
-    if (params == momentum || gbar == params || gbar == momentum) return ABS_EINVAL;
-    if (params->elem != ABS_F32 || momentum->elem != ABS_F32 || gbar->elem != ABS_F32) return ABS_EINVAL;
-    TabPtrsAny tabs;
-    std::memset(&tabs, 0, sizeof tabs);
-    for (int j = 0; j < c.n; ++j) {
-        const abs_tensorset *s = acc[c.idx[j]];
-        if (!set_ok(s, L) || s->elem != ABS_F32 || s == gbar) return ABS_EINVAL;
-        tabs.t[j] = reinterpret_cast<const float *const *>(s->d_tab);
-    }
-    if (L->chunks.empty()) return ABS_OK;
-    rc = layout_to_device(L);
-    if (rc == ABS_OK) rc = layout_lars_scratch(L);
-    if (rc != ABS_OK) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    float *const *xt = reinterpret_cast<float *const *>(params->d_tab);
-    float *const *vt = reinterpret_cast<float *const *>(momentum->d_tab);
-    float *const *gt = reinterpret_cast<float *const *>(gbar->d_tab);
-    const dim3 grid((unsigned)L->chunks.size()), block(BLOCK);
-    hipLaunchKernelGGL(lars_reduce_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, gt, tabs, c.n, L->tile,
-                       (float)c.M, L->d_partials);
-    hipLaunchKernelGGL(lars_rates, dim3((unsigned)L->sizes.size()), dim3(BLOCK), 0, s, L->d_chunk_begin,
-                       L->d_partials, L->d_step, (double)lr, (double)wd, (double)eta);
-    hipLaunchKernelGGL(lars_update_ragged, grid, block, 0, s, L->d_chunks, L->d_sizes, xt, vt, gt, L->d_step,
-                       L->tile, mu, wd);
-    return launch_status();
+    return sync_update_lars(L, params, momentum, gbar, acc, counts, K, lr, mu, wd, eta, nullptr, false,
+                            static_cast<hipStream_t>(stream));
 }
 
 // --------------------------------------------------------- double buffer
@@ -872,8 +901,14 @@ int abs_ctx_create(abs_ctx **out, int K, int64_t P, float *const *acc_A, float *
 {
     if (!out || K < 1 || K > ABS_MAX_K || P < 0 || !acc_A || !acc_B) return ABS_EINVAL;
     for (int k = 0; k < K; ++k) {
-        if (P > 0 && (!acc_A[k] || !acc_B[k] || acc_A[k] == acc_B[k])) return ABS_EINVAL;
+        if (P > 0 && (!acc_A[k] || !acc_B[k])) return ABS_EINVAL;
         if (!aligned_to(acc_A[k], 4) || !aligned_to(acc_B[k], 4)) return ABS_EINVAL;
+        // the 2K accumulators are all written: no two may share bytes
+        for (int q = 0; q < K; ++q) {
+            if (overlap(acc_A[k], 4 * P, acc_B[q], 4 * P)) return ABS_EINVAL;
+            if (q < k && (overlap(acc_A[k], 4 * P, acc_A[q], 4 * P) || overlap(acc_B[k], 4 * P, acc_B[q], 4 * P)))
+                return ABS_EINVAL;
+        }
     }
     abs_ctx *C = new (std::nothrow) abs_ctx;
     if (!C) return ABS_EINVAL;
@@ -891,8 +926,12 @@ int abs_ctx_create_mt(abs_ctx **out, int K, abs_layout *L, const abs_tensorset *
 {
     if (!out || K < 1 || K > ABS_MAX_K || !L || !acc_A || !acc_B) return ABS_EINVAL;
     for (int k = 0; k < K; ++k) {
-        if (!set_ok(acc_A[k], L) || !set_ok(acc_B[k], L) || acc_A[k] == acc_B[k]) return ABS_EINVAL;
+        if (!set_ok(acc_A[k], L) || !set_ok(acc_B[k], L)) return ABS_EINVAL;
         if (acc_A[k]->elem != ABS_F32 || acc_B[k]->elem != ABS_F32) return ABS_EINVAL;
+        for (int q = 0; q < K; ++q) {
+            if (acc_A[k] == acc_B[q]) return ABS_EINVAL;
+            if (q < k && (acc_A[k] == acc_A[q] || acc_B[k] == acc_B[q])) return ABS_EINVAL;
+        }
     }
     abs_ctx *C = new (std::nothrow) abs_ctx;
     if (!C) return ABS_EINVAL;
@@ -915,30 +954,98 @@ int abs_ctx_destroy(abs_ctx *C)
     return ABS_OK;
 }
 
-int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype, int64_t n_samples)
+int abs_ctx_set_launch_tuning(abs_ctx *C, int blocks_per_cu, int max_rows_per_tile)
 {
-    if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
-    C->launches[(size_t)k] += 1;
-    return abs_accumulate(C->acc[C->cur][(size_t)k], grad, grad_dtype, C->P, n_samples,
-                          &C->counts[C->cur][(size_t)k], C->stream_of(k));
+    if (!C || !tuning_ok(blocks_per_cu, max_rows_per_tile)) return ABS_EINVAL;
+    C->own_shape = true;
+    C->blocks_per_cu = blocks_per_cu;
+    C->max_rows = max_rows_per_tile;
+    return ABS_OK;
+}
+
+int abs_ctx_set_cache_policy(abs_ctx *C, int accumulate_mode, int update_mode)
+{
+    if (!C || !policy_ok(accumulate_mode, update_mode)) return ABS_EINVAL;
+    C->own_policy = true;
+    C->policy_acc = accumulate_mode;
+    C->policy_upd = update_mode;
+    return ABS_OK;
 }
 
 int abs_ctx_accumulate_batch(abs_ctx *C, int k, const void *const *grads, abs_dtype grad_dtype, int J,
                              const int64_t *n_samples)
 {
     if (!C || C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
-    C->launches[(size_t)k] += J > 0 ? (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH : 0;
-    return abs_accumulate_batch(C->acc[C->cur][(size_t)k], grads, grad_dtype, J, C->P, n_samples,
-                                &C->counts[C->cur][(size_t)k], C->stream_of(k));
+    const int rc = accumulate_batch_flat(C->tuning(), C->acc[C->cur][(size_t)k], grads, grad_dtype, J, C->P,
+                                         n_samples, &C->counts[C->cur][(size_t)k], C->stream_of(k));
+    if (rc == ABS_OK) C->launches[(size_t)k] += (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH;
+    return rc;
+}
+
+int abs_ctx_accumulate(abs_ctx *C, int k, const void *grad, abs_dtype grad_dtype, int64_t n_samples)
+{
+    const void *grads[1] = {grad};
+    return abs_ctx_accumulate_batch(C, k, grads, grad_dtype, 1, &n_samples);
 }
 
 int abs_ctx_accumulate_batch_mt(abs_ctx *C, int k, const abs_tensorset *const *grads, int J,
                                 const int64_t *n_samples)
 {
     if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
-    C->launches[(size_t)k] += J > 0 ? (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH : 0;
-    return abs_accumulate_batch_mt(C->layout, C->set[C->cur][(size_t)k], grads, J, n_samples,
-                                   &C->counts[C->cur][(size_t)k], C->stream_of(k));
+    const int rc = accumulate_batch_mt(C->tuning(), C->layout, C->set[C->cur][(size_t)k], grads, J, n_samples,
+                                       &C->counts[C->cur][(size_t)k], C->stream_of(k));
+    if (rc == ABS_OK) C->launches[(size_t)k] += (J + ABS_MAX_BATCH - 1) / ABS_MAX_BATCH;
+    return rc;
+}
+
+int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
+{
+    return abs_ctx_accumulate_batch_mt(C, k, &grad, 1, &n_samples);
+}
+
+// Step 2 of all K workers in one call.  grads / n_samples: worker 0's m[0] entries, then
+// worker 1's m[1], ...  Runs on the context's first accumulate stream.
+static int ctx_step_checks(const abs_ctx *C, const int *m, int64_t &total)
+{
+    if (!C || !m || C->s_acc.size() != 1) return ABS_EINVAL;
+    total = 0;
+    for (int k = 0; k < C->K; ++k) {
+        if (m[k] < 0) return ABS_EINVAL;
+        total += m[k];
+    }
+    return ABS_OK;
+}
+
+int abs_ctx_accumulate_step(abs_ctx *C, const void *const *grads, const int *m, const int64_t *n_samples,
+                            abs_dtype grad_dtype, int fold)
+{
+    int64_t total = 0;
+    int rc = ctx_step_checks(C, m, total);
+    if (rc != ABS_OK || C->layout || (total > 0 && (!grads || !n_samples))) return ABS_EINVAL;
+    abs_job jobs[ABS_MAX_K];
+    int64_t at = 0;
+    for (int k = 0; k < C->K; ++k) {
+        jobs[k] = abs_job{C->acc[C->cur][(size_t)k], grads + at, n_samples + at, m[k],
+                          &C->counts[C->cur][(size_t)k]};
+        at += m[k];
+    }
+    return accumulate_jobs_flat(C->tuning(), jobs, C->K, grad_dtype, C->P, fold, C->s_acc[0]);
+}
+
+int abs_ctx_accumulate_step_mt(abs_ctx *C, const abs_tensorset *const *grads, const int *m,
+                               const int64_t *n_samples, int fold)
+{
+    int64_t total = 0;
+    int rc = ctx_step_checks(C, m, total);
+    if (rc != ABS_OK || !C->layout || (total > 0 && (!grads || !n_samples))) return ABS_EINVAL;
+    abs_job_mt jobs[ABS_MAX_K];
+    int64_t at = 0;
+    for (int k = 0; k < C->K; ++k) {
+        jobs[k] = abs_job_mt{C->set[C->cur][(size_t)k], grads + at, n_samples + at, m[k],
+                             &C->counts[C->cur][(size_t)k]};
+        at += m[k];
+    }
+    return accumulate_jobs_mt(C->tuning(), C->layout, jobs, C->K, fold, C->s_acc[0]);
 }
 
 int abs_ctx_set_accumulate_streams(abs_ctx *C, void *const *streams, int n)
@@ -958,20 +1065,12 @@ int abs_suggest_accumulate_streams(int64_t P, int K)
     return (K >= 2 && bytes >= (int64_t(24) << 20) && bytes <= (int64_t(112) << 20)) ? 2 : 1;
 }
 
-int abs_ctx_accumulate_mt(abs_ctx *C, int k, const abs_tensorset *grad, int64_t n_samples)
-{
-    if (!C || !C->layout || k < 0 || k >= C->K) return ABS_EINVAL;
-    C->launches[(size_t)k] += 1;
-    return abs_accumulate_mt(C->layout, C->set[C->cur][(size_t)k], grad, n_samples,
-                             &C->counts[C->cur][(size_t)k], C->stream_of(k));
-}
-
 int abs_ctx_sync_update(abs_ctx *C, float *params, float *momentum, float lr, float mu, float wd)
 {
     if (!C || C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    return abs_sync_update(params, momentum, C->acc[prev].data(), C->counts[prev].data(), C->K, C->P,
-                           lr, mu, wd, C->s_upd);
+    return sync_update_flat(C->tuning(), SGD, params, momentum, nullptr, C->acc[prev].data(),
+                            C->counts[prev].data(), C->K, C->P, hyper_sgd(lr, mu, wd, 0.f), C->s_upd);
 }
 
 int abs_ctx_sync_update_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *momentum,
@@ -979,8 +1078,8 @@ int abs_ctx_sync_update_mt(abs_ctx *C, const abs_tensorset *params, const abs_te
 {
     if (!C || !C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_mt(C->layout, params, momentum, C->set[prev].data(), C->counts[prev].data(),
-                              C->K, lr, mu, wd, C->s_upd);
+    return sync_update_mt(C->tuning(), SGD, C->layout, params, momentum, nullptr, C->set[prev].data(),
+                          C->counts[prev].data(), C->K, hyper_sgd(lr, mu, wd, 0.f), C->s_upd);
 }
 
 int abs_ctx_sync_update_dc(abs_ctx *C, float *params, float *params_prev, float *momentum, float lr,
@@ -988,8 +1087,8 @@ int abs_ctx_sync_update_dc(abs_ctx *C, float *params, float *params_prev, float 
 {
     if (!C || C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_dc(params, params_prev, momentum, C->acc[prev].data(), C->counts[prev].data(),
-                              C->K, C->P, lr, mu, wd, lambda, C->s_upd);
+    return sync_update_flat(C->tuning(), SGD_DC, params, momentum, params_prev, C->acc[prev].data(),
+                            C->counts[prev].data(), C->K, C->P, hyper_sgd(lr, mu, wd, lambda), C->s_upd);
 }
 
 int abs_ctx_sync_update_dc_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *params_prev,
@@ -997,8 +1096,8 @@ int abs_ctx_sync_update_dc_mt(abs_ctx *C, const abs_tensorset *params, const abs
 {
     if (!C || !C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_dc_mt(C->layout, params, params_prev, momentum, C->set[prev].data(),
-                                 C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->s_upd);
+    return sync_update_mt(C->tuning(), SGD_DC, C->layout, params, momentum, params_prev, C->set[prev].data(),
+                          C->counts[prev].data(), C->K, hyper_sgd(lr, mu, wd, lambda), C->s_upd);
 }
 
 int abs_ctx_sync_update_dcm(abs_ctx *C, float *params, float *momentum, float lr, float mu, float wd,
@@ -1006,8 +1105,9 @@ int abs_ctx_sync_update_dcm(abs_ctx *C, float *params, float *momentum, float lr
 {
     if (!C || C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    const int rc = abs_sync_update_dcm(params, momentum, C->acc[prev].data(), C->counts[prev].data(), C->K,
-                                       C->P, lr, mu, wd, lambda, C->lr_applied, C->s_upd);
+    const int rc = sync_update_flat(C->tuning(), SGD_DCM, params, momentum, nullptr, C->acc[prev].data(),
+                                    C->counts[prev].data(), C->K, C->P,
+                                    hyper_sgd(lr, mu, wd, lambda, C->lr_applied), C->s_upd);
     if (rc == ABS_OK) C->lr_applied = lr;
     else if (rc == ABS_EMPTY) C->lr_applied = 0.f;
     return rc;
@@ -1018,9 +1118,9 @@ int abs_ctx_sync_update_dcm_mt(abs_ctx *C, const abs_tensorset *params, const ab
 {
     if (!C || !C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    const int rc = abs_sync_update_dcm_mt(C->layout, params, momentum, C->set[prev].data(),
-                                          C->counts[prev].data(), C->K, lr, mu, wd, lambda, C->lr_applied,
-                                          C->s_upd);
+    const int rc = sync_update_mt(C->tuning(), SGD_DCM, C->layout, params, momentum, nullptr,
+                                  C->set[prev].data(), C->counts[prev].data(), C->K,
+                                  hyper_sgd(lr, mu, wd, lambda, C->lr_applied), C->s_upd);
     if (rc == ABS_OK) C->lr_applied = lr;
     else if (rc == ABS_EMPTY) C->lr_applied = 0.f;
     return rc;
@@ -1030,9 +1130,12 @@ int abs_ctx_sync_update_adam(abs_ctx *C, float *params, float *exp_avg, float *e
                              float beta1, float beta2, float eps, float wd, int64_t step)
 {
     if (!C || C->layout) return ABS_EINVAL;
+    Hyper h;
+    int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
+    if (rc != ABS_OK) return rc;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_adam(params, exp_avg, exp_avg_sq, C->acc[prev].data(), C->counts[prev].data(),
-                                C->K, C->P, lr, beta1, beta2, eps, wd, step, C->s_upd);
+    return sync_update_flat(C->tuning(), ADAM, params, exp_avg, exp_avg_sq, C->acc[prev].data(),
+                            C->counts[prev].data(), C->K, C->P, h, C->s_upd);
 }
 
 int abs_ctx_sync_update_adam_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *exp_avg,
@@ -1040,9 +1143,12 @@ int abs_ctx_sync_update_adam_mt(abs_ctx *C, const abs_tensorset *params, const a
                                 float eps, float wd, int64_t step)
 {
     if (!C || !C->layout) return ABS_EINVAL;
+    Hyper h;
+    int rc = hyper_adam(h, lr, beta1, beta2, eps, wd, step);
+    if (rc != ABS_OK) return rc;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_adam_mt(C->layout, params, exp_avg, exp_avg_sq, C->set[prev].data(),
-                                   C->counts[prev].data(), C->K, lr, beta1, beta2, eps, wd, step, C->s_upd);
+    return sync_update_mt(C->tuning(), ADAM, C->layout, params, exp_avg, exp_avg_sq, C->set[prev].data(),
+                          C->counts[prev].data(), C->K, h, C->s_upd);
 }
 
 int abs_ctx_sync_update_lars_mt(abs_ctx *C, const abs_tensorset *params, const abs_tensorset *momentum,
@@ -1050,8 +1156,8 @@ int abs_ctx_sync_update_lars_mt(abs_ctx *C, const abs_tensorset *params, const a
 {
     if (!C || !C->layout) return ABS_EINVAL;
     const int prev = C->cur ^ 1;
-    return abs_sync_update_lars_mt(C->layout, params, momentum, gbar, C->set[prev].data(),
-                                   C->counts[prev].data(), C->K, lr, mu, wd, eta, C->s_upd);
+    return sync_update_lars(C->layout, params, momentum, gbar, C->set[prev].data(), C->counts[prev].data(),
+                            C->K, lr, mu, wd, eta, nullptr, false, C->s_upd);
 }
 
 int abs_swap_buffers(abs_ctx *C)

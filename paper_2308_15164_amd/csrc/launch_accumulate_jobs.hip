@@ -1,0 +1,73 @@
+// Launches of the job-list accumulate kernels: one launch for several workers.
+#include "abs_kernels.hpp"
+
+#include "abs_host.hpp"
+
+using namespace absk;
+
+namespace absh {
+
+namespace {
+
+// Workgroups of `kernel` one CU can hold, from the runtime's occupancy calculator.
+template <class Kernel>
+int occupancy_per_cu(Kernel kernel, int fallback)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, BLOCK, 0) == hipSuccess && n > 0) return n;
+    (void)hipGetLastError();
+    return fallback;
+}
+
+// The tile is chosen as if the jobs were one vector of njobs * P elements, so that
+// the whole launch, not each job, is a whole number of resident rounds.
+template <bool BF16, int JMAX>
+int jobs_flat(const Tuning &tu, const JobList &jobs, int njobs, int64_t P, hipStream_t s)
+{
+    static const int per_cu = occupancy_per_cu(accumulate_jobs_flat<BF16, false, JMAX>, 4);
+    const int64_t tile64 = choose_tile(rows_of(P) * njobs, resident(tu, per_cu), tu.max_rows);
+    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
+    const dim3 grid((unsigned)tiles_for(P, tile64), (unsigned)njobs), block(BLOCK);
+    if (stream_acc(tu, P))
+        hipLaunchKernelGGL((accumulate_jobs_flat<BF16, true, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
+    else
+        hipLaunchKernelGGL((accumulate_jobs_flat<BF16, false, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
+    return ABS_OK;
+}
+
+template <bool BF16, int JMAX>
+int jobs_ragged(const Tuning &tu, const RaggedView &L, const JobList &jobs, int njobs, hipStream_t s)
+{
+    const dim3 grid(L.nchunks, (unsigned)njobs), block(BLOCK);
+    if (stream_acc(tu, L.total))
+        hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, true, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);
+    else
+        hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, false, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);
+    return ABS_OK;
+}
+
+}  // namespace
+
+int launch_accumulate_jobs_flat(const Tuning &tu, const JobList &jobs, int njobs, int jmax, abs_dtype dt,
+                                int64_t P, hipStream_t s)
+{
+    if (njobs < 1 || njobs > MAX_JOBS || jmax < 1 || jmax > ABS_MAX_BATCH) return ABS_EINVAL;
+    const bool bf = dt == ABS_BF16;
+    if (jmax == 1) return bf ? jobs_flat<true, 1>(tu, jobs, njobs, P, s) : jobs_flat<false, 1>(tu, jobs, njobs, P, s);
+    if (jmax == 2) return bf ? jobs_flat<true, 2>(tu, jobs, njobs, P, s) : jobs_flat<false, 2>(tu, jobs, njobs, P, s);
+    if (jmax <= 4) return bf ? jobs_flat<true, 4>(tu, jobs, njobs, P, s) : jobs_flat<false, 4>(tu, jobs, njobs, P, s);
+    return bf ? jobs_flat<true, 8>(tu, jobs, njobs, P, s) : jobs_flat<false, 8>(tu, jobs, njobs, P, s);
+}
+
+int launch_accumulate_jobs_ragged(const Tuning &tu, const RaggedView &L, const JobList &jobs, int njobs,
+                                  int jmax, abs_dtype dt, hipStream_t s)
+{
+    if (njobs < 1 || njobs > MAX_JOBS || jmax < 1 || jmax > ABS_MAX_BATCH) return ABS_EINVAL;
+    const bool bf = dt == ABS_BF16;
+    if (jmax == 1) return bf ? jobs_ragged<true, 1>(tu, L, jobs, njobs, s) : jobs_ragged<false, 1>(tu, L, jobs, njobs, s);
+    if (jmax == 2) return bf ? jobs_ragged<true, 2>(tu, L, jobs, njobs, s) : jobs_ragged<false, 2>(tu, L, jobs, njobs, s);
+    if (jmax <= 4) return bf ? jobs_ragged<true, 4>(tu, L, jobs, njobs, s) : jobs_ragged<false, 4>(tu, L, jobs, njobs, s);
+    return bf ? jobs_ragged<true, 8>(tu, L, jobs, njobs, s) : jobs_ragged<false, 8>(tu, L, jobs, njobs, s);
+}
+
+}  // namespace absh

@@ -31,11 +31,15 @@ class DeviceRun:
     adam         : (beta1, beta2, eps) switches the update rule to Adam;
     lars         : trust coefficient eta switches it to LARS (one layer per tensor);
     batched=True : a worker's m_k gradients of a step go in one abs_accumulate_batch
-                   call (same bits, the accumulator is read and written once).
+                   call (same bits, the accumulator is read and written once);
+    step_fold=f  : Step 2 of all K workers goes in ONE abs_ctx_accumulate_step call per
+                   iteration, a launch folding at most f gradients per worker (f = 1: one
+                   launch per round of gradients, the traffic of single calls; f = 8: the
+                   batched traffic, normally one launch).
     """
 
     def __init__(self, w, x0, pool, schedule, overlap=True, P=None, acc_streams=1, lam=None, batched=False,
-                 adam=None, lars=None, lam_from_momentum=False):
+                 adam=None, lars=None, lam_from_momentum=False, step_fold=None):
         self.w = w
         self.P = int(w.P if P is None else P)
         self.K = w.K
@@ -45,6 +49,7 @@ class DeviceRun:
         self.lam = None if lam is None else float(lam)   # delayed gradient compensation coefficient
         self.dcm = self.lam is not None and bool(lam_from_momentum)      # no x_{t-1} buffer then
         self.batched = bool(batched)                     # one accumulate launch per worker and step
+        self.step_fold = None if step_fold is None else int(step_fold)   # one accumulate call per step
         self.adam = None if adam is None else tuple(float(t) for t in adam)   # (beta1, beta2, eps)
         self.adam_step = 0                               # applied Adam updates so far
         self.lars = None if lars is None else float(lars)   # LARS trust coefficient eta (ragged layouts)
@@ -161,7 +166,14 @@ class DeviceRun:
         ctx, n, gdt = self.ctx, self.w.n, self.gdt
         applied = self.sync_update()
         calls = self.plan_step(t) if calls is None else calls
-        if not self.batched:
+        if self.step_fold is not None:
+            # plan_step lists the calls worker by worker, which is the order the step call takes
+            m = [0] * self.K
+            for k, _ in calls:
+                m[k] += 1
+            ctx.abs_accumulate_step([g for _, g in calls], m, [n] * len(calls), fold=self.step_fold,
+                                    grad_dtype=gdt)
+        elif not self.batched:
             for k, g in calls:
                 ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
         else:

@@ -17,6 +17,7 @@ def pytest_sessionstart(session):
     import shutil
     lib = os.path.join(ROOT, "paper_2308_15164_amd", "libabs_sgd.so")
     if not os.path.exists(lib) and shutil.which("hipcc"):
-        from paper_2308_15164_amd.build import build_library, build_probe
+        from paper_2308_15164_amd.build import build_library
+        from bench_probe.build import build_probe
         build_library(force=True)
         build_probe()

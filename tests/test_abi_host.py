@@ -280,3 +280,89 @@ def test_suggested_accumulate_streams_for_the_stated_configurations():
         assert absgd.abs_suggest_accumulate_streams(w.P, w.K) == n, name
     assert absgd.abs_suggest_accumulate_streams(11_689_512, 1) == 1        # one worker: nothing to spread
     assert absgd.abs_suggest_accumulate_streams(0, 4) == 1
+
+
+def test_flat_calls_reject_overlapping_buffers():
+    """A buffer a call writes may not share a byte with another buffer of the call: partial
+    overlaps are refused like exact aliases, before anything is enqueued."""
+    L = absgd.lib()
+    P = 8                                       # 32 bytes per fp32 vector, 16 per bf16 vector
+    c = ctypes.c_int64(0)
+    # the gradient starts inside the accumulator / the accumulator starts inside the gradient
+    assert L.abs_accumulate(1024, 1024 + 16, absgd.ABS_F32, P, 32, ctypes.byref(c), None) == absgd.ABS_EINVAL
+    assert L.abs_accumulate(1024 + 8, 1024, absgd.ABS_BF16, P, 32, ctypes.byref(c), None) == absgd.ABS_EINVAL
+    assert c.value == 0
+    one, cnt = (ctypes.c_void_p * 1)(4096), (ctypes.c_int64 * 1)(32)
+    sync = lambda x, v, a=one: L.abs_sync_update(x, v, a, cnt, 1, P, 0.1, 0.9, 0.0, None)
+    assert sync(1024, 1024 + 28) == absgd.ABS_EINVAL                            # v starts in x's last element
+    assert sync(1024, 2048, (ctypes.c_void_p * 1)(1024 + 16)) == absgd.ABS_EINVAL   # an accumulator inside x
+    assert sync(1024, 2048, (ctypes.c_void_p * 1)(2048 - 4)) == absgd.ABS_EINVAL    # ... reaching into v
+    assert L.abs_sync_update_dc(1024, 2048 + 4, 2048, one, cnt, 1, P, 0.1, 0.9, 0.0, 0.5, None) == absgd.ABS_EINVAL
+    assert L.abs_sync_update_adam(1024, 2048, 1024 + 20, one, cnt, 1, P, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1,
+                                  None) == absgd.ABS_EINVAL
+    # the 2K accumulators of a context are all written
+    ctx = ctypes.c_void_p()
+    A, B = (ctypes.c_void_p * 2)(1024, 2048), (ctypes.c_void_p * 2)(4096, 2048 + 16)
+    assert L.abs_ctx_create(ctypes.byref(ctx), 2, P, A, B, None, None) == absgd.ABS_EINVAL
+    A2 = (ctypes.c_void_p * 2)(1024, 1024 + 4)
+    assert L.abs_ctx_create(ctypes.byref(ctx), 2, P, A2, (ctypes.c_void_p * 2)(4096, 8192), None, None) == absgd.ABS_EINVAL
+
+
+def test_python_default_launch_tuning_is_the_librarys():
+    """abs_set_launch_tuning() without arguments restores what the library starts with (tiles of
+    at most 4 rows), not the uncapped shape."""
+    row = absgd.abs_row_elems()
+    absgd.abs_set_launch_tuning(0, 0)
+    absgd.abs_set_launch_tuning()
+    lay = absgd.Layout([row * 2048 * 7 + 3])
+    assert lay.tile() == 4 * row
+    lay.close()
+
+
+def test_job_list_host_side_without_a_gpu():
+    """P = 0 launches nothing: the job list's counts, its argument checks, and the one-call Step 2
+    of a context run anywhere."""
+    L = absgd.lib()
+    counts = [absgd.Count(0), absgd.Count(32), absgd.Count(0)]
+    ns = [[32, 32], [], [8, 16, 24]]
+    assert absgd.abs_accumulate_jobs([0, 0, 0], [[0, 0], [], [0, 0, 0]], ns, counts, fold=2, P=0,
+                                     grad_dtype=absgd.ABS_F32, stream=0) is True
+    assert [c.value for c in counts] == [64, 32, 48]
+    for bad_fold in (0, 9):
+        with pytest.raises(absgd.AbsError):
+            absgd.abs_accumulate_jobs([0], [[0]], [[32]], [absgd.Count(0)], fold=bad_fold, P=0,
+                                      grad_dtype=absgd.ABS_F32, stream=0)
+    with pytest.raises(absgd.AbsError):                       # a batch has samples
+        absgd.abs_accumulate_jobs([0], [[0]], [[0]], [absgd.Count(0)], P=0, grad_dtype=absgd.ABS_F32, stream=0)
+    shared = absgd.Count(0)
+    with pytest.raises(absgd.AbsError):                       # two jobs, one count
+        absgd.abs_accumulate_jobs([0, 0], [[0], [0]], [[32], [32]], [shared, shared], P=0,
+                                  grad_dtype=absgd.ABS_F32, stream=0)
+    assert shared.value == 0
+    # two jobs into one accumulator, or a gradient that is another job's accumulator: refused at P > 0
+    c2 = [absgd.Count(0), absgd.Count(0)]
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_jobs([1024, 1024 + 16], [[4096], [8192]], [[32], [32]], c2, P=8,
+                                  grad_dtype=absgd.ABS_F32, stream=0)
+    with pytest.raises(absgd.AbsError):
+        absgd.abs_accumulate_jobs([1024, 2048], [[2048 + 4], [8192]], [[32], [32]], c2, P=8,
+                                  grad_dtype=absgd.ABS_F32, stream=0)
+    assert [c.value for c in c2] == [0, 0]
+    assert L.abs_accumulate_jobs(None, 1, absgd.ABS_F32, 0, 8, None) == absgd.ABS_EINVAL
+    # the context's one-call Step 2
+    ctx = absgd.Context([0, 0, 0], [0, 0, 0], 0, 0, P=0)
+    assert ctx.abs_accumulate_step([0] * 5, [2, 0, 3], [32] * 5, fold=1, grad_dtype=absgd.ABS_F32) is True
+    assert ctx.counts(0) == [64, 0, 96]
+    assert ctx.abs_accumulate_step([0], [0, 1, 0], [7], fold=8, grad_dtype=absgd.ABS_BF16) is True
+    assert ctx.counts(0) == [64, 7, 96]
+    with pytest.raises(absgd.AbsError):
+        ctx.abs_accumulate_step([0], [0, -1, 0], [7], grad_dtype=absgd.ABS_F32)
+    assert absgd.abs_swap_buffers(ctx) is True
+    assert ctx.counts(1) == [64, 7, 96] and ctx.counts(0) == [0, 0, 0]
+    # settings of its own: same argument checks as the process-wide calls
+    assert ctx.abs_set_cache_policy(1, 0) is True and ctx.abs_set_launch_tuning(2, 3) is True
+    with pytest.raises(absgd.AbsError):
+        ctx.abs_set_cache_policy(2, 0)
+    with pytest.raises(absgd.AbsError):
+        ctx.abs_set_launch_tuning(0, -1)
+    ctx.close()

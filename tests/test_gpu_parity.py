@@ -228,6 +228,107 @@ def test_accumulate_batch_rejects_bad_arguments(absgd):
 
 
 # ---------------------------------------------------------------------------
+# abs_accumulate_jobs: Step 2 of several workers in one launch == each worker's
+# gradients taken one by one by the oracle, bit for bit
+# ---------------------------------------------------------------------------
+
+def _jobs_case(absgd, P, Js, dtype, fold, seed, start_counts=None, shift=0):
+    """Js[w] gradients for worker w; start_counts[w] > 0 continues an accumulator."""
+    rng = np.random.default_rng(seed)
+    W = len(Js)
+    start_counts = [0] * W if start_counts is None else start_counts
+    grads = [[_grad(rng, P, dtype) for _ in range(J)] for J in Js]
+    ns = [[int(v) for v in rng.integers(1, 200, size=J)] for J in Js]
+    bases = [rng.standard_normal(P).astype(F32) for _ in range(W)]
+
+    def up(a):
+        if not shift:
+            return _up(a)
+        pad = np.zeros(P + 8, dtype=a.dtype)
+        pad[shift:shift + P] = a
+        return _up(pad.view(np.int16) if a.dtype == np.uint16 else pad)[shift:shift + P]
+
+    accs = [up(bases[w]) if start_counts[w] else up(np.full(P, np.nan, dtype=F32)) for w in range(W)]
+    g_d = [[up(g) for g in gs] for gs in grads]
+    counts = [absgd.Count(c) for c in start_counts]
+    absgd.abs_accumulate_jobs(accs, g_d, ns, counts, fold=fold, P=P,
+                              grad_dtype=absgd.ABS_BF16 if dtype == "bf16" else absgd.ABS_F32)
+    for w in range(W):
+        G32 = bases[w].copy() if start_counts[w] else np.zeros(P, dtype=F32)
+        G64 = G32.astype(np.float64)
+        M = start_counts[w]
+        for g, n in zip(grads[w], ns[w]):
+            orc.accumulate32(G32, g, n, first=(M == 0))
+            orc.accumulate(G64, g, n)
+            M += n
+        assert counts[w].value == M, f"job {w}: count"
+        got = accs[w].cpu().numpy()
+        if Js[w] == 0 and not start_counts[w]:
+            assert np.all(np.isnan(got)), f"job {w}: an idle worker's buffer was touched"
+            continue
+        _assert_bitexact(got, G32, f"job {w} (J={Js[w]}, fold={fold}) vs fp32 oracle")
+        assert np.max(np.abs(got - G64)) <= RTOL * max(np.max(np.abs(G64)), 1e-30)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fold", [1, 2, 3, 8])
+def test_accumulate_jobs_matches_oracle(absgd, dtype, fold):
+    print(f"[case] accumulate_jobs dtype={dtype} fold={fold}", flush=True)
+    # adaptive batch sizes: every worker brings another number of gradients, one sits out,
+    # one continues an accumulator that already holds samples
+    _jobs_case(absgd, 5 * 4096 + 1031, [2, 2, 4, 8, 0, 1, 11], dtype, fold, seed=2000 + fold,
+               start_counts=[0, 64, 0, 0, 0, 32, 0])
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 7, 1023, 4096, 4097, 100_003])
+def test_accumulate_jobs_sizes(absgd, P):
+    print(f"[case] accumulate_jobs P={P}", flush=True)
+    _jobs_case(absgd, P, [3, 1, 5], "f32", 2, seed=2100 + P)
+    _jobs_case(absgd, P, [1, 6], "bf16", 8, seed=2200 + P)
+
+
+def test_accumulate_jobs_more_jobs_than_one_launch_carries(absgd):
+    print("[case] accumulate_jobs 37 workers", flush=True)
+    Js = [1 + (w * 7) % 9 for w in range(37)]                  # 1..9: some need two launches at fold 8
+    _jobs_case(absgd, 3 * 4096 + 5, Js, "bf16", 8, seed=2300)
+    _jobs_case(absgd, 3 * 4096 + 5, Js, "f32", 1, seed=2301)
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_accumulate_jobs_unaligned_views(absgd, shift):
+    print(f"[case] accumulate_jobs unaligned shift={shift}", flush=True)
+    _jobs_case(absgd, 2 * 4096 + 77, [2, 5, 1], "f32", 4, seed=2400 + shift, shift=shift)
+    _jobs_case(absgd, 2 * 4096 + 77, [2, 5, 1], "bf16", 4, seed=2410 + shift, shift=shift)
+
+
+@pytest.mark.parametrize("tuned", TUNINGS, indirect=True)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_accumulate_jobs_multi_row_tiles(absgd, tuned, dtype):
+    print(f"[case] accumulate_jobs multi-row dtype={dtype} tuning={tuned}", flush=True)
+    _jobs_case(absgd, 1_048_576 + 13, [1, 3, 8], dtype, 8, seed=2500)
+    _jobs_case(absgd, 700_001, [2, 2], dtype, 1, seed=2501)
+
+
+@pytest.mark.parametrize("policy", [(0, 0), (1, 1)], indirect=True)
+def test_accumulate_jobs_cache_flavours(absgd, policy):
+    print(f"[case] accumulate_jobs policy={policy}", flush=True)
+    _jobs_case(absgd, 3 * 4096 + 9, [4, 1, 2], "f32", 2, seed=2600)
+    _jobs_case(absgd, 3 * 4096 + 9, [4, 1, 2], "bf16", 8, seed=2601)
+
+
+def test_accumulate_jobs_rejects_shared_buffers(absgd):
+    acc = torch.zeros(64, device="cuda")
+    g = torch.zeros(64, device="cuda")
+    c = [absgd.Count(0), absgd.Count(0)]
+    with pytest.raises(absgd.AbsError):                       # two jobs into overlapping accumulators
+        absgd.abs_accumulate_jobs([acc[:32], acc[16:48]], [[g[:32]], [g[32:]]], [[32], [32]], c, P=32)
+    with pytest.raises(absgd.AbsError):                       # a gradient that is another job's accumulator
+        absgd.abs_accumulate_jobs([acc[:32], acc[32:]], [[g[:32]], [acc[:32]]], [[32], [32]], c, P=32)
+    assert [x.value for x in c] == [0, 0]
+    assert torch.count_nonzero(acc).item() == 0
+
+
+# ---------------------------------------------------------------------------
 # abs_sync_update, call by call
 # ---------------------------------------------------------------------------
 
@@ -686,6 +787,24 @@ def _ragged_case(absgd, sizes, counts, seed, dtype="f32", misalign=False):
         orc.accumulate32(want, g, n, first=False)
     _assert_bitexact(cat(acc_t), want, "accumulate_mt + accumulate_batch_mt")
 
+    # Step 2 of several workers as one job list: a fresh accumulator, a worker that sits the
+    # call out, and the accumulator from above carried on; at most two gradients per launch
+    acc2_t, idle_t = split(np.full(P, np.nan, dtype=F32)), split(np.full(P, np.nan, dtype=F32))
+    aset2, iset = absgd.TensorSet(lay, acc2_t), absgd.TensorSet(lay, idle_t)
+    c2, ci = absgd.Count(0), absgd.Count(0)
+    absgd.abs_accumulate_jobs_mt(lay, [aset2, iset, aset], [[gsets[0], gsets[1], gsets[2]], [], [gsets[3], gsets[0]]],
+                                 [[32, 8, 16], [], [64, 32]], [c2, ci, cnt], fold=2)
+    assert (c2.value, ci.value, cnt.value) == (56, 0, 240)
+    want2 = np.zeros(P, dtype=F32)
+    for j, (g, n) in enumerate(((grads[0], 32), (grads[1], 8), (grads[2], 16))):
+        orc.accumulate32(want2, g, n, first=(j == 0))
+    for g, n in ((grads[3], 64), (grads[0], 32)):
+        orc.accumulate32(want, g, n, first=False)
+    _assert_bitexact(cat(acc2_t), want2, "accumulate_jobs_mt, fresh accumulator")
+    _assert_bitexact(cat(acc_t), want, "accumulate_jobs_mt, accumulator carried on")
+    if P:
+        assert np.all(np.isnan(cat(idle_t))), "accumulate_jobs_mt touched an idle worker's buffers"
+
     # Step 1 + update, every rule
     x0 = (rng.standard_normal(P) * 0.05).astype(F32)
     v0 = (rng.standard_normal(P) * 0.3).astype(F32)
@@ -895,8 +1014,17 @@ def test_trajectory_lars(absgd, name):
                           lars=(list(w.tensor_sizes), f(eta)))
     assert res[1][2] == h
     gx, gv = res[1][:2]
-    assert np.max(np.abs(gx - x64)) <= RTOL * np.max(np.abs(x64))
-    assert np.max(np.abs(gv - v64)) <= RTOL * np.max(np.abs(v64))
+    # norm-wise and element by element, each element against the magnitude of the operands that
+    # formed it over the run (v: its own size plus one typical step of its layer; x: where it
+    # started and what was subtracted from it)
+    off = wl.tensor_offsets(w.tensor_sizes)
+    rms = np.concatenate([np.full(off[t + 1] - off[t], np.sqrt(np.mean(x64[off[t]:off[t + 1]] ** 2)))
+                          for t in range(len(w.tensor_sizes))])
+    typical_step = w.lr * eta * rms                    # lr * rate_l * |g| is of this size in layer l
+    scale_v = np.abs(v64) + typical_step
+    scale_x = np.abs(x0.astype(np.float64)) + np.abs(x64) + steps * scale_v
+    _assert_close64(gx, x64, scale_x, f"{name} lars x vs double oracle")
+    _assert_close64(gv, v64, scale_v, f"{name} lars v vs double oracle")
     assert np.max(np.abs(x64 - x0)) > 1e-5                                                # it moved
 
 
@@ -915,7 +1043,8 @@ def _oracle_trajectory(w, x0, pool, sched, steps, precision, R=None, lam=None, l
                    lam_from_momentum=lam_from_momentum)
 
 
-def _trajectory_case(absgd, name, steps=None, P=None, lam=None, batched=False, lam_from_momentum=False):
+def _trajectory_case(absgd, name, steps=None, P=None, lam=None, batched=False, lam_from_momentum=False,
+                     step_fold=None):
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
     steps = w.steps if steps is None else steps
@@ -927,7 +1056,7 @@ def _trajectory_case(absgd, name, steps=None, P=None, lam=None, batched=False, l
     for overlap in (False, True):
         print(f"[case] trajectory {name} overlap={overlap}", flush=True)
         run = DeviceRun(w, x0, pool, sched, overlap=overlap, P=size, lam=lam, batched=batched,
-                        lam_from_momentum=lam_from_momentum)
+                        lam_from_momentum=lam_from_momentum, step_fold=step_fold)
         run.run(steps)
         out[overlap] = run.read_state() + (run.count_history, run.applied)
         run.close()
@@ -1000,6 +1129,15 @@ def test_trajectory_batched_accumulate(absgd, name, kw):
     _trajectory_case(absgd, name, batched=True, **kw)
 
 
+@pytest.mark.parametrize("fold", [1, 3, 8])
+@pytest.mark.parametrize("name,kw", [("paper_static", dict(steps=6, P=300_007)), ("cfg1_small", {}),
+                                     ("tiny_tail_bf16", {}), ("ragged_odd_f32", {}), ("ragged_odd_bf16", dict(lam=0.5))])
+def test_trajectory_one_accumulate_call_per_step(absgd, name, kw, fold):
+    """Step 2 of all K workers in one abs_ctx_accumulate_step call per iteration (a job list);
+    the oracle still takes every worker's gradients one by one."""
+    _trajectory_case(absgd, name, step_fold=fold, **kw)
+
+
 @pytest.mark.parametrize("name,kw", [("paper_static", dict(steps=6, P=300_007)), ("cfg1_small", {}),
                                      ("tiny_tail_bf16", {}), ("ragged_odd_f32", {}), ("ragged_odd_bf16", {})])
 def test_trajectory_with_compensation(absgd, name, kw):
@@ -1039,49 +1177,68 @@ def test_trajectory_delay_invariant_on_gpu(absgd):
 # the full stated sizes in the benchmark's launch configuration, sampled outputs
 # ---------------------------------------------------------------------------
 
+# every element where the oracle needs only seconds for the whole vector; a sample elsewhere
+FULL_VECTOR = ("cfg2_resnet18", "cfg3_resnet50_bf16")
+
+
 @pytest.mark.parametrize("name,lam,batched", [("cfg2_resnet18", None, False), ("cfg3_resnet50_bf16", None, False),
                                               ("cfg4_vgg16", None, False), ("cfg5_gpt2_ragged_bf16", None, False),
                                               ("cfg2_resnet18", 0.5, False), ("cfg5_gpt2_ragged_bf16", 0.5, False),
                                               ("cfg2_resnet18", None, True), ("cfg3_resnet50_bf16", None, True),
                                               ("cfg5_gpt2_ragged_bf16", None, True),
                                               ("cfg2_resnet18", "0.5 from momentum", False),
-                                              ("cfg5_gpt2_ragged_bf16", "0.5 from momentum", True)])
-def test_full_size_sampled(absgd, name, lam, batched):
-    """Every output element depends only on the same index of the inputs, so the
-    oracle runs on a sample of indices gathered from the very same host arrays."""
+                                              ("cfg5_gpt2_ragged_bf16", "0.5 from momentum", True),
+                                              ("cfg2_resnet18", None, "step 8"), ("cfg3_resnet50_bf16", None, "step 1"),
+                                              ("cfg4_vgg16", None, "step 8"), ("cfg4_vgg16", None, "step 1"),
+                                              ("cfg5_gpt2_ragged_bf16", None, "step 8")])
+def test_full_size(absgd, name, lam, batched):
+    """The stated configurations at full size, in the launch configuration the benchmark times.
+    cfg 2 and cfg 3: every element against the oracle.  cfg 4 and cfg 5: every output element
+    depends only on the same index of the inputs, so the oracle runs on a sample of indices
+    gathered from the very same host arrays.  batched "step f": one abs_ctx_accumulate_step call
+    per iteration folding at most f gradients per worker and launch."""
     from paper_2308_15164_amd.driver import DeviceRun
     w = wl.WORKLOADS[name]
     dcm = isinstance(lam, str)                   # compensation with x_t - x_{t-1} taken from the momentum
     lam = float(lam.split()[0]) if dcm else lam
+    fold = int(batched.split()[1]) if isinstance(batched, str) else None
     print(f"[case] full size {name}: generating inputs", flush=True)
     x0 = wl.initial_params(w)
     R = 4
     pool = wl.gradient_pool(w, pool=R)
     sched = wl.schedule(w)
-    # the stream plan bench.py finds fastest for this workload (and reports `value` for)
-    overlap, n_acc = {"cfg2_resnet18": (True, 2), "cfg3_resnet50_bf16": (True, 2)}.get(name, (False, 1))
-    print(f"[case] full size {name}: device run, overlap={overlap}, {n_acc} accumulate stream(s)", flush=True)
-    run = DeviceRun(w, x0, pool, sched, overlap=overlap, acc_streams=n_acc, lam=lam, batched=batched,
-                    lam_from_momentum=dcm)
+    # the stream plan bench.py times for this workload: the step call runs on one stream; separate
+    # calls on what abs_suggest_accumulate_streams names
+    n_acc = 1 if fold is not None else absgd.abs_suggest_accumulate_streams(w.P, w.K)
+    overlap = n_acc > 1
+    print(f"[case] full size {name}: device run, overlap={overlap}, {n_acc} accumulate stream(s), fold={fold}",
+          flush=True)
+    run = DeviceRun(w, x0, pool, sched, overlap=overlap, acc_streams=n_acc, lam=lam,
+                    batched=batched is True, lam_from_momentum=dcm, step_fold=fold)
     run.run(w.steps)
-    idx = wl.sample_indices(w.P, 200_000, w.seed)
-    if w.tensor_sizes is not None:       # both sides of every tensor boundary
-        off = wl.tensor_offsets(w.tensor_sizes)
-        extra = np.concatenate([off[:-1], off[1:] - 1, np.minimum(off[:-1] + 1, w.P - 1)])
-        idx = np.unique(np.concatenate([idx, extra]))
-    gx, gv = run.read_state_at(idx)
+    if name in FULL_VECTOR:
+        idx = None
+        gx, gv = run.read_state()
+    else:
+        idx = wl.sample_indices(w.P, 200_000, w.seed)
+        if w.tensor_sizes is not None:       # both sides of every tensor boundary
+            off = wl.tensor_offsets(w.tensor_sizes)
+            extra = np.concatenate([off[:-1], off[1:] - 1, np.minimum(off[:-1] + 1, w.P - 1)])
+            idx = np.unique(np.concatenate([idx, extra]))
+        gx, gv = run.read_state_at(idx)
     counts = run.count_history
     run.close()
     del run
     torch.cuda.empty_cache()
-    print(f"[case] full size {name}: oracle on {idx.size} sampled elements", flush=True)
-    x0s = np.ascontiguousarray(x0[idx])
-    pools = [np.ascontiguousarray(g[idx]) for g in pool]
+    print(f"[case] full size {name}: oracle on {w.P if idx is None else idx.size} elements", flush=True)
+    x0s = x0 if idx is None else np.ascontiguousarray(x0[idx])
+    pools = pool if idx is None else [np.ascontiguousarray(g[idx]) for g in pool]
     x32, v32, h32 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f32", R, lam=lam, lam_from_momentum=dcm)
+    _assert_bitexact(gx, x32, f"{name} x vs fp32 oracle")
+    _assert_bitexact(gv, v32, f"{name} v vs fp32 oracle")
+    del x32, v32
     x64, v64, h64 = _oracle_trajectory(w, x0s, pools, sched, w.steps, "f64", R, lam=lam)   # Algorithm 1 as printed
     assert counts == h32 == h64
-    _assert_bitexact(gx, x32, f"{name} sampled x")
-    _assert_bitexact(gv, v32, f"{name} sampled v")
     scale_x = np.abs(x0s.astype(np.float64)) + np.abs(x64) + w.lr * np.abs(v64) * w.steps
     scale_v = np.abs(v64) + 10 * w.sigma_g
     nx = _assert_close64(gx, x64, scale_x, f"{name} x vs double oracle")
