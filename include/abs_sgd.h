@@ -365,6 +365,32 @@ int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
                             const abs_tensorset *const *acc, const int64_t *counts, int K, float lr,
                             float mu, float wd, float eta, void *stream);
 
+/* For callers that cannot allocate -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: abs_sync_update_lars_mt with its scratch
+ * (per-chunk sums of squares, per-tensor step factors, the first-chunk table, which
+ * the kernels rebuild from the chunk table) in a fixed device array inside the
+ * library instead of memory owned by the layout.  The array is about 1.03 MiB; every
+ * GPU the library runs on holds its own copy until the process ends.  The call never
+ * allocates or frees, on the host side of the runtime or through it, and does not
+ * wait for the device; the first call on a device looks the array's address up once.
+ *
+ *   Limits: abs_layout_num_chunks(layout) <= ABS_NOALLOC_MAX_CHUNKS and
+ *   abs_layout_num_tensors(layout) <= ABS_NOALLOC_MAX_TENSORS, else ABS_EINVAL with
+ *   nothing enqueued.  The layout must already be on the device (it is once a tensor
+ *   set exists over it); ABS_EINVAL otherwise.
+ *   All calls on one GPU, whatever their layout or context, share the one array,
+ *   which keeps the last call's contents: calls that overlap in time on one GPU
+ *   race; order them on one stream or with events.  Nothing in it needs clearing:
+ *   a call writes every entry before it reads it.
+ *   Arguments, arithmetic, results (bit for bit), ABS_EMPTY and the other errors:
+ *   as abs_sync_update_lars_mt. */
+#define ABS_NOALLOC_MAX_CHUNKS 65536
+#define ABS_NOALLOC_MAX_TENSORS 4096
+int abs_sync_update_lars_mt_noalloc(abs_layout *layout, const abs_tensorset *params,
+                                    const abs_tensorset *momentum, const abs_tensorset *gbar,
+                                    const abs_tensorset *const *acc, const int64_t *counts, int K,
+                                    float lr, float mu, float wd, float eta, void *stream);
+
 /* ------------------------------------------------------------------------
  * (4) Double buffer -- Algorithm 1, the line that runs Step 1 and Step 2 side
  *     by side: two generations of (K accumulators, K counts).  Accumulation of batch t runs

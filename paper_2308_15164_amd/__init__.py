@@ -61,6 +61,7 @@ SYMBOLS = {
     "abs_sync_update_dc_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_sync_update_adam_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _f, _i64, _vp]),
     "abs_sync_update_lars_mt": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
+    "abs_sync_update_lars_mt_noalloc": (_int, [_vp, _vp, _vp, _vp, _pvp, _pi64, _int, _f, _f, _f, _f, _vp]),
     "abs_ctx_create": (_int, [_pvp, _int, _i64, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_create_mt": (_int, [_pvp, _int, _vp, _pvp, _pvp, _vp, _vp]),
     "abs_ctx_destroy": (_int, [_vp]),
@@ -426,6 +427,15 @@ def abs_sync_update_lars_mt(layout, params, momentum, gbar, acc, counts, lr, mu,
     return _check("abs_sync_update_lars_mt", rc, allow_empty=True)
 
 
+def abs_sync_update_lars_mt_noalloc(layout, params, momentum, gbar, acc, counts, lr, mu, wd, eta, stream=None):
+    """abs_sync_update_lars_mt with its scratch in the library's fixed device array (no allocation)."""
+    sets = _ptr_array([a.handle.value for a in acc])
+    rc = lib().abs_sync_update_lars_mt_noalloc(layout.handle, params.handle, momentum.handle, gbar.handle, sets,
+                                               _i64_array(counts), len(acc), float(lr), float(mu), float(wd),
+                                               float(eta), _stream_handle(stream))
+    return _check("abs_sync_update_lars_mt_noalloc", rc, allow_empty=True)
+
+
 class Context:
     """abs_ctx: the double buffer.  acc_A / acc_B are K tensors each (flat form)
     or K TensorSets each over `layout` (ragged form)."""
@@ -565,7 +575,7 @@ def abs_swap_buffers(ctx):
 
 
 __all__ = ["abs_swap_buffers", "abs_set_cache_policy", "abs_suggest_accumulate_streams", "lib", "AbsError", "Count", "Layout", "TensorSet", "Context", "abs_accumulate",
-           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_accumulate_jobs", "abs_accumulate_jobs_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_accumulate_mt", "abs_sync_update_mt",
+           "abs_accumulate_batch", "abs_accumulate_batch_mt", "abs_accumulate_jobs", "abs_accumulate_jobs_mt", "abs_sync_update", "abs_sync_update_dc", "abs_sync_update_dcm", "abs_sync_update_dcm_mt", "abs_sync_update_adam", "abs_sync_update_adam_mt", "abs_sync_update_lars_mt", "abs_sync_update_lars_mt_noalloc", "abs_accumulate_mt", "abs_sync_update_mt",
            "abs_sync_update_dc_mt", "abs_version",
            "abs_row_elems", "abs_set_launch_tuning", "ABS_OK", "ABS_EMPTY", "ABS_EINVAL", "ABS_EHIP", "ABS_F32",
            "ABS_BF16", "ABS_MAX_K", "SYMBOLS", "LIB_PATH"]

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -453,6 +454,51 @@ int sync_update_lars(const abs_layout *L, const abs_tensorset *params, const abs
     return launch_status();
 }
 
+// ------------------------------------------------- allocation-free scratch
+//
+// The LARS launches need per-chunk partial sums, per-tensor step factors and the
+// first-chunk table.  abs_sync_update_lars_mt keeps them in memory the layout
+// allocated; abs_sync_update_lars_mt_noalloc, for callers that may not allocate,
+// keeps them in this fixed array instead.  Every GPU the library runs on holds its
+// own copy at its own address until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress: the address the kernels
+// get is the one that call returns for the current device.
+struct StaticScratch {
+    double partials[2 * ABS_NOALLOC_MAX_CHUNKS];
+    float step[ABS_NOALLOC_MAX_TENSORS];
+    int32_t chunk_begin[ABS_NOALLOC_MAX_TENSORS + 1];
+};
+
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on device d; null until asked
+
+// Device address of the scratch array on the current device, looked up once per device.
+int scratch_on_current_device(LarsScratch &sc)
+{
+    int dev = 0;
+    ABS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ABS_EINVAL;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            ABS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) return ABS_EINVAL;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    StaticScratch *st = static_cast<StaticScratch *>(ptr);       // device memory: only addresses are formed here
+    sc.partials = st->partials;
+    sc.step = st->step;
+    sc.chunk_begin = st->chunk_begin;
+    return ABS_OK;
+}
+
 // ------------------------------------------------------------- job lists
 //
 // One worker's share of a step, in device terms (flat: buffers; ragged: pointer tables).
@@ -860,6 +906,23 @@ int abs_sync_update_lars_mt(abs_layout *L, const abs_tensorset *params, const ab
                             void *stream)
 {
     return sync_update_lars(L, params, momentum, gbar, acc, counts, K, lr, mu, wd, eta, nullptr, false,
+                            static_cast<hipStream_t>(stream));
+}
+
+int abs_sync_update_lars_mt_noalloc(abs_layout *L, const abs_tensorset *params, const abs_tensorset *momentum,
+                                    const abs_tensorset *gbar, const abs_tensorset *const *acc,
+                                    const int64_t *counts, int K, float lr, float mu, float wd, float eta,
+                                    void *stream)
+{
+    if (!L) return ABS_EINVAL;
+    if (L->chunks.size() > (size_t)ABS_NOALLOC_MAX_CHUNKS || L->sizes.size() > (size_t)ABS_NOALLOC_MAX_TENSORS)
+        return ABS_EINVAL;                   // beyond what the fixed scratch array holds
+    LarsScratch sc;
+    int rc = scratch_on_current_device(sc);
+    if (rc != ABS_OK) return rc;
+    // every entry of the three tables that the kernels read is written earlier in this same call
+    // (first-chunk table, then per-chunk sums, then per-tensor factors): nothing needs clearing
+    return sync_update_lars(L, params, momentum, gbar, acc, counts, K, lr, mu, wd, eta, &sc, true,
                             static_cast<hipStream_t>(stream));
 }
 
