@@ -192,9 +192,13 @@ def _mix64(z: int) -> int:
 
 
 def pool_index(w: Workload, t: int, k: int, j: int, pool: Optional[int] = None) -> int:
-    """Which pool vector serves as micro-batch j of worker k in step t."""
+    """Which pool vector serves as micro-batch j of worker k in step t: a seeded start
+    per (step, worker), then consecutive pool entries, so the gradients one worker
+    takes in one step are distinct vectors as long as it takes no more than the pool
+    holds (a vector read twice by one launch would be served from cache the second
+    time, which no real sequence of micro-batch gradients offers)."""
     R = w.pool if pool is None else pool
-    return _mix64(_mix64(_mix64(_mix64(w.seed) ^ t) ^ (k << 20)) ^ (j << 40)) % R
+    return (_mix64(_mix64(_mix64(w.seed) ^ t) ^ (k << 20)) + j) % R
 
 
 def tensor_offsets(sizes):

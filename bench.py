@@ -2,16 +2,30 @@
 """Benchmark of the ABS-SGD hot path on one MI355X.
 
 A step is one iteration of Algorithm 1 as one GPU sees it: the fused
-sync-update of the delayed generation (K accumulators -> x, v) on one stream,
-sum_k m_k accumulate calls into the current generation on another, and the
-swap.  Inputs are resident in HBM before the timed region starts.
+sync-update of the delayed generation (K accumulators -> x, v), Step 2 of the
+K workers (sum_k m_k micro-batch gradients into the current generation), and
+the swap.  Inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line: whole-step throughput under the fastest stream plan, the dominant
-kernel against the HBM roofline, and the CPU oracle timed on the same box.
+Prints ONE JSON line: whole-step throughput of the headline workload, its
+dominant kernel against the HBM roofline, a table over the five stated
+configurations, and the CPU oracle timed on the same box.
+
+How Step 2 is issued (--accumulate):
+  calls   one abs_ctx_accumulate call, one launch, per micro-batch gradient: every gradient
+          is folded in as it arrives, g_b + 8 bytes per parameter each (default: the path
+          the metric's byte count describes);
+  rounds  one abs_ctx_accumulate_step call per iteration with fold = 1: one launch per
+          round of gradients (every worker that still has one contributes one), the same
+          traffic in max_k m_k launches instead of sum_k m_k;
+  step    the same call with fold = 8: a worker's gradients of the iteration are folded in
+          together (m_k g_b + 8 bytes per parameter), normally ONE launch for all workers:
+          fewer bytes and fewer launches, for callers that hold a step's gradients at once.
+Every line prices its time with the algorithmic bytes of its own mode.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -23,108 +37,99 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 METRIC = "sync-update+accumulate GB/s and % of HBM peak; params/s per step"
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs of this same command, scaled by what the same counters read
-# for a plain copy of known size (summaries under profiles/).  None = not measured.
-MEASURED_TRAFFIC = {
-    # FETCH_SIZE x 2.000 = 81.88 MB, WRITE_SIZE x 1.000 = 46.75 MB per launch (average over
-    # the 12 read-modify-write and 4 overwrite launches of a step)
-    ("cfg2_resnet18", "absk::accumulate_flat<false, *, 1>"): 128.63e6,
-    # cfg4: 923.7 MB fetched + 553.4 MB written per launch (schedule average)
-    ("cfg4_vgg16", "absk::accumulate_flat<false, *, 1>"): 1477.1e6,
-}
+STATED = ["cfg1_small", "cfg2_resnet18", "cfg3_resnet50_bf16", "cfg4_vgg16", "cfg5_gpt2_ragged_bf16"]
+# buffers of these workloads fit the 256 MiB memory-side cache wholly or in good part, so their
+# algorithmic GB/s is not an HBM rate (it can exceed the box's plain-copy rate)
+CACHE_ASSISTED = {"cfg1_small", "cfg2_resnet18", "cfg3_resnet50_bf16", "paper_static", "paper_dynamic",
+                  "paper_static_dynamic"}
+
+MAX_BATCH = 8   # ABS_MAX_BATCH: gradients one accumulate launch folds in per worker
 
 
-MAX_BATCH = 8   # ABS_MAX_BATCH: gradients one accumulate launch folds in
+def measured_traffic(workload, kernel):
+    """HBM-side bytes per launch of `kernel` in `workload`, from profiles/traffic.json (written by
+    the profile summaries from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command).
+    Returns (bytes or None, where it came from)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None, "profiles/traffic.json is absent"
+    with open(path) as fh:
+        table = json.load(fh)
+    for row in table.get("rows", []):
+        if row["workload"] == workload and row["kernel"] == kernel:
+            return row["bytes_per_launch"], {"file": "profiles/traffic.json", "summary": row.get("summary"),
+                                             "counters": table.get("counters"), "level": table.get("level")}
+    return None, f"no row for {kernel} in {workload} in profiles/traffic.json"
 
 
-def bytes_per_param(w, m_row, extra_state=False, batched=False, lars=False):
-    """Algorithmic bytes per parameter in one step with micro-batch counts m_row:
-    an accumulate reads one gradient element and reads+writes one fp32
-    accumulator element (the first call of a step only writes it); the
-    sync-update reads K accumulators and reads+writes x and v (and the previous
-    iterate when the delayed gradient compensation is on)."""
+def bytes_per_param(w, m_row, mode, extra_state=False, lars=False):
+    """Algorithmic bytes per parameter in one step with micro-batch counts m_row: (accumulate,
+    sync-update).  A launch reads each of the gradients it folds in once and reads + writes the
+    fp32 accumulator once (a worker's first launch of a step only writes it); the sync-update
+    reads K accumulators and reads + writes x and v (and a third state vector for the stored-
+    iterate compensation and for Adam)."""
     gb = 4 if w.grad_dtype == "f32" else 2
-    if batched:
-        # a worker's m gradients go in ceil(m / MAX_BATCH) launches: every gradient is read
-        # once, the accumulator is written once per launch and read by all but the first
-        acc = sum(int(m) * gb + 8 * (-(-int(m) // MAX_BATCH)) - 4 for m in m_row)
+    if mode in ("step", "batched"):
+        acc = sum(int(m) * gb + 8 * (-(-int(m) // MAX_BATCH)) - 4 for m in m_row if m > 0)
     else:
-        acc = sum(int(m) * (gb + 8) - 4 for m in m_row)
+        acc = sum(int(m) * (gb + 8) - 4 for m in m_row if m > 0)
     if lars:
         # K accumulators + x read, Gbar written; then Gbar, x, v read and x, v written
         return acc, (4 * w.K + 8) + 20
     return acc, 4 * w.K + 16 + (8 if extra_state else 0)
 
 
-def accumulate_launches(m_row, batched):
-    return sum(-(-int(m) // MAX_BATCH) if batched else int(m) for m in m_row)
-
-
-def dominant_kernel(w, batched=False):
-    """The accumulate kernel: it moves most of a step's bytes in every workload.
-    Template arguments: bf16 gradients, streaming flavour, gradients per launch."""
+def dominant_kernel(w, mode):
+    """The accumulate kernel: it moves most of a step's bytes in every workload.  Template
+    arguments: bf16 gradients, streaming flavour, (most) gradients per launch and worker."""
     bf = "true" if w.grad_dtype == "bf16" else "false"
     kind = "ragged" if w.tensor_sizes is not None else "flat"
-    return f"absk::accumulate_{kind}<{bf}, *, {'*' if batched else '1'}>"
+    if mode in ("step", "rounds"):
+        return f"absk::accumulate_jobs_{kind}<{bf}, *, {'1' if mode == 'rounds' else '*'}>"
+    return f"absk::accumulate_{kind}<{bf}, *, {'*' if mode == 'batched' else '1'}>"
 
 
-HOST_ISSUE = {}    # seconds the host needed to enqueue the last timed region's steps
-
-
-def time_steps(run, plans, t0, steps, torch, tag=None):
+def timed_region(run, plans, t0, steps, torch):
+    """EXACTLY `steps` steps between two device synchronisations.  Returns (wall seconds,
+    seconds the host needed to enqueue them)."""
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for t in range(t0, t0 + steps):
         run.step(t, plans[t])
     t_issued = time.perf_counter()
     torch.cuda.synchronize()
-    if tag is not None:
-        HOST_ISSUE[tag] = t_issued - t_start
-    return time.perf_counter() - t_start
+    return time.perf_counter() - t_start, t_issued - t_start
 
 
 def kernel_event_pass(run, plans, t0, steps, torch):
-    """Replay the timed steps with ONE HIP event pair per step around that step's
-    whole sequence of accumulate launches, recorded on the stream they run on
-    (launches on one stream run back to back, so the bracket divided by the
-    number of launches is the average launch duration; one pair per ~16
-    launches keeps the events' own cost below 1 %).  The sync-update of the
-    step runs concurrently on the other stream, as in the timed region."""
-    ctx, n, gdt = run.ctx, run.w.n, run.gdt
-    pairs, launches, sync_pairs = [], [], []
+    """Replay the timed steps on ONE stream with a HIP event pair per step around that step's
+    accumulate launches and one around its sync-update launch, recorded on the stream the
+    kernels run on.  Returns per step: accumulate bracket ms, its launches, sync-update bracket ms
+    (None for a step that applied nothing)."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    rows = []
     torch.cuda.synchronize()
     for t in range(t0, t0 + steps):
-        es = torch.cuda.Event(enable_timing=True)
+        es, e0, e1 = ev(), ev(), ev()
         es.record(run.s_acc)
         applied = run.sync_update()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
         e0.record(run.s_acc)
-        if run.batched:
-            per_worker = {}
-            for k, g in plans[t]:
-                per_worker.setdefault(k, []).append(g)
-            for k, gs in per_worker.items():
-                ctx.abs_accumulate_batch(k, gs, [n] * len(gs), grad_dtype=gdt)
-            launches.append(sum(-(-len(gs) // MAX_BATCH) for gs in per_worker.values()))
-        else:
-            for k, g in plans[t]:
-                ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
-            launches.append(len(plans[t]))
+        n_launch = run.accumulate(plans[t])
         e1.record(run.s_acc)
-        pairs.append((e0, e1))
-        if applied:
-            sync_pairs.append((es, e0))      # one stream: the sync-update sits between these two
-        ctx.abs_swap_buffers()
+        run.ctx.abs_swap_buffers()
+        rows.append((e0, e1, n_launch, (es, e0) if applied else None))
     torch.cuda.synchronize()
-    return [a.elapsed_time(b) for a, b in pairs], launches, [a.elapsed_time(b) for a, b in sync_pairs]
+    return [(a.elapsed_time(b), n, s[0].elapsed_time(s[1]) if s else None) for a, b, n, s in rows]
 
 
-def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
-    """Copy / read / write / triad (a += s*b: the accumulate's two reads and one
-    write) rates of plain streaming kernels on this machine (context for the roofline
-    fraction; not part of the method)."""
+def probe_ceilings(torch, Ks=(), nbytes=4 * 138_357_544, reps=20):
+    """Copy / read / write / triad (two reads and one write in place: the steady accumulate's
+    mix) rates of plain streaming kernels on this machine, and for each K in Ks a plain kernel with
+    the sync-update's traffic (K + 2 vectors read, two of them written in place) and the same
+    K + 2 vectors only read (what mixing a write stream into the reads costs).  Context for the
+    roofline fractions; not part of the method.  Every vector is as long as the VGG16-sized
+    parameter vector (553 MB): power-of-two sizes put all streams on the same DRAM banks at
+    the same time and read 2-5 % low."""
     import ctypes
     path = os.path.join(ROOT, "bench_probe", "libabs_probe.so")
     if not os.path.exists(path):
@@ -143,7 +148,7 @@ def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
     for name, fn, moved in (("copy", lambda: L.probe_copy(a.data_ptr(), b.data_ptr(), nbytes, st), 2 * nbytes),
                             ("read", lambda: L.probe_read(a.data_ptr(), nbytes, sink.data_ptr(), st), nbytes),
                             ("write", lambda: L.probe_write(a.data_ptr(), nbytes, 1.0, st), nbytes),
-                            ("triad", lambda: L.probe_triad(a.data_ptr(), b.data_ptr(), nbytes, 0.0, st), 3 * nbytes)):
+                            ("triad", lambda: L.probe_triad(a.data_ptr(), b.data_ptr(), nbytes, 0.5, st), 3 * nbytes)):
         for _ in range(3):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -153,22 +158,26 @@ def probe_ceilings(torch, K=None, nbytes=1 << 30, reps=20):
         e1.record()
         torch.cuda.synchronize()
         out[name + "_GBs"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    if K in (4, 8, 16):
-        # a plain kernel with the sync-update's traffic: K + 2 vectors read, two of them written
-        del a, b
-        R, nb = K + 2, 1 << 28
-        L.probe_mix.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp]
+    del a, b
+    L.probe_mix.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp]
+    L.probe_readk.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp, vp]
+    for K in sorted(set(k for k in Ks if k in (4, 8, 16))):
+        R, nb = K + 2, nbytes
         bufs = [torch.zeros(nb // 4, device="cuda") for _ in range(2 * R)]      # two sets, used in turn
         sets = [(vp * R)(*[t.data_ptr() for t in bufs[i * R:(i + 1) * R]]) for i in range(2)]
-        for i in range(4):
-            assert L.probe_mix(sets[i % 2], R, nb, st) == 0
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(reps):
-            L.probe_mix(sets[i % 2], R, nb, st)
-        e1.record()
-        torch.cuda.synchronize()
-        out[f"mix_{K}_workers_GBs"] = (R + 2) * nb * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        for name, fn, moved in ((f"mix_{K}_workers_GBs", lambda i: L.probe_mix(sets[i % 2], R, nb, st), (R + 2) * nb),
+                                (f"read_only_{K}_workers_GBs",
+                                 lambda i: L.probe_readk(sets[i % 2], R, nb, sink.data_ptr(), st), R * nb)):
+            for i in range(4):
+                assert fn(i) == 0
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            out[name] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del bufs, sets
     return out
 
 
@@ -187,7 +196,7 @@ def calibrate_copy(torch, nbytes=1 << 30, reps=10):
                       "bytes_written_per_launch": nbytes, "launches": reps}))
 
 
-def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
+def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, mode):
     """Whole steps of the workload through the oracle until budget_s of wall time is spent."""
     import numpy as np
     P, K = x0.size, w.K
@@ -210,7 +219,7 @@ def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
                 M[cur][i] += w.n
         orc.sync_update(x, v, G[prev], M[prev], w.lr, w.mu, w.wd)
         cur, prev = prev, cur
-        a, s = bytes_per_param(w, sched[t])
+        a, s = bytes_per_param(w, sched[t], mode)
         done_bytes += (a + s) * P
         # what the oracle itself moves: double accumulators (zero pass, then read + write per
         # reference batch), all K of them read by the update, x and v in double
@@ -222,44 +231,163 @@ def _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, comp=False):
     return done_bytes, done_steps, time.perf_counter() - t_start, own_bytes
 
 
-def cpu_baseline(w, x0, pool, sched, budget_s=10.0):
-    """The oracle as it stands, on the host cores, on a bounded run of the same
-    workload: whole steps at full P, about budget_s of wall time with every core the
-    box gives the process (OpenMP over the parameter index), then a few seconds on
-    one thread."""
+def cpu_baseline(w, x0, pool, sched, mode, budget_s=10.0):
+    """The oracle as it stands, on the host cores, on a bounded run of the same workload: whole
+    steps at full P, about budget_s of wall time with every core the box gives the process
+    (OpenMP over the parameter index), then a few seconds on one thread."""
     import abs_workloads as wl
     from oracle import abs_oracle as orc
 
     threads = orc.max_threads()
     P = x0.size
-    nbytes, steps, dt, own = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s)
+    nbytes, steps, dt, own = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s, mode)
     orc.set_threads(1)
-    b1, s1, dt1, _ = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s / 4)
+    b1, s1, dt1, _ = _oracle_steps(orc, wl, w, x0, pool, sched, budget_s / 4, mode)
     orc.set_threads(threads)
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{steps} whole steps of {w.name} at full P={P} (same inputs and m_k), "
                       f"{dt:.1f} s wall, OpenMP over the parameter index",
             "ms_per_step": dt / steps * 1e3, "params_per_s": P * steps / dt,
-            # `value` uses the method's algorithmic bytes (as for the GPU); this is the oracle's own traffic
+            # `value` prices the oracle's time with the same algorithmic bytes as the GPU line;
+            # this is the oracle's own traffic
             "own_bytes_GBs": own / dt / 1e9,
             "single_thread": {"value": b1 / dt1 / 1e9, "unit": "GB/s", "ms_per_step": dt1 / s1 * 1e3,
                               "sample": f"{s1} whole steps, {dt1:.1f} s wall"}}
 
 
+def stream_plans(absgd, w, mode, only=None):
+    """(name, sync-update on a stream of its own, accumulate streams) to time, and the name of
+    the plan whose time is `value`: the one the library's own rule names for this size."""
+    plans = [("one stream", False, 1), ("accumulate | sync-update", True, 1)]
+    if mode in ("calls", "batched"):
+        for n in (2, 4):
+            if n <= w.K:
+                plans.append((f"{n} accumulate streams (workers balanced over them) | sync-update", True, n))
+        n_sug = absgd.abs_suggest_accumulate_streams(w.P, w.K)
+        chosen = "one stream" if n_sug == 1 else next(p[0] for p in plans if p[2] == n_sug)
+    else:
+        chosen = "one stream"          # a step call keeps all workers on one stream; two streams cannot add bandwidth
+    if only is not None:
+        plans = [p for p in plans if p[0] in only or p[0] == chosen]
+    return plans, chosen
+
+
+_INPUTS = {}     # workload name -> (x0, gradient pool) on the host
+
+
+def measure(torch, absgd, wl, w, args, mode, K_steps, W, repeats, all_plans=True, variant=None):
+    """Everything measured for one workload and one way of issuing Step 2."""
+    from paper_2308_15164_amd.driver import DeviceRun
+    variant = variant or {}
+    total = W + K_steps
+    sched = wl.schedule(w, total)
+    if w.name not in _INPUTS:
+        _INPUTS.clear()                                          # one workload's host arrays at a time
+        # at least as many distinct gradient vectors as any worker folds in per step: no launch
+        # reads one vector twice
+        _INPUTS[w.name] = (wl.initial_params(w), wl.gradient_pool(w, pool=max(args.pool, int(sched.max()))))
+    x0, pool = _INPUTS[w.name]
+    lam = variant.get("lam")
+    dcm = lam is not None and variant.get("dcm", False)
+    adam, lars = variant.get("adam"), variant.get("lars")
+    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=lam, batched=(mode == "batched"),
+                    lam_from_momentum=dcm, adam=adam, lars=lars,
+                    step_fold={"step": MAX_BATCH, "rounds": 1}.get(mode))
+    if adam:
+        run.lr = 1e-3
+    extra = (lam is not None and not dcm) or adam is not None      # a third state vector is moved
+    calls = [run.plan_step(t) for t in range(total)]
+    plans, chosen = stream_plans(absgd, w, mode, None if all_plans else ("one stream",))
+    timings, issue = {}, {}
+    for name, overlap, n_acc in plans:
+        run.configure_streams(overlap, n_acc)
+        timed_region(run, calls, 0, max(W, 3), torch)          # warm-up; also refills the delayed generation
+        reps = [timed_region(run, calls, W, K_steps, torch) for _ in range(repeats)]
+        timings[name] = [r[0] for r in reps]
+        issue[name] = statistics.median(r[1] for r in reps)
+    med = {k: statistics.median(v) for k, v in timings.items()}
+    dt = med[chosen]
+    fastest = min(med, key=med.get)
+
+    # the kernels alone on the GPU: one stream, same steps, one event bracket per step and kernel
+    run.configure_streams(False, 1)
+    timed_region(run, calls, 0, max(W, 3), torch)
+    rows = []
+    for _ in range(repeats):
+        rows += kernel_event_pass(run, calls, W, K_steps, torch)
+    run.close()
+    del run, calls
+    torch.cuda.empty_cache()
+
+    P = w.P
+    bpp = [bytes_per_param(w, sched[t], mode, extra, lars is not None) for t in range(W, total)]
+    step_bytes = sum((a + s) * P for a, s in bpp)
+    acc_bytes = [a * P for a, _ in bpp] * repeats
+    gbs = step_bytes / dt / 1e9
+    launches = sum(n for _, n, _ in rows)
+    kern_ms = sum(ms for ms, _, _ in rows) / launches
+    kern_bytes = sum(acc_bytes) / launches
+    achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+    per_step_rate = [b / (ms * 1e-3) / 1e9 for b, (ms, _, _) in zip(acc_bytes, rows)]
+    sync_ms = [s for _, _, s in rows if s is not None]
+    sync_bytes = bpp[0][1] * P
+    sync_med = statistics.median(sync_ms)
+    sync_gbs = sync_bytes / (sync_med * 1e-3) / 1e9
+    kname = dominant_kernel(w, mode)
+    traffic, traffic_src = measured_traffic(w.name, kname)
+    res = {
+        "workload": w.name, "P": P, "K": w.K, "grad_dtype": w.grad_dtype, "accumulate": mode,
+        "value": gbs, "pct_of_8TBs": 100.0 * gbs / HBM_PEAK_GBS,
+        "ms_per_step": dt / K_steps * 1e3,
+        "ms_per_step_repeats": [t / K_steps * 1e3 for t in timings[chosen]],
+        "params_per_s": P * K_steps / dt,
+        "algorithmic_bytes_per_step": step_bytes // K_steps,
+        "plan": chosen,
+        "ms_per_step_by_stream_plan": {k: v / K_steps * 1e3 for k, v in med.items()},
+        "fastest_plan": {"name": fastest, "faster_than_chosen_by": med[chosen] / med[fastest] - 1.0},
+        "overlap_speedup": med["one stream"] / min(v for k, v in med.items() if k != "one stream")
+        if len(med) > 1 else None,
+        "host_issue_ms_per_step": issue[chosen] / K_steps * 1e3,
+        "cache_assisted": w.name in CACHE_ASSISTED,
+        "accumulate_kernel": {
+            "kernel": kname, "achieved": achieved, "frac": achieved / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms,
+            "launches_timed": launches, "launches_per_step": launches / len(rows),
+            "median_step_rate": statistics.median(per_step_rate),
+            "min_step_rate": min(per_step_rate), "max_step_rate": max(per_step_rate),
+            "traffic": traffic, "traffic_source": traffic_src,
+        },
+        "sync_update_kernel": {
+            "achieved": sync_gbs, "frac": sync_gbs / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": sync_bytes, "median_launch_ms": sync_med,
+            "min_launch_ms": min(sync_ms), "max_launch_ms": max(sync_ms), "launches_timed": len(sync_ms),
+        },
+    }
+    return res, (x0, pool, sched)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2_resnet18")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--repeats", type=int, default=5, help="timed regions of --steps steps; the median is reported")
+    ap.add_argument("--workload", default="cfg4_vgg16")
+    ap.add_argument("--accumulate", default="calls", choices=["step", "rounds", "calls", "batched"],
+                    help="how Step 2 is issued (see the module docstring); batched = one "
+                         "abs_ctx_accumulate_batch call per worker")
     ap.add_argument("--pool", type=int, default=8, help="distinct gradient vectors resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-table", action="store_true", help="skip the table over the five stated configurations")
+    ap.add_argument("--no-variants", action="store_true", help="skip the other ways of issuing Step 2")
+    ap.add_argument("--only-chosen-plan", action="store_true",
+                    help="time only the stream plan `value` comes from (with one stream, every kernel of the "
+                         "command then runs alone on the GPU: what a profiler run wants)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the plain streaming kernels (box_ceilings)")
     ap.add_argument("--cache-policy", default="-1,-1",
                     help="accumulate,update: -1 auto, 0 cached, 1 streaming (see abs_set_cache_policy)")
     ap.add_argument("--launch-tuning", default=None,
                     help="blocks_per_cu,max_rows_per_tile (see abs_set_launch_tuning); default: the library's")
-    ap.add_argument("--acc-streams", type=int, default=1,
-                    help="streams the K workers' accumulations are spread over")
     ap.add_argument("--compensation", type=float, default=None, metavar="LAMBDA",
                     help="also apply the delayed gradient compensation with this coefficient "
                          "(abs_sync_update_dc; +8 B/param); default: off, the four-part path of the headline metric")
@@ -272,9 +400,6 @@ def main():
     ap.add_argument("--lars", action="store_true",
                     help="LARS (trust 0.001) per tensor as the update rule (abs_sync_update_lars_mt; ragged "
                          "workloads only; 4K + 28 B/param)")
-    ap.add_argument("--batched", action="store_true",
-                    help="one abs_accumulate_batch call per worker and step instead of one abs_accumulate "
-                         "per micro-batch (fewer bytes: the accumulator is read and written once)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB copy kernel (profiler counter calibration)")
     args = ap.parse_args()
@@ -286,7 +411,6 @@ def main():
     import torch
     import abs_workloads as wl
     import paper_2308_15164_amd as absgd
-    from paper_2308_15164_amd.driver import DeviceRun
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -300,84 +424,24 @@ def main():
         absgd.abs_set_launch_tuning(*[int(v) for v in args.launch_tuning.split(",")])
 
     w = wl.WORKLOADS[args.workload]
-    W, K_steps = args.warmup, args.steps
-    total = W + K_steps
-    x0 = wl.initial_params(w)
-    pool = wl.gradient_pool(w, pool=args.pool)
-    sched = wl.schedule(w, total)
+    W, K_steps, R = args.warmup, args.steps, max(1, args.repeats)
+    variant = {"lam": args.compensation, "dcm": args.compensation_from_momentum,
+               "adam": (0.9, 0.999, 1e-8) if args.adam else None, "lars": 0.001 if args.lars else None}
+    plain = args.compensation is None and not args.adam and not args.lars
+    mode = args.accumulate
 
-    # Stream plans.  The double buffer is in use in all of them; they differ in which
-    # HIP streams carry the work.  Each plan is warmed up and timed over the same K steps.
-    plans_wanted = [("one stream", False, 1), ("accumulate | sync-update", True, 1)]
-    for n in (2, 4):
-        if n <= w.K:
-            plans_wanted.append((f"{n} accumulate streams (workers balanced over them) | sync-update", True, n))
-    if args.acc_streams > 1:
-        plans_wanted = [p for p in plans_wanted if p[2] in (1, args.acc_streams)]
-    dcm = args.compensation is not None and args.compensation_from_momentum
-    run = DeviceRun(w, x0, pool, sched, overlap=False, lam=args.compensation, batched=args.batched,
-                    lam_from_momentum=dcm,
-                    adam=(0.9, 0.999, 1e-8) if args.adam else None, lars=0.001 if args.lars else None)
-    if args.adam:
-        run.lr = 1e-3
-    comp = (args.compensation is not None and not dcm) or args.adam    # a third state vector is moved
-    calls = [run.plan_step(t) for t in range(total)]
-    timings = {}
-    for name, overlap, n_acc in plans_wanted:
-        run.configure_streams(overlap, n_acc)
-        time_steps(run, calls, 0, max(W, 1), torch)        # also refills the delayed generation
-        timings[name] = time_steps(run, calls, W, K_steps, torch, tag=name)
-    # `value` comes from the plan the library's own rule names for this size
-    # (abs_suggest_accumulate_streams), not from whichever happened to win this run;
-    # the fastest one is reported beside it
-    fastest = min(timings, key=timings.get)
-    n_sug = absgd.abs_suggest_accumulate_streams(w.P, w.K)
-    best = "one stream" if n_sug == 1 else next((k for k in timings if k.startswith(f"{n_sug} accumulate streams")), None)
-    if best is None or best not in timings:
-        best = fastest
-    dt = timings[best]
-    dt_serial = timings["one stream"]
-    dt_overlap = min(v for k, v in timings.items() if k != "one stream")
-
-    # Dominant kernel (accumulate) alone on the GPU: the one-stream plan, same steps.
-    run.configure_streams(False, 1)
-    time_steps(run, calls, 0, max(W, 1), torch)
-    bracket_ms, step_launches, sync_ms = kernel_event_pass(run, calls, W, K_steps, torch)
-    run.close()
-    del run, calls
-    torch.cuda.empty_cache()
-
-    step_bytes = 0
-    for t in range(W, total):
-        a, s_ = bytes_per_param(w, sched[t], comp, args.batched, args.lars)
-        step_bytes += (a + s_) * w.P
-    gbs = step_bytes / dt / 1e9
-    # Algorithmic bytes per accumulate launch = the step's accumulate bytes
-    # (sum_k [m_k (g_b + 8) - 4] per parameter) averaged over its sum_k m_k launches.
-    # A step whose bracket is far off the others (a hiccup of the box) is left out: steps are
-    # ranked by time per launch and the slowest twentieth dropped.
-    step_acc_bytes = [bytes_per_param(w, sched[t], comp, args.batched, args.lars)[0] * w.P for t in range(W, total)]
-    order = sorted(range(K_steps), key=lambda i: bracket_ms[i] / step_launches[i])
-    keep = order[:max(1, K_steps - K_steps // 20)]
-    launches = sum(step_launches[i] for i in keep)
-    kern_ms = sum(bracket_ms[i] for i in keep) / launches
-    kern_bytes = sum(step_acc_bytes[i] for i in keep) / launches
-    achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
-    sync_ms = sorted(sync_ms)[:max(1, len(sync_ms) - len(sync_ms) // 20)]
-    sync_avg_ms = sum(sync_ms) / len(sync_ms)
-    sync_bytes = bytes_per_param(w, sched[W], comp, args.batched, args.lars)[1] * w.P
-    sync_gbs = sync_bytes / (sync_avg_ms * 1e-3) / 1e9
-    kname = dominant_kernel(w, args.batched)
-    traffic = MEASURED_TRAFFIC.get((w.name, kname))
+    head, (x0, pool, sched) = measure(torch, absgd, wl, w, args, mode, K_steps, W, R, variant=variant,
+                                      all_plans=not args.only_chosen_plan)
+    ak, sk = head["accumulate_kernel"], head["sync_update_kernel"]
 
     out = {
         "metric": METRIC,
-        "value": gbs,
+        "value": head["value"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": K_steps,
         "warmup": W,
-        "ms_per_step": dt / K_steps * 1e3,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -387,48 +451,102 @@ def main():
             "workload": w.name, "P": w.P, "K": w.K, "grad_dtype": w.grad_dtype,
             "samples_per_microbatch": w.n, "m_k": w.schedule + (str(list(w.ratio)) if w.ratio else ""),
             "tensors": 1 if w.tensor_sizes is None else len(w.tensor_sizes),
-            "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": args.pool,
-            "compensation_lambda": args.compensation, "compensation_from_momentum": dcm, "batched_accumulate": args.batched,
+            "lr": w.lr, "mu": w.mu, "wd": w.wd, "gradient_pool": len(pool),
+            "accumulate": mode, "compensation_lambda": args.compensation,
+            "compensation_from_momentum": variant["dcm"] and args.compensation is not None,
             "update_rule": "adam" if args.adam else ("lars" if args.lars else "momentum sgd"),
-            "streams": best + ", double-buffered",
-            "algorithmic_bytes_per_step": step_bytes // K_steps,
+            "streams": head["plan"] + ", double-buffered",
+            "algorithmic_bytes_per_step": head["algorithmic_bytes_per_step"],
         },
-        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
-        "params_per_s": w.P * K_steps / dt,
-        "overlap_speedup": dt_serial / dt_overlap,
-        "ms_per_step_by_stream_plan": {k: v / K_steps * 1e3 for k, v in timings.items()},
+        "timing": f"median of {R} timed regions of exactly {K_steps} steps, each between two device "
+                  f"synchronisations, after {max(W, 3)} warm-up steps; kernel figures from HIP events on the "
+                  f"kernels' own stream over the same steps x {R}",
+        "repeats": R,
+        "ms_per_step_repeats": head["ms_per_step_repeats"],
+        # algorithmic bytes / time as a share of the published 8 TB/s; an HBM rate only where the
+        # buffers exceed the memory-side cache (cache_assisted false)
+        "pct_of_8TBs": head["pct_of_8TBs"],
+        "cache_assisted": head["cache_assisted"],
+        "params_per_s": head["params_per_s"],
+        "overlap_speedup": head["overlap_speedup"],
+        "ms_per_step_by_stream_plan": head["ms_per_step_by_stream_plan"],
+        "fastest_plan": head["fastest_plan"],
         # time the host needed to enqueue a step (binding + launches + event joins): when it
         # approaches ms_per_step the workload is bound by launches, not by the kernels
-        "host_issue_ms_per_step": HOST_ISSUE[best] / K_steps * 1e3,
-        "fastest_plan": {"name": fastest, "ms_per_step": timings[fastest] / K_steps * 1e3,
-                         "is_the_chosen_one": fastest == best,
-                         "faster_than_chosen_by": timings[best] / timings[fastest] - 1.0},
+        "host_issue_ms_per_step": head["host_issue_ms_per_step"],
         "roofline": {
-            "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-            "algorithmic_bytes_per_launch": kern_bytes, "avg_launch_ms": kern_ms,
-            "launches_timed": launches,
-            "measured": "HIP events around each step's accumulate launches, one-stream plan "
-                        "(the kernel alone on the GPU), same steps as the timed region",
+            "bound": "hbm", "kernel": ak["kernel"], "achieved": ak["achieved"], "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": ak["frac"], "traffic": ak["traffic"], "traffic_source": ak["traffic_source"],
+            "algorithmic_bytes_per_launch": ak["algorithmic_bytes_per_launch"],
+            "avg_launch_ms": ak["avg_launch_ms"], "launches_timed": ak["launches_timed"],
+            "launches_per_step": ak["launches_per_step"],
+            "step_rate_GBs": {"median": ak["median_step_rate"], "min": ak["min_step_rate"],
+                              "max": ak["max_step_rate"]},
+            "measured": "HIP events around each step's accumulate launches on their stream, one-stream plan "
+                        "(the kernel alone on the GPU), every timed step of every repeat, no step left out",
         },
-        "sync_update_kernel": {
-            "achieved": sync_gbs, "unit": "GB/s", "frac": sync_gbs / HBM_PEAK_GBS,
-            "algorithmic_bytes_per_launch": sync_bytes, "avg_launch_ms": sync_avg_ms,
-            "measured": "HIP events around the single sync-update launch of each step, one-stream plan, same "
-                        "steps; a bracket around one launch also holds ~5 us of dispatch latency, so this is "
-                        "a lower bound on the kernel's rate (the kernel trace under profiles/ has its own duration)",
-        },
-        "box_ceilings": probe_ceilings(torch, w.K),
+        "sync_update_kernel": dict(sk, unit="GB/s",
+                                   measured="HIP events around the single sync-update launch of each step, "
+                                            "one-stream plan; a bracket around ONE launch also holds a few us "
+                                            "of dispatch latency, so this is a lower bound on the kernel's rate "
+                                            "(the kernel trace under profiles/ has its own duration)"),
     }
-    if out["box_ceilings"]:
-        out["pct_of_box_copy_rate"] = 100.0 * gbs / out["box_ceilings"]["copy_GBs"]
-        # the dominant kernel against a plain kernel of its own read:write mix at 1 GiB per vector
-        out["roofline"]["frac_of_box_triad"] = achieved / out["box_ceilings"]["triad_GBs"]
-        mix = out["box_ceilings"].get(f"mix_{w.K}_workers_GBs")
+
+    table_Ks = {w.K}
+    if plain and not args.no_variants:
+        # the same workload with Step 2 issued the other ways (each priced with its own algorithmic bytes)
+        out["accumulate_variants"] = {}
+        for m in ("step", "rounds", "calls"):
+            if m == mode:
+                r = head
+            else:
+                r, _ = measure(torch, absgd, wl, w, args, m, K_steps, W, max(3, R // 2 + 1), all_plans=(m == "calls"))
+            out["accumulate_variants"][m] = {
+                k: r[k] for k in ("value", "pct_of_8TBs", "ms_per_step", "params_per_s", "plan",
+                                  "algorithmic_bytes_per_step", "host_issue_ms_per_step")}
+            out["accumulate_variants"][m]["accumulate_kernel_frac"] = r["accumulate_kernel"]["frac"]
+            out["accumulate_variants"][m]["launches_per_step"] = r["accumulate_kernel"]["launches_per_step"] + 1
+    if plain and not args.no_table:
+        def row(r):
+            return {"value": r["value"], "pct_of_8TBs": r["pct_of_8TBs"], "ms_per_step": r["ms_per_step"],
+                    "params_per_s": r["params_per_s"], "plan": r["plan"],
+                    "algorithmic_bytes_per_step": r["algorithmic_bytes_per_step"],
+                    "accumulate_frac": r["accumulate_kernel"]["frac"], "sync_update_frac": r["sync_update_kernel"]["frac"],
+                    "accumulate_launch_ms": r["accumulate_kernel"]["avg_launch_ms"],
+                    "sync_update_launch_ms": r["sync_update_kernel"]["median_launch_ms"],
+                    "launches_per_step": r["accumulate_kernel"]["launches_per_step"] + 1,
+                    "host_issue_ms_per_step": r["host_issue_ms_per_step"]}
+        out["per_config"] = {}
+        for name in STATED:
+            wc = wl.WORKLOADS[name]
+            table_Ks.add(wc.K)
+            r = head if name == w.name else measure(torch, absgd, wl, wc, args, mode, min(K_steps, 20), W, R,
+                                                    all_plans=False)[0]
+            entry = dict(row(r), P=wc.P, K=wc.K, grad_dtype=wc.grad_dtype, accumulate=mode,
+                         cache_assisted=r["cache_assisted"])
+            if mode != "step":
+                # the same configuration with Step 2 as one job-list call per iteration
+                rs = measure(torch, absgd, wl, wc, args, "step", min(K_steps, 20), W, R, all_plans=False)[0]
+                entry["one_call_per_step"] = dict(row(rs), step_time_vs_separate_calls=rs["ms_per_step"] / r["ms_per_step"])
+            out["per_config"][name] = entry
+
+    ceil = None if args.no_ceilings else probe_ceilings(torch, table_Ks)
+    out["box_ceilings"] = ceil
+    if ceil:
+        out["pct_of_box_copy_rate"] = 100.0 * head["value"] / ceil["copy_GBs"]
+        out["pct_of_box_read_rate"] = 100.0 * head["value"] / ceil["read_GBs"]
+        out["roofline"]["frac_of_box_triad"] = ak["achieved"] / ceil["triad_GBs"]
+        mix = ceil.get(f"mix_{w.K}_workers_GBs")
         if mix:
-            out["sync_update_kernel"]["frac_of_box_mix"] = sync_gbs / mix
+            out["sync_update_kernel"]["frac_of_box_mix"] = sk["achieved"] / mix
+        for name, row in out.get("per_config", {}).items():
+            row["pct_of_box_copy"] = 100.0 * row["value"] / ceil["copy_GBs"]
+            row["accumulate_vs_box_triad"] = row["accumulate_frac"] * HBM_PEAK_GBS / ceil["triad_GBs"]
+            mix = ceil.get(f"mix_{row['K']}_workers_GBs")
+            if mix:
+                row["sync_update_vs_box_mix"] = row["sync_update_frac"] * HBM_PEAK_GBS / mix
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:])
+        out["cpu_baseline"] = cpu_baseline(w, x0, pool, sched[W:], mode)
     print(json.dumps(out))
     return 0
 

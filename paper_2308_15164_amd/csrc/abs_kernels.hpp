@@ -145,13 +145,15 @@ struct GradArgs {
 };
 
 // Rows per group and gradients whose loads are issued together.  One gradient per
-// launch: 4 rows (8 loads in flight per lane).  Several: 2 rows and all of them at
-// once (up to 18 loads); measured best among 1-4 rows x 2-8 gradients per batch.
+// launch: 4 rows (8 loads in flight per lane).  Several: 4 rows x 4 gradients at a time
+// (up to 20 loads).  Measured at P = 1.4e8 with J distinct gradient vectors, J = 2..8:
+// groups of 4 rows move 2-4 % more than groups of 2 rows for both gradient types, and
+// whether 2, 4 or 8 gradients are loaded at a time then matters little.
 #ifndef ABS_ACCB_BATCH
-#define ABS_ACCB_BATCH 8       // gradients per load batch when a launch folds in several
+#define ABS_ACCB_BATCH 4       // gradients per load batch when a launch folds in several
 #endif
 #ifndef ABS_ACCB_ROWS
-#define ABS_ACCB_ROWS 2        // rows per group when a launch folds in several gradients
+#define ABS_ACCB_ROWS 4        // rows per group when a launch folds in several gradients
 #endif
 template <int J>
 constexpr int acc_batch() { return J < ABS_ACCB_BATCH ? J : ABS_ACCB_BATCH; }
@@ -569,9 +571,37 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__re
 // is read with scalar loads (y is uniform over the workgroup).
 // JMAX bounds the J of every job of the launch (the host instantiates 1, 2, 4, 8), so
 // that a launch of single gradients does not carry the registers of an 8-gradient one.
+//
+// A workgroup lives for some microseconds only, so what it waits for before its first
+// vector load matters: everything it needs of its job (J, the flag, the accumulator,
+// JMAX gradient pointers and sample counts) is read in ONE batch of scalar loads, whether
+// or not the job uses all JMAX entries, and only then does the code branch on J.
+template <int JMAX>
+struct JobView {
+    float *acc;
+    const void *g[JMAX];
+    float n[JMAX];
+    int J, first;
+};
+
+template <int JMAX>
+__device__ __forceinline__ JobView<JMAX> view_job(const Job &jb)
+{
+    JobView<JMAX> v;
+    v.acc = static_cast<float *>(jb.acc);
+    v.J = jb.J;
+    v.first = jb.first;
+#pragma unroll
+    for (int j = 0; j < JMAX; ++j) {
+        v.g[j] = jb.g[j];
+        v.n[j] = jb.n[j];
+    }
+    return v;
+}
+
 template <bool BF16, bool NTA, int JMAX, int J = 1>
-__device__ __forceinline__ void accumulate_job_tile(float *__restrict__ acc, const Job &jb, int64_t base,
-                                                    const void *const *gp, int len)
+__device__ __forceinline__ void accumulate_job_tile(float *__restrict__ acc, const JobView<JMAX> &jb, int64_t base,
+                                                    int len)
 {
     typedef typename GradT<BF16>::elem gelem;
     if (jb.J == J) {
@@ -579,39 +609,47 @@ __device__ __forceinline__ void accumulate_job_tile(float *__restrict__ acc, con
         bool vec_ok = aligned16(acc);
 #pragma unroll
         for (int j = 0; j < J; ++j) {
-            G.g[j] = static_cast<const gelem *>(gp[j]) + base;
+            G.g[j] = static_cast<const gelem *>(jb.g[j]) + base;
             G.n[j] = jb.n[j];
             vec_ok = vec_ok && (BF16 ? aligned8(G.g[j]) : aligned16(G.g[j]));
         }
         accumulate_tile<BF16, NTA, J>(acc, G, len, jb.first != 0, vec_ok);
         return;
     }
-    if constexpr (J < JMAX) accumulate_job_tile<BF16, NTA, JMAX, J + 1>(acc, jb, base, gp, len);
+    if constexpr (J < JMAX) accumulate_job_tile<BF16, NTA, JMAX, J + 1>(acc, jb, base, len);
 }
 
 template <bool BF16, bool NTA, int JMAX>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_flat(JobList L, int64_t P, int tile)
 {
-    const Job &jb = L.job[blockIdx.y];
+    const JobView<JMAX> jb = view_job<JMAX>(L.job[blockIdx.y]);
     const int64_t base = (int64_t)blockIdx.x * tile;
-    accumulate_job_tile<BF16, NTA, JMAX>(static_cast<float *>(jb.acc) + base, jb, base, jb.g,
-                                         tile_len(P, base, tile));
+    accumulate_job_tile<BF16, NTA, JMAX>(jb.acc + base, jb, base, tile_len(P, base, tile));
 }
 
+// Ragged: the job's entries are pointer TABLES; the chunk, the tensor's size and the
+// tensor's base pointers (accumulator and JMAX gradients, unused entries read from the
+// accumulator's table so that every load is valid) follow in a second batch.
 template <bool BF16, bool NTA, int JMAX>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_ragged(const Chunk *__restrict__ chunks,
                                                                    const int64_t *__restrict__ sizes,
                                                                    JobList L, int tile)
 {
-    const Job &jb = L.job[blockIdx.y];
+    const JobView<JMAX> tabs = view_job<JMAX>(L.job[blockIdx.y]);
     const Chunk c = chunks[blockIdx.x];
     const int64_t base = (int64_t)c.index * tile;
-    const void *gp[8];
+    JobView<JMAX> jb;
+    jb.J = tabs.J;
+    jb.first = tabs.first;
+    jb.acc = reinterpret_cast<float *const *>(tabs.acc)[c.tensor];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-        gp[j] = (j < JMAX && j < jb.J) ? static_cast<const void *const *>(jb.g[j])[c.tensor] : nullptr;
-    accumulate_job_tile<BF16, NTA, JMAX>(static_cast<float *const *>(jb.acc)[c.tensor] + base, jb, base, gp,
-                                         tile_len(sizes[c.tensor], base, tile));
+    for (int j = 0; j < JMAX; ++j) {
+        const void *const *t = j < tabs.J ? static_cast<const void *const *>(tabs.g[j])
+                                          : reinterpret_cast<const void *const *>(tabs.acc);
+        jb.g[j] = t[c.tensor];
+        jb.n[j] = tabs.n[j];
+    }
+    accumulate_job_tile<BF16, NTA, JMAX>(jb.acc + base, jb, base, tile_len(sizes[c.tensor], base, tile));
 }
 
 template <int K> struct TabPtrs { const float *const *t[K]; };

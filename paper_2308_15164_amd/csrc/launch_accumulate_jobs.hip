@@ -28,7 +28,7 @@ int jobs_flat(const Tuning &tu, const JobList &jobs, int njobs, int64_t P, hipSt
     const int64_t tile64 = choose_tile(rows_of(P) * njobs, resident(tu, per_cu), tu.max_rows);
     if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
     const dim3 grid((unsigned)tiles_for(P, tile64), (unsigned)njobs), block(BLOCK);
-    if (stream_acc(tu, P))
+    if (stream_jobs(tu, P, njobs))
         hipLaunchKernelGGL((accumulate_jobs_flat<BF16, true, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
     else
         hipLaunchKernelGGL((accumulate_jobs_flat<BF16, false, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
@@ -39,7 +39,7 @@ template <bool BF16, int JMAX>
 int jobs_ragged(const Tuning &tu, const RaggedView &L, const JobList &jobs, int njobs, hipStream_t s)
 {
     const dim3 grid(L.nchunks, (unsigned)njobs), block(BLOCK);
-    if (stream_acc(tu, L.total))
+    if (stream_jobs(tu, L.total, njobs))
         hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, true, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);
     else
         hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, false, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);

@@ -160,12 +160,10 @@ class DeviceRun:
         return self.ctx.abs_sync_update_dc(self.x_arg, self.xp_arg, self.v_arg, self.lr, self.mu, self.wd,
                                            self.lam)
 
-    def step(self, t, calls=None):
-        """One iteration of Algorithm 1: Step 1 + update on the delayed generation,
-        Step 2 (accumulation) on the current one, then the swap."""
+    def accumulate(self, calls):
+        """Step 2 of all workers for one iteration, issued the way this run was set up.
+        Returns the number of kernel launches it took."""
         ctx, n, gdt = self.ctx, self.w.n, self.gdt
-        applied = self.sync_update()
-        calls = self.plan_step(t) if calls is None else calls
         if self.step_fold is not None:
             # plan_step lists the calls worker by worker, which is the order the step call takes
             m = [0] * self.K
@@ -173,16 +171,24 @@ class DeviceRun:
                 m[k] += 1
             ctx.abs_accumulate_step([g for _, g in calls], m, [n] * len(calls), fold=self.step_fold,
                                     grad_dtype=gdt)
-        elif not self.batched:
+            return -(-max(m) // self.step_fold) * -(-self.K // 16)
+        if not self.batched:
             for k, g in calls:
                 ctx.abs_accumulate(k, g, n, grad_dtype=gdt)
-        else:
-            per_worker = {}
-            for k, g in calls:
-                per_worker.setdefault(k, []).append(g)
-            for k, gs in per_worker.items():
-                ctx.abs_accumulate_batch(k, gs, [n] * len(gs), grad_dtype=gdt)
-        ctx.abs_swap_buffers()
+            return len(calls)
+        per_worker = {}
+        for k, g in calls:
+            per_worker.setdefault(k, []).append(g)
+        for k, gs in per_worker.items():
+            ctx.abs_accumulate_batch(k, gs, [n] * len(gs), grad_dtype=gdt)
+        return sum(-(-len(gs) // 8) for gs in per_worker.values())
+
+    def step(self, t, calls=None):
+        """One iteration of Algorithm 1: Step 1 + update on the delayed generation,
+        Step 2 (accumulation) on the current one, then the swap."""
+        applied = self.sync_update()
+        self.accumulate(self.plan_step(t) if calls is None else calls)
+        self.ctx.abs_swap_buffers()
         return applied
 
     def run(self, steps, record_counts=True):
