@@ -107,6 +107,11 @@ WORKLOADS = {w.name: w for w in [
              "uniform_1_4", pool=8, notes="flat vector with a ragged tail"),
     Workload("tiny_tail_bf16", 9, 100_003, 7, "bf16", 32, 0.05, 0.01, 0.1, 0.9, 5e-4, 4,
              "uniform_1_4", pool=8),
+    Workload("vgg16_k8_bf16", 13, 138_357_544, 8, "bf16", 32, 0.05, 0.01, 0.1, 0.9, 5e-4, 6,
+             "poisson4_plus1", notes="measurement only: the K = 8 kernels with every buffer far beyond the "
+                                     "memory-side cache"),
+    Workload("vgg16_k16_bf16", 14, 138_357_544, 16, "bf16", 32, 0.05, 0.01, 0.1, 0.9, 5e-4, 6,
+             "uniform_1_8", notes="measurement only: the flat K = 16 kernels at a large size"),
     Workload("paper_static", 10, 11_689_512, 4, "f32", 32, 0.05, 0.01, 0.01, 0.0, 0.0, 20,
              "fixed", ratio=(12, 6, 4, 3),
              notes="the paper's own setting: plain SGD, lr 0.01, iteration-time ratio "

@@ -23,6 +23,7 @@ How Step 2 is issued (--accumulate):
 Every line prices its time with the algorithmic bytes of its own mode.
 """
 import argparse
+import gc
 import json
 import os
 import statistics
@@ -93,12 +94,16 @@ def timed_region(run, plans, t0, steps, torch):
     """EXACTLY `steps` steps between two device synchronisations.  Returns (wall seconds,
     seconds the host needed to enqueue them)."""
     torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for t in range(t0, t0 + steps):
-        run.step(t, plans[t])
-    t_issued = time.perf_counter()
-    torch.cuda.synchronize()
-    return time.perf_counter() - t_start, t_issued - t_start
+    gc.disable()                       # a collection between two launches would idle the GPU for milliseconds
+    try:
+        t_start = time.perf_counter()
+        for t in range(t0, t0 + steps):
+            run.step(t, plans[t])
+        t_issued = time.perf_counter()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start, t_issued - t_start
+    finally:
+        gc.enable()
 
 
 def kernel_event_pass(run, plans, t0, steps, torch):

@@ -73,18 +73,25 @@ static_assert(ROW == BLOCK * VEC, "a workgroup row is one 128-bit vector per lan
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Every buffer this library touches is device (global) memory.  Pointers that reach a
+// kernel through a table in memory carry no address space the compiler could know of,
+// and would be accessed with generic (flat) instructions; the casts say what they are.
+#define ABS_GLOBAL __attribute__((address_space(1)))
+
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T *p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
+    const ABS_GLOBAL T *g = (const ABS_GLOBAL T *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(g);
+    else return *g;
 }
 
 template <bool NT, typename T>
 __device__ __forceinline__ void st(T *p, T v)
 {
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    ABS_GLOBAL T *g = (ABS_GLOBAL T *)p;
+    if constexpr (NT) __builtin_nontemporal_store(v, g);
+    else *g = v;
 }
 
 // bfloat16 is the high half of a binary32: widening is a shift.
@@ -437,38 +444,92 @@ __device__ __forceinline__ void sync_tile(float *__restrict__ x, float *__restri
     }
 }
 
-// K known only at run time (K above the specialised range).  get(k) yields
-// worker k's accumulator pointer for this tile; it is uniform across the
-// workgroup, so it costs scalar loads only.
-template <int RULE, class GetPtr>
+// K known only at run time (K above the specialised range).  The workers' base
+// pointers for this tile sit in LDS (`ptrs`, filled by the kernel before the call).
+// Same shape as the specialised kernels -- groups of ABS_SYNC_ROWS rows, the K-way read
+// in batches of ANY_KC workers, ascending order -- but as a LOOP over the batches: the
+// registers hold one batch whatever K is, where the unrolled form at K = 14 or 16 leaves
+// the compiler so short of registers that it issues the loads one at a time.
+#ifndef ABS_ANY_KC
+#define ABS_ANY_KC 4           // workers per batch in the run-time-K kernels
+#endif
+constexpr int ANY_KC = ABS_ANY_KC;
+
+template <int RULE, bool NTX, bool WHOLE>
+__device__ __forceinline__ void sync_group_any(f32x4 *__restrict__ xv, f32x4 *__restrict__ vv,
+                                               f32x4 *__restrict__ pv, const float *const *ptrs, int K, int g0,
+                                               int nvec, int tid, const Hyper &h)
+{
+    constexpr bool S2 = uses_s2<RULE>();
+    constexpr int U = ABS_SYNC_ROWS;
+    f32x4 sum[U] = {}, xr[U] = {}, vr[U] = {}, pr[U] = {};
+    const f32x4 *p0 = reinterpret_cast<const f32x4 *>(ptrs[0]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = GIDX(g0, u, tid, U, false);
+        if (WHOLE || i < nvec) {
+            sum[u] = ld<ABS_NT_SYNC_ACC != 0>(p0 + i);
+            xr[u] = ld<NTX>(xv + i);
+            vr[u] = ld<NTX>(vv + i);
+            if constexpr (S2) pr[u] = ld<NTX>(pv + i);
+        }
+    }
+    for (int k0 = 1; k0 < K; k0 += ANY_KC) {
+        f32x4 a[U][ANY_KC] = {};
+#pragma unroll
+        for (int kk = 0; kk < ANY_KC; ++kk) {
+            if (k0 + kk < K) {
+                const f32x4 *pk = reinterpret_cast<const f32x4 *>(ptrs[k0 + kk]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int i = GIDX(g0, u, tid, U, false);
+                    if (WHOLE || i < nvec) a[u][kk] = ld<ABS_NT_SYNC_ACC != 0>(pk + i);
+                }
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < ANY_KC; ++kk) {
+            if (k0 + kk < K) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) sum[u] = sum[u] + a[u][kk];
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = GIDX(g0, u, tid, U, false);
+        if (WHOLE || i < nvec) {
+            update_vec<RULE>(sum[u], xr[u], vr[u], pr[u], h);
+            st<NTX>(vv + i, vr[u]);
+            if constexpr (S2) st<NTX>(pv + i, pr[u]);
+            st<NTX>(xv + i, xr[u]);
+        }
+    }
+}
+
+template <int RULE, bool NTX>
 __device__ __forceinline__ void sync_tile_any(float *__restrict__ x, float *__restrict__ v,
-                                              float *__restrict__ xp, GetPtr get, int K, int len,
+                                              float *__restrict__ xp, const float *const *ptrs, int K, int len,
                                               const Hyper &h, bool vec_ok)
 {
     constexpr bool S2 = uses_s2<RULE>();
+    constexpr int U = ABS_SYNC_ROWS;
     const int tid = threadIdx.x;
+    int done = 0;
     if (vec_ok) {
         f32x4 *xv = reinterpret_cast<f32x4 *>(x);
         f32x4 *vv = reinterpret_cast<f32x4 *>(v);
         f32x4 *pv = reinterpret_cast<f32x4 *>(xp);
         const int nvec = len / VEC;
-        for (int i = tid; i < nvec; i += BLOCK) {
-            f32x4 s = ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(get(0)) + i);
-#pragma unroll 8
-            for (int k = 1; k < K; ++k)
-                s = s + ld<ABS_NT_SYNC_ACC != 0>(reinterpret_cast<const f32x4 *>(get(k)) + i);
-            f32x4 xr = xv[i], vr = vv[i], pr = {};
-            if constexpr (S2) pr = pv[i];
-            update_vec<RULE>(s, xr, vr, pr, h);
-            vv[i] = vr;
-            if constexpr (S2) pv[i] = pr;
-            xv[i] = xr;
-        }
+        int g0 = 0;
+        for (; g0 + U * BLOCK <= nvec; g0 += U * BLOCK)
+            sync_group_any<RULE, NTX, true>(xv, vv, pv, ptrs, K, g0, nvec, tid, h);
+        if (g0 < nvec) sync_group_any<RULE, NTX, false>(xv, vv, pv, ptrs, K, g0, nvec, tid, h);
+        done = nvec * VEC;
     }
-    const int done = vec_ok ? (len / VEC) * VEC : 0;
     for (int i = done + tid; i < len; i += BLOCK) {
-        float s = get(0)[i];
-        for (int k = 1; k < K; ++k) s = s + get(k)[i];
+        float s = ptrs[0][i];
+        for (int k = 1; k < K; ++k) s = s + ptrs[k][i];
         float ps = 0.f;
         if constexpr (S2) ps = xp[i];
         update_one<RULE>(s, x[i], v[i], ps, h);
@@ -516,16 +577,19 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat(float *__restrict_
                             tile_len(P, base, tile), h, vec_ok != 0);
 }
 
-template <int RULE>
+template <int RULE, bool NTX>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restrict__ x,
                                                                  float *__restrict__ v,
                                                                  float *__restrict__ xp,
                                                                  AccPtrsAny A, int K, int64_t P,
                                                                  int tile, Hyper h, int vec_ok)
 {
+    __shared__ const float *ptrs[64];
     const int64_t base = (int64_t)blockIdx.x * tile;
-    sync_tile_any<RULE>(x + base, v + base, uses_s2<RULE>() ? xp + base : nullptr,
-                        [&](int k) { return A.p[k] + base; }, K, tile_len(P, base, tile), h, vec_ok != 0);
+    if ((int)threadIdx.x < K) ptrs[threadIdx.x] = A.p[threadIdx.x] + base;
+    __syncthreads();
+    sync_tile_any<RULE, NTX>(x + base, v + base, uses_s2<RULE>() ? xp + base : nullptr, ptrs, K,
+                             tile_len(P, base, tile), h, vec_ok != 0);
 }
 
 // Ragged layout: workgroup b looks its (tensor, tile index) up in a table; the
@@ -682,7 +746,7 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__r
     sync_tile<K, NTX, RULE>(x, v, xp, A, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
 }
 
-template <int RULE>
+template <int RULE, bool NTX>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk *__restrict__ chunks,
                                                                    const int64_t *__restrict__ sizes,
                                                                    float *const *__restrict__ x_tab,
@@ -691,15 +755,23 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk 
                                                                    TabPtrsAny tabs, int K, int tile,
                                                                    Hyper h)
 {
+    __shared__ const float *ptrs[64];
+    __shared__ int all_aligned;
     const Chunk c = chunks[blockIdx.x];
     const int64_t base = (int64_t)c.index * tile;
+    if (threadIdx.x == 0) all_aligned = 1;
+    __syncthreads();
+    if ((int)threadIdx.x < K) {
+        const float *p = tabs.t[threadIdx.x][c.tensor] + base;
+        ptrs[threadIdx.x] = p;
+        if (!aligned16(p)) all_aligned = 0;          // every writer stores the same value
+    }
+    __syncthreads();
     float *x = x_tab[c.tensor] + base;
     float *v = v_tab[c.tensor] + base;
     float *xp = uses_s2<RULE>() ? p_tab[c.tensor] + base : nullptr;
-    bool vec_ok = aligned16(x) && aligned16(v) && aligned16(xp);
-    for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned16(tabs.t[k][c.tensor] + base);
-    sync_tile_any<RULE>(x, v, xp, [&](int k) { return tabs.t[k][c.tensor] + base; }, K,
-                        tile_len(sizes[c.tensor], base, tile), h, vec_ok);
+    const bool vec_ok = aligned16(x) && aligned16(v) && aligned16(xp) && all_aligned != 0;
+    sync_tile_any<RULE, NTX>(x, v, xp, ptrs, K, tile_len(sizes[c.tensor], base, tile), h, vec_ok);
 }
 
 }  // namespace absk

@@ -60,6 +60,10 @@ void sync_ragged_k(const Tuning &tu, const RaggedView &L, float *const *xt, floa
 
 }  // namespace
 
+// Workers up to this many get a kernel of their own (the K-way read fully unrolled);
+// beyond it the run-time-K kernels loop over batches of workers.
+constexpr int kMaxSpecialisedK = 8;
+
 template <int RULE>
 int launch_sync_flat_r(const Tuning &tu, float *x, float *s1, float *s2, const float *const *ptrs, int n,
                        int64_t P, const Hyper &h, int vec_ok, hipStream_t s)
@@ -67,18 +71,21 @@ int launch_sync_flat_r(const Tuning &tu, float *x, float *s1, float *s2, const f
     switch (n) {
 #define ABS_CASE(K) case K: return sync_flat_k<K, RULE>(tu, x, s1, s2, ptrs, P, h, vec_ok, s);
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
-        ABS_CASE(16)
 #undef ABS_CASE
     default: {
+        static_assert(kMaxSpecialisedK == 8, "the cases above");
         if (n < 1 || n > ABS_MAX_K) return ABS_EINVAL;
-        const int64_t tile64 = choose_tile(rows_of(P), resident(tu, 4), tu.max_rows);
+        static const int per_cu = occupancy_per_cu(sync_update_flat_any<RULE, false>, 3);
+        const int64_t tile64 = choose_tile(rows_of(P), resident(tu, per_cu), tu.max_rows);
         if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
         AccPtrsAny A;
         std::memset(&A, 0, sizeof A);
         for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
-        hipLaunchKernelGGL(sync_update_flat_any<RULE>, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0,
-                           s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok);
+        const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
+        if (stream_upd(tu, P, uses_s2<RULE>() ? 3 : 2))
+            hipLaunchKernelGGL((sync_update_flat_any<RULE, true>), grid, block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok);
+        else
+            hipLaunchKernelGGL((sync_update_flat_any<RULE, false>), grid, block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok);
         return ABS_OK;
     }
     }
@@ -92,16 +99,17 @@ int launch_sync_ragged_r(const Tuning &tu, const RaggedView &L, float *const *xt
     switch (n) {
 #define ABS_CASE(K) case K: sync_ragged_k<K, RULE>(tu, L, xt, s1t, s2t, tabs, h, s); return ABS_OK;
         ABS_CASE(1) ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8)
-        ABS_CASE(9) ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15)
-        ABS_CASE(16)
 #undef ABS_CASE
     default: {
         if (n < 1 || n > ABS_MAX_K) return ABS_EINVAL;
         TabPtrsAny T;
         std::memset(&T, 0, sizeof T);
         for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
-        hipLaunchKernelGGL(sync_update_ragged_any<RULE>, dim3(L.nchunks), dim3(BLOCK), 0, s, L.chunks, L.sizes,
-                           xt, s1t, s2t, T, n, L.tile, h);
+        const dim3 grid(L.nchunks), block(BLOCK);
+        if (stream_upd(tu, L.total, uses_s2<RULE>() ? 3 : 2))
+            hipLaunchKernelGGL((sync_update_ragged_any<RULE, true>), grid, block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h);
+        else
+            hipLaunchKernelGGL((sync_update_ragged_any<RULE, false>), grid, block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h);
         return ABS_OK;
     }
     }

@@ -9,9 +9,10 @@
  * Covered: abs_accumulate (fp32 and bf16 gradients, overwrite-on-first),
  * abs_accumulate_batch, abs_sync_update, and Algorithm 1's loop through the
  * double-buffer context (abs_ctx_create / abs_ctx_accumulate /
- * abs_ctx_sync_update / abs_swap_buffers) on two streams, and the ragged forms
- * (abs_layout, abs_tensorset, abs_accumulate[_batch]_mt, abs_sync_update_mt)
- * over separately allocated tensors, one of them empty.
+ * abs_ctx_sync_update / abs_swap_buffers) on two streams, the same loop with
+ * Step 2 of all workers as one abs_ctx_accumulate_step call, and the ragged forms
+ * (abs_layout, abs_tensorset, abs_accumulate[_batch]_mt, abs_accumulate_jobs_mt,
+ * abs_sync_update_mt) over separately allocated tensors, one of them empty.
  *
  * Exit status 0 and a last line "abi_check: OK" on success.
  */
@@ -218,13 +219,14 @@ static int check_calls(int64_t P)
 }
 
 /* ---- case 2: Algorithm 1's loop through the double-buffer context, two streams ---- */
-static int check_loop(int64_t P)
+static int check_loop(int64_t P, int fold)
 {
     enum { K = 2, T = 5, R = 4 };
     static const int m[T][K] = {{1, 3}, {2, 1}, {0, 2}, {3, 3}, {1, 1}};   /* reference batches per worker and iteration */
     const int64_t M_r = 32;
     int ok = 1;
-    printf("[case] Algorithm 1 loop through abs_ctx, P = %lld, K = %d, T = %d\n", (long long)P, K, T);
+    printf("[case] Algorithm 1 loop through abs_ctx, P = %lld, K = %d, T = %d, %s\n", (long long)P, K, T,
+           fold ? "Step 2 of all workers as ONE abs_ctx_accumulate_step call per iteration" : "one abs_ctx_accumulate call per batch");
     fflush(stdout);
     float *x = malloc((size_t)P * 4), *pool[R];
     void *d_pool[R];
@@ -258,15 +260,20 @@ static int check_loop(int64_t P)
         const float *Gp[K] = {G[cur ^ 1][0], G[cur ^ 1][1]};
         const int want = oracle32_sync_update(x32, v32, Gp, M[cur ^ 1], K, P, 0.05f, 0.9f, 1e-3f) == 0 ? ABS_OK : ABS_EMPTY;
         if (applied != want) { fprintf(stderr, "iteration %d: sync-update returned %d, oracle says %d\n", t, applied, want); ok = 0; }
+        const void *step_grads[K * 3];                 /* worker 0's batches, then worker 1's */
+        int64_t step_ns[K * 3];
+        int n_step = 0;
         for (int k = 0; k < K; ++k) {
             M[cur][k] = 0;
             for (int j = 0; j < m[t][k]; ++j) {
                 const int r = (3 * t + 2 * k + j) % R;
-                CHECK_ABS(abs_ctx_accumulate(ctx, k, d_pool[r], ABS_F32, M_r), ABS_OK);
+                if (fold) { step_grads[n_step] = d_pool[r]; step_ns[n_step++] = M_r; }
+                else CHECK_ABS(abs_ctx_accumulate(ctx, k, d_pool[r], ABS_F32, M_r), ABS_OK);
                 oracle32_accumulate_f32(G[cur][k], pool[r], P, M_r, M[cur][k] == 0);
                 M[cur][k] += M_r;
             }
         }
+        if (fold) CHECK_ABS(abs_ctx_accumulate_step(ctx, step_grads, m[t], step_ns, ABS_F32, fold), ABS_OK);
         int64_t got[K];
         CHECK_ABS(abs_ctx_counts(ctx, 0, got), ABS_OK);
         for (int k = 0; k < K; ++k)
@@ -335,6 +342,19 @@ static int check_ragged(void)
     const abs_tensorset *accs[K] = {sa[0], sa[1]};
     CHECK_ABS(abs_sync_update_mt(L, sx, sv, accs, counts, K, 0.1f, 0.9f, 5e-4f, NULL), ABS_OK);
     CHECK_HIP(hipDeviceSynchronize());
+    /* the same two accumulations once more, both workers in ONE job-list call (fresh buffers) */
+    void *dj[K][T];
+    abs_tensorset *sj[K];
+    for (int k = 0; k < K; ++k) {
+        for (int t = 0; t < T; ++t) dj[k][t] = sizes[t] ? device_garbage((size_t)sizes[t] * 4) : NULL;
+        CHECK_ABS(abs_tensorset_create(&sj[k], L, dj[k], ABS_F32), ABS_OK);
+    }
+    int64_t jcounts[K] = {0, 0};
+    const abs_tensorset *job0[2] = {sg32, sg32}, *job1[2] = {sg32, sg32};
+    const int64_t jn0[2] = {32, 64}, jn1[2] = {16, 48};
+    const abs_job_mt jobs[K] = {{sj[0], job0, jn0, 2, &jcounts[0]}, {sj[1], job1, jn1, 2, &jcounts[1]}};
+    CHECK_ABS(abs_accumulate_jobs_mt(L, jobs, K, 8, NULL), ABS_OK);
+    CHECK_HIP(hipDeviceSynchronize());
 
     float *G0 = malloc((size_t)P * 4), *G1 = malloc((size_t)P * 4), *x32 = malloc((size_t)P * 4), *v32 = malloc((size_t)P * 4);
     oracle32_accumulate_bf16(G0, gbf, P, 32, 1);
@@ -355,6 +375,20 @@ static int check_ragged(void)
     for (int t = 0; t < T; ++t)
         if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], da[1][t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
     ok &= same_bits(out, G1, P, "ragged accumulator (batched)");
+    for (int t = 0; t < T; ++t)
+        if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], dj[1][t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
+    ok &= same_bits(out, G1, P, "ragged accumulator (job list, worker 1)");
+    oracle32_accumulate_f32(G0, g32, P, 32, 1);
+    oracle32_accumulate_f32(G0, g32, P, 64, 0);
+    for (int t = 0; t < T; ++t)
+        if (sizes[t]) CHECK_HIP(hipMemcpy(out + off[t], dj[0][t], (size_t)sizes[t] * 4, hipMemcpyDeviceToHost));
+    ok &= same_bits(out, G0, P, "ragged accumulator (job list, worker 0)");
+    if (jcounts[0] != 96 || jcounts[1] != 64) { fprintf(stderr, "job-list counts\n"); ok = 0; }
+    for (int k = 0; k < K; ++k) {
+        abs_tensorset_destroy(sj[k]);
+        for (int t = 0; t < T; ++t)
+            if (sizes[t]) CHECK_HIP(hipFree(dj[k][t]));
+    }
 
     abs_tensorset_destroy(sx); abs_tensorset_destroy(sv); abs_tensorset_destroy(sg32); abs_tensorset_destroy(sgbf);
     for (int k = 0; k < K; ++k) abs_tensorset_destroy(sa[k]);
@@ -379,7 +413,9 @@ int main(void)
     int ok = 1;
     ok &= check_calls(3 * 4096 + 1029);        /* several tiles and a ragged tail */
     ok &= check_calls(5);                      /* shorter than one vector */
-    ok &= check_loop(200003);
+    ok &= check_loop(200003, 0);
+    ok &= check_loop(200003, 8);               /* a job list: all workers of an iteration in one launch */
+    ok &= check_loop(70001, 1);                /* the same call, one batch per worker and launch */
     ok &= check_ragged();
     if (!ok) {
         fprintf(stderr, "abi_check: FAILED\n");
