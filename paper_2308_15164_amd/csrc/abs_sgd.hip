@@ -213,6 +213,8 @@ void layout_free_device(const abs_layout *L)
 // called when a tensor set is created (or explicitly), never from a launch.
 int layout_upload(const abs_layout *L)
 {
+    static std::mutex upload_mutex;      // two threads may make their first tensor sets over one layout at once
+    std::lock_guard<std::mutex> lock(upload_mutex);
     int dev = 0;
     ABS_HIP(hipGetDevice(&dev));
     if (L->device >= 0) return L->device == dev ? ABS_OK : ABS_EINVAL;
@@ -928,24 +930,36 @@ int abs_sync_update_lars_mt_noalloc(abs_layout *L, const abs_tensorset *params, 
 
 // --------------------------------------------------------- double buffer
 
+// Everything that can fail happens before the context is touched: after an error the
+// context still works with the streams it had.
 static int ctx_set_streams(abs_ctx *C, const hipStream_t *streams, int n)
 {
-    for (hipEvent_t e : C->ev_acc) (void)hipEventDestroy(e);
-    C->ev_acc.clear();
+    bool joins = false;
+    for (int i = 0; i < n; ++i) joins = joins || streams[i] != C->s_upd;
+    hipEvent_t upd = C->ev_upd;
+    std::vector<hipEvent_t> ev;
+    if (joins) {
+        hipError_t e = hipSuccess;
+        if (!upd) e = hipEventCreateWithFlags(&upd, hipEventDisableTiming);
+        for (int i = 0; i < n && e == hipSuccess; ++i) {
+            hipEvent_t one = nullptr;
+            e = hipEventCreateWithFlags(&one, hipEventDisableTiming);
+            if (e == hipSuccess) ev.push_back(one);
+        }
+        if (e != hipSuccess) {
+            for (hipEvent_t one : ev) (void)hipEventDestroy(one);
+            if (upd && upd != C->ev_upd) (void)hipEventDestroy(upd);
+            return hip_fail(e);
+        }
+    }
+    for (hipEvent_t one : C->ev_acc) (void)hipEventDestroy(one);
+    C->ev_acc.swap(ev);
+    C->ev_upd = upd;
     C->s_acc.assign(streams, streams + n);
     C->slot.resize((size_t)C->K);
     for (int k = 0; k < C->K; ++k) C->slot[(size_t)k] = k % n;
     C->launches.assign((size_t)C->K, 0);
-    C->joins = false;
-    for (hipStream_t s : C->s_acc) C->joins = C->joins || s != C->s_upd;
-    if (C->joins) {
-        if (!C->ev_upd) ABS_HIP(hipEventCreateWithFlags(&C->ev_upd, hipEventDisableTiming));
-        for (int i = 0; i < n; ++i) {
-            hipEvent_t e = nullptr;
-            ABS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            C->ev_acc.push_back(e);
-        }
-    }
+    C->joins = joins;
     return ABS_OK;
 }
 
