@@ -1447,3 +1447,22 @@ def test_c_abi_from_plain_c(absgd):
     print(r.stdout, r.stderr, flush=True)
     assert r.returncode == 0
     assert r.stdout.strip().endswith("abi_check: OK")
+
+
+# ---------------------------------------------------------------------------
+# the usage example of the README runs as printed
+# ---------------------------------------------------------------------------
+
+def test_readme_example_runs(absgd):
+    import os
+    import torch
+    readme = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")
+    code = open(readme).read().split("```python")[1].split("```")[0]
+    print("[case] README example", flush=True)
+    ns = {}
+    exec(compile(code, "README.md", "exec"), ns)
+    x, v, ctx = ns["x"], ns["v"], ns["ctx"]
+    assert bool(torch.isfinite(x).all()) and bool(torch.isfinite(v).all())
+    assert float(v.abs().max()) > 0.0                       # updates were applied
+    assert ctx.counts(0) == [0] * ns["K"]                   # after the last swap: nothing accumulated yet
+    assert ctx.counts(1) == [32 * (1 + k) for k in range(ns["K"])]
