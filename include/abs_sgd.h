@@ -372,7 +372,11 @@ int abs_sync_update_lars_mt(abs_layout *layout, const abs_tensorset *params,
  * library instead of memory owned by the layout.  The array is about 1.03 MiB; every
  * GPU the library runs on holds its own copy until the process ends.  The call never
  * allocates or frees, on the host side of the runtime or through it, and does not
- * wait for the device; the first call on a device looks the array's address up once.
+ * wait for the device.  The array's address on a device is looked up once, when a
+ * layout's tables go to that device (abs_layout_upload, or the first tensor set over
+ * a layout), so the call itself asks the runtime for nothing but launches and may be
+ * recorded into a HIP graph; a recorded call replays with the sample counts it was
+ * recorded with.
  *
  *   Limits: abs_layout_num_chunks(layout) <= ABS_NOALLOC_MAX_CHUNKS and
  *   abs_layout_num_tensors(layout) <= ABS_NOALLOC_MAX_TENSORS, else ABS_EINVAL with

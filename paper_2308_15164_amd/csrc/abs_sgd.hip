@@ -209,6 +209,8 @@ void layout_free_device(const abs_layout *L)
     L->device = -1;
 }
 
+int scratch_on_current_device(LarsScratch &sc);
+
 // Copies the tables to the current device and allocates the LARS scratch.  Blocking;
 // called when a tensor set is created (or explicitly), never from a launch.
 int layout_upload(const abs_layout *L)
@@ -235,6 +237,11 @@ int layout_upload(const abs_layout *L)
         return hip_fail(e);
     }
     L->device = dev;
+    // Set-up time on this device: look the fixed scratch array's address up now, so that the
+    // allocation-free entry point has nothing left to ask the runtime for (its first call may
+    // then already be inside a graph capture).  A failure here is reported by that call.
+    LarsScratch unused;
+    (void)scratch_on_current_device(unused);
     return ABS_OK;
 }
 

@@ -53,6 +53,48 @@ def _pair(absgd, sizes, counts, seed, lr=0.1, mu=0.9, wd=5e-4, eta=0.02):
     return out, x0b, lay_chunks
 
 
+def test_noalloc_lars_recorded_into_a_graph_and_replayed(absgd):
+    """What the entry point is for: a caller under graph capture.  The call is recorded with no call
+    before it (the scratch array's address was looked up when the layout's tables went to the device),
+    replayed three times with eager work between the replays, and every replay is compared bit for
+    bit with the allocating entry point applied eagerly to a copy of the same state."""
+    rng = np.random.default_rng(77)
+    sizes, counts = [4096 * 5 + 3, 700, 1, 65_537], [32, 64, 0, 96]
+    hyper = (0.1, 0.9, 5e-4, 0.02)
+    lay = absgd.Layout(sizes)
+    mk = lambda sigma: [torch.from_numpy((rng.standard_normal(s) * sigma).astype(F32)).cuda() for s in sizes]
+    x0, v0 = mk(0.05), mk(0.01)
+    accs = [mk(20.0 * max(c, 1) / 32) for c in counts]
+    asets = [absgd.TensorSet(lay, a) for a in accs]
+    state = lambda: ([t.clone() for t in x0], [t.clone() for t in v0], [torch.zeros_like(t) for t in x0])
+    xr, vr, gr = state()          # eager, allocating entry point
+    xg, vg, gg = state()          # replays of the recorded allocation-free call
+    xw, vw, gw = state()          # eager allocation-free calls between the replays
+    rs, gs, ws = ([absgd.TensorSet(lay, t) for t in trio] for trio in ((xr, vr, gr), (xg, vg, gg), (xw, vw, gw)))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    print("[case] noalloc lars: capture", flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        assert absgd.abs_sync_update_lars_mt_noalloc(lay, gs[0], gs[1], gs[2], asets, counts, *hyper)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(xg), _bits(x0)), "recording a call must not run it"
+    for r in range(3):
+        print(f"[case] noalloc lars: replay {r}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert absgd.abs_sync_update_lars_mt(lay, rs[0], rs[1], rs[2], asets, counts, *hyper)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(xg), _bits(xr)), f"x differs after replay {r}"
+        assert np.array_equal(_bits(vg), _bits(vr)), f"v differs after replay {r}"
+        # the program's own eager work between replays, a call that shares the scratch array included
+        assert absgd.abs_sync_update_lars_mt_noalloc(lay, ws[0], ws[1], ws[2], asets, counts, *hyper)
+        float(torch.randn(1 << 20, device="cuda").sum())
+        torch.cuda.synchronize()
+    assert not np.array_equal(_bits(xg), _bits(x0))
+
+
 def test_noalloc_lars_equals_the_allocating_entry_point_twice_in_a_row(absgd):
     cases = [([1_048_576 + 13, 300_007, 5, 0, 70_001, 1], [32, 64, 0, 96], 31),    # larger first
              ([5000, 3, 700], [64, 32], 32),                                     # then smaller: stale scratch beyond it
