@@ -29,22 +29,28 @@ struct Streams { f32x4 *p[MAXR]; };
 template <int R, int W, bool INPLACE, bool WHOLE>
 __device__ __forceinline__ void tile(const Streams &S, int64_t nvec, float scale, float *sink)
 {
-    const int64_t base = (int64_t)blockIdx.x * (BLOCK * VPT) + threadIdx.x;
+    // The tile's base is uniform over the workgroup and the lane's part of the index fits 32 bits:
+    // every access is (scalar base) + (32-bit lane offset), which leaves the registers to the data.
+    const int64_t tile0 = (int64_t)blockIdx.x * (BLOCK * VPT);
+    const int lane = threadIdx.x;
+    const int left = (int)(nvec - tile0 < BLOCK * VPT ? nvec - tile0 : BLOCK * VPT);   // vectors of this tile
     f32x4 a[VPT][R > 0 ? R : 1];
     if constexpr (R > 0) {
+        // stream by stream: 4 KiB of one stream per wavefront before the next stream is touched
 #pragma unroll
-        for (int u = 0; u < VPT; ++u) {
-            const int64_t i = base + u * BLOCK;
-            if (WHOLE || i < nvec) {
+        for (int r = 0; r < R; ++r) {
+            const f32x4 *p = S.p[r] + tile0;
 #pragma unroll
-                for (int r = 0; r < R; ++r) a[u][r] = __builtin_nontemporal_load(S.p[r] + i);
+            for (int u = 0; u < VPT; ++u) {
+                const int i = lane + u * BLOCK;
+                if (WHOLE || i < left) a[u][r] = __builtin_nontemporal_load(p + i);
             }
         }
     }
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t i = base + u * BLOCK;
-        if (WHOLE || i < nvec) {
+        const int i = lane + u * BLOCK;
+        if (WHOLE || i < left) {
             f32x4 s = {scale, scale, scale, scale};
             if constexpr (R > 0) {
                 s = a[u][0];
@@ -57,7 +63,7 @@ __device__ __forceinline__ void tile(const Streams &S, int64_t nvec, float scale
             } else {
 #pragma unroll
                 for (int w = 0; w < W; ++w)
-                    __builtin_nontemporal_store(R > 0 ? s * (scale * (w + 1)) : s, S.p[INPLACE ? w : R + w] + i);
+                    __builtin_nontemporal_store(R > 0 ? s * (scale * (w + 1)) : s, S.p[INPLACE ? w : R + w] + tile0 + i);
             }
         }
     }
