@@ -1434,6 +1434,61 @@ def test_special_values(absgd):
 
 
 # ---------------------------------------------------------------------------
+# seeded random draws: the grids above vary one thing at a time, these vary all at once
+# ---------------------------------------------------------------------------
+
+def _draw_P(rng):
+    lo, hi = [(1, 64), (64, 5000), (5000, 70_000)][int(rng.integers(0, 3))]
+    return int(rng.integers(lo, hi))
+
+
+def test_random_draws_accumulate_jobs(absgd):
+    rng = np.random.default_rng(0x5EED)
+    for case in range(36):
+        P, W = _draw_P(rng), int(rng.integers(1, 21))
+        Js = [int(j) for j in rng.integers(0, 11, size=W)]
+        if sum(Js) == 0:
+            Js[0] = 1
+        start = [32 * int(rng.integers(1, 4)) if rng.integers(0, 2) else 0 for _ in range(W)]
+        fold, dtype = int(rng.integers(1, 9)), ("f32", "bf16")[int(rng.integers(0, 2))]
+        shift = int(rng.choice([0, 0, 1, 2, 3]))
+        print(f"[case] draw {case}: accumulate_jobs P={P} Js={Js} start={start} fold={fold} {dtype} shift={shift}",
+              flush=True)
+        _jobs_case(absgd, P, Js, dtype, fold, seed=7000 + case, start_counts=start, shift=shift)
+
+
+def test_random_draws_sync_update_rules(absgd):
+    rng = np.random.default_rng(0xD1CE)
+    rules = [("sgd", _sync_case), ("dc", _sync_dc_case), ("dcm", _sync_dcm_case), ("adam", _sync_adam_case)]
+    for case in range(40):
+        P, K = _draw_P(rng), int(rng.integers(1, 41))
+        counts = [32 * int(c) for c in rng.integers(0, 4, size=K)]       # about a quarter of the workers idle
+        if sum(counts) == 0:
+            counts[int(rng.integers(0, K))] = 64
+        name, fn = rules[case % 4]
+        print(f"[case] draw {case}: {name} P={P} K={K} counts={counts}", flush=True)
+        fn(absgd, K, P, counts, seed=7100 + case)
+
+
+def test_random_draws_ragged_layouts(absgd):
+    rng = np.random.default_rng(0xFACE)
+    for case in range(12):
+        T = int(rng.integers(1, 13))
+        sizes = [0 if rng.integers(0, 6) == 0 else _draw_P(rng) for _ in range(T)]
+        if sum(sizes) == 0:
+            sizes[0] = 17
+        K = int(rng.integers(1, 25))
+        counts = [32 * int(c) for c in rng.integers(0, 4, size=K)]
+        if sum(counts) == 0:
+            counts[0] = 32
+        dtype, misalign = ("f32", "bf16")[case % 2], bool(rng.integers(0, 2))
+        print(f"[case] draw {case}: ragged sizes={sizes} counts={counts}", flush=True)
+        _ragged_case(absgd, sizes, counts, seed=7200 + case, dtype=dtype, misalign=misalign)
+        if case % 3 == 0:
+            _lars_case(absgd, sizes, counts, seed=7300 + case)
+
+
+# ---------------------------------------------------------------------------
 # the C ABI from plain C: no Python binding, no PyTorch in the process
 # ---------------------------------------------------------------------------
 
