@@ -134,7 +134,8 @@ def probe_ceilings(torch, Ks=(), nbytes=4 * 138_357_544, reps=20):
     K + 2 vectors only read (what mixing a write stream into the reads costs).  Context for the
     roofline fractions; not part of the method.  Every vector is as long as the VGG16-sized
     parameter vector (553 MB): power-of-two sizes put all streams on the same DRAM banks at
-    the same time and read 2-5 % low."""
+    the same time and read 2-5 % low.  A probe is launched over sub-ranges, one launch per GiB
+    moved, as the library cuts its own long calls (multi-GB launches run 4-7 % slower)."""
     import ctypes
     path = os.path.join(ROOT, "bench_probe", "libabs_probe.so")
     if not os.path.exists(path):
@@ -150,39 +151,54 @@ def probe_ceilings(torch, Ks=(), nbytes=4 * 138_357_544, reps=20):
     sink = torch.zeros(4, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     out = {}
-    for name, fn, moved in (("copy", lambda: L.probe_copy(a.data_ptr(), b.data_ptr(), nbytes, st), 2 * nbytes),
-                            ("read", lambda: L.probe_read(a.data_ptr(), nbytes, sink.data_ptr(), st), nbytes),
-                            ("write", lambda: L.probe_write(a.data_ptr(), nbytes, 1.0, st), nbytes),
-                            ("triad", lambda: L.probe_triad(a.data_ptr(), b.data_ptr(), nbytes, 0.5, st), 3 * nbytes)):
-        for _ in range(3):
-            fn()
+
+    def cuts(moved):
+        """Sub-ranges of a vector, so that a probe is launched the way the library launches its own
+        kernels: one launch per GiB moved (one below two), cut at multiples of 16 KiB."""
+        n = max(1, moved // (1 << 30))
+        edges = [(nbytes * i // n) // 16384 * 16384 for i in range(n)] + [nbytes]
+        return [(edges[i], edges[i + 1] - edges[i]) for i in range(n)]
+
+    def timed(fn, moved, warm=3):
+        for i in range(warm):
+            fn(i)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(reps):
-            fn()
+        for i in range(reps):
+            fn(i)
         e1.record()
         torch.cuda.synchronize()
-        out[name + "_GBs"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        return moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    pa, pb = a.data_ptr(), b.data_ptr()
+    for name, one, moved in (("copy", lambda o, n: L.probe_copy(pa + o, pb + o, n, st), 2 * nbytes),
+                             ("read", lambda o, n: L.probe_read(pa + o, n, sink.data_ptr(), st), nbytes),
+                             ("write", lambda o, n: L.probe_write(pa + o, n, 1.0, st), nbytes),
+                             ("triad", lambda o, n: L.probe_triad(pa + o, pb + o, n, 0.5, st), 3 * nbytes)):
+        parts = cuts(moved)
+
+        def fn(i, one=one, parts=parts):
+            for o, n in parts:
+                assert one(o, n) == 0
+        out[name + "_GBs"] = timed(fn, moved)
     del a, b
     L.probe_mix.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp]
     L.probe_readk.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp, vp]
     for K in sorted(set(k for k in Ks if k in (4, 8, 16))):
-        R, nb = K + 2, nbytes
-        bufs = [torch.zeros(nb // 4, device="cuda") for _ in range(2 * R)]      # two sets, used in turn
-        sets = [(vp * R)(*[t.data_ptr() for t in bufs[i * R:(i + 1) * R]]) for i in range(2)]
-        for name, fn, moved in ((f"mix_{K}_workers_GBs", lambda i: L.probe_mix(sets[i % 2], R, nb, st), (R + 2) * nb),
-                                (f"read_only_{K}_workers_GBs",
-                                 lambda i: L.probe_readk(sets[i % 2], R, nb, sink.data_ptr(), st), R * nb)):
-            for i in range(4):
-                assert fn(i) == 0
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for i in range(reps):
-                fn(i)
-            e1.record()
-            torch.cuda.synchronize()
-            out[name] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del bufs, sets
+        R = K + 2
+        bufs = [torch.zeros(nbytes // 4, device="cuda") for _ in range(2 * R)]      # two sets, used in turn
+        for name, moved, call in ((f"mix_{K}_workers_GBs", (R + 2) * nbytes,
+                                   lambda ptrs, n: L.probe_mix(ptrs, R, n, st)),
+                                  (f"read_only_{K}_workers_GBs", R * nbytes,
+                                   lambda ptrs, n: L.probe_readk(ptrs, R, n, sink.data_ptr(), st))):
+            parts = [[((vp * R)(*[t.data_ptr() + o for t in bufs[i * R:(i + 1) * R]]), n) for o, n in cuts(moved)]
+                     for i in range(2)]
+
+            def fn(i, call=call, parts=parts):
+                for ptrs, n in parts[i % 2]:
+                    assert call(ptrs, n) == 0
+            out[name] = timed(fn, moved, warm=4)
+        del bufs
     return out
 
 

@@ -84,6 +84,20 @@ int64_t abs_row_elems(void);
  * results never change.  Process-wide default; see abs_ctx_set_launch_tuning. */
 int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile);
 
+/* Launch length.  Very long launches move fewer bytes per second on this part than the
+ * same work in shorter ones, so a call whose kernels would move n times `bytes` is
+ * enqueued as n launches over consecutive ranges of its workgroups (one launch when
+ * n < 2), on the same stream, in order.  Default 1 GiB; 0 = never cut.  Results never
+ * change: every element is still written once, by the same arithmetic.  Process-wide,
+ * read once per call; ABS_EINVAL for a negative value. */
+int abs_set_launch_slice_bytes(int64_t bytes);
+/* The rule itself, for callers that want to know how a call is enqueued: workgroups
+ * per launch for a call of `workgroups` workgroups moving `bytes` bytes when
+ * `resident_workgroups` of them run at once (every launch but the last is a whole number
+ * of such rounds).  Equal to `workgroups` when the call is not cut.  ABS_EINVAL for a
+ * negative count or fewer than one resident workgroup. */
+int64_t abs_slice_workgroups(int64_t workgroups, int64_t bytes, int resident_workgroups);
+
 /* Cache policy of the kernels.  Accumulators, x and v are re-read soon after a
  * launch (next micro-batch, next iteration).  Each kernel has a cached flavour
  * and a streaming one (non-temporal accesses to those buffers); results are

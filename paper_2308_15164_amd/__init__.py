@@ -28,6 +28,8 @@ SYMBOLS = {
     "abs_error_string": (ctypes.c_char_p, [_int]),
     "abs_row_elems": (_i64, []),
     "abs_set_launch_tuning": (_int, [_int, _int]),
+    "abs_set_launch_slice_bytes": (_int, [_i64]),
+    "abs_slice_workgroups": (_i64, [_i64, _i64, _int]),
     "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
     "abs_accumulate_batch": (_int, [_vp, _pvp, _int, _int, _i64, _pi64, _pi64, _vp]),
@@ -174,6 +176,11 @@ def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=4):
     """See abs_set_launch_tuning in abs_sgd.h; the defaults are the library's own."""
     return _check("abs_set_launch_tuning",
                   lib().abs_set_launch_tuning(int(blocks_per_cu), int(max_rows_per_tile)))
+
+
+def abs_set_launch_slice_bytes(nbytes=1 << 30):
+    """See abs_set_launch_slice_bytes in abs_sgd.h; the default is the library's own; 0 = never cut."""
+    return _check("abs_set_launch_slice_bytes", lib().abs_set_launch_slice_bytes(int(nbytes)))
 
 
 def abs_suggest_accumulate_streams(P, K):

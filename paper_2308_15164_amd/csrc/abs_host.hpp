@@ -23,6 +23,9 @@
 #ifndef ABS_UPD_STREAM_BYTES
 #define ABS_UPD_STREAM_BYTES (int64_t(256) << 20)
 #endif
+#ifndef ABS_SLICE_BYTES
+#define ABS_SLICE_BYTES (int64_t(1) << 30)
+#endif
 
 namespace absh {
 
@@ -39,6 +42,7 @@ struct Tuning {
     int max_rows;        // cap on rows per tile; 0 = none
     int policy_acc;      // cache policy of accumulator traffic: -1 from the sizes, 0 cached, 1 streaming
     int policy_upd;      // the same for x and the state vectors
+    int64_t slice_bytes; // a call moving n times this many bytes goes in n launches; 0 = never cut
 };
 
 constexpr int64_t kMaxGrid = 0x7fffffff;
@@ -73,6 +77,30 @@ inline int resident(const Tuning &tu, int per_cu) { return (tu.blocks_per_cu > 0
 // The one-gradient accumulate kernels need few registers: 8 workgroups of 4 wavefronts per CU.
 constexpr int kAccBlocksPerCU = 8;
 inline int acc_resident(const Tuning &tu) { return resident(tu, kAccBlocksPerCU); }
+
+// Long launches lose rate on this part.  Measured at P = 1.38e8 with consecutive launches
+// over sub-ranges of the same vectors: a launch moving 1-2 GB is as fast as any shorter
+// one, but the sync-update over 8 workers (6.6 GB in one launch) gains 4-6 % when cut
+// into 4-12 launches, over 16 workers (11 GB) 4-7 % in 6-12, an accumulate over a 2.2 GB
+// vector (6.6 GB) 6 % in 4-8 -- and a job list of four 553 MB accumulators in one launch
+// is 4-8 % SLOWER than four launches.  So a call is cut into floor(bytes / slice_bytes)
+// launches over consecutive workgroup ranges (one launch below twice that), each a whole
+// number of resident rounds.  Returns the workgroups per launch.
+inline int64_t slice_wgs(const Tuning &tu, int64_t wgs, int64_t bytes, int resident_wgs)
+{
+    if (tu.slice_bytes <= 0) return wgs;
+    const int64_t slices = bytes / tu.slice_bytes;
+    if (slices <= 1 || wgs <= resident_wgs) return wgs;
+    const int64_t per = (wgs + slices - 1) / slices;
+    return ((per + resident_wgs - 1) / resident_wgs) * resident_wgs;
+}
+
+// launch(b0, n) for every slice [b0, b0 + n) of `wgs` workgroups, `per` at a time.
+template <class Launch>
+inline void for_slices(int64_t wgs, int64_t per, Launch launch)
+{
+    for (int64_t b0 = 0; b0 < wgs; b0 += per) launch((unsigned)b0, (unsigned)(wgs - b0 < per ? wgs - b0 : per));
+}
 
 // Accumulators, x and v are touched again soon after a kernel ends.  When they
 // fit the memory-side cache (256 MiB on this part) keeping them cached pays;
@@ -145,7 +173,7 @@ int launch_copy_ragged(const RaggedView &L, float *const *dst_tab, float *const 
 // First chunk of every tensor, from the chunk table (one small launch).
 int launch_lars_chunk_begin(const RaggedView &L, int32_t *chunk_begin, hipStream_t s);
 // The three LARS launches; chunk_begin must already be valid in `sc` on the stream.
-int launch_lars(const RaggedView &L, float *const *xt, float *const *vt, float *const *gt,
+int launch_lars(const Tuning &tu, const RaggedView &L, float *const *xt, float *const *vt, float *const *gt,
                 const float *const *const *tabs, int n, float M, float lr, float mu, float wd, float eta,
                 const LarsScratch &sc, hipStream_t s);
 

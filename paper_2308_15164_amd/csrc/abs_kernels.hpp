@@ -551,13 +551,15 @@ __device__ __forceinline__ int tile_len(int64_t total, int64_t base, int tile)
 }
 
 // Flat vector: workgroup b owns elements [b*tile, min(P, (b+1)*tile)); tile is a
-// multiple of ROW chosen by the host.
+// multiple of ROW chosen by the host.  A call may be cut into several launches
+// (abs_host.hpp, slice_wgs): b0 is the index of the launch's first workgroup in the
+// call, so b = blockIdx.x + b0 in every kernel below.
 template <bool BF16, bool NTA, int J>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_flat(float *__restrict__ acc,
                                                             GradArgs<BF16, J> G, int64_t P, int tile,
-                                                            int first, int vec_ok)
+                                                            int first, int vec_ok, unsigned b0)
 {
-    const int64_t base = (int64_t)blockIdx.x * tile;
+    const int64_t base = (int64_t)(blockIdx.x + b0) * tile;
 #pragma unroll
     for (int j = 0; j < J; ++j) G.g[j] += base;
     accumulate_tile<BF16, NTA, J>(acc + base, G, tile_len(P, base, tile), first != 0, vec_ok != 0);
@@ -567,9 +569,10 @@ template <int K, bool NTX, int RULE>
 __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat(float *__restrict__ x,
                                                              float *__restrict__ v,
                                                              float *__restrict__ xp, AccPtrs<K> A,
-                                                             int64_t P, int tile, Hyper h, int vec_ok)
+                                                             int64_t P, int tile, Hyper h, int vec_ok,
+                                                             unsigned b0)
 {
-    const int64_t base = (int64_t)blockIdx.x * tile;
+    const int64_t base = (int64_t)(blockIdx.x + b0) * tile;
     AccPtrs<K> B;
 #pragma unroll
     for (int k = 0; k < K; ++k) B.p[k] = A.p[k] + base;
@@ -582,10 +585,10 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_flat_any(float *__restr
                                                                  float *__restrict__ v,
                                                                  float *__restrict__ xp,
                                                                  AccPtrsAny A, int K, int64_t P,
-                                                                 int tile, Hyper h, int vec_ok)
+                                                                 int tile, Hyper h, int vec_ok, unsigned b0)
 {
     __shared__ const float *ptrs[64];
-    const int64_t base = (int64_t)blockIdx.x * tile;
+    const int64_t base = (int64_t)(blockIdx.x + b0) * tile;
     if ((int)threadIdx.x < K) ptrs[threadIdx.x] = A.p[threadIdx.x] + base;
     __syncthreads();
     sync_tile_any<RULE, NTX>(x + base, v + base, uses_s2<RULE>() ? xp + base : nullptr, ptrs, K,
@@ -607,10 +610,11 @@ template <bool BF16, bool NTA, int J>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__restrict__ chunks,
                                                               const int64_t *__restrict__ sizes,
                                                               float *const *__restrict__ acc_tab,
-                                                              GradTabs<J> tabs, int tile, int first)
+                                                              GradTabs<J> tabs, int tile, int first,
+                                                              unsigned b0)
 {
     typedef typename GradT<BF16>::elem gelem;
-    const Chunk c = chunks[blockIdx.x];
+    const Chunk c = chunks[blockIdx.x + b0];
     const int64_t base = (int64_t)c.index * tile;
     float *acc = acc_tab[c.tensor] + base;
     bool vec_ok = aligned16(acc);
@@ -628,11 +632,15 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_ragged(const Chunk *__re
 //
 // One launch for several workers: job w is one worker's share of the launch, its
 // accumulator and the J_w <= 8 gradients folded into it, in order, with the
-// roundings of J_w single launches.  Workgroup (x, y) owns tile x of job y; the
-// hardware hands out x fastest, so the jobs stream through the chip one after
-// the other with no ramp-up or drain between them, and a launch lasts as long
-// as all of them together.  The job table travels in the kernel arguments and
-// is read with scalar loads (y is uniform over the workgroup).
+// roundings of J_w single launches.  The grid is ONE-dimensional: workgroup b owns
+// tile b % tiles of job b / tiles, and workgroups start in the order of their index,
+// so the jobs stream through the chip one after the other with no ramp-up or drain
+// between them, and a launch lasts as long as all of them together.  (A two-
+// dimensional grid, job = blockIdx.y, runs the jobs side by side instead: measured
+// at P = 1.4e8, lists of 2 and 4 jobs then move 2-8 % less per second than single
+// launches, the chip streaming through 2-4 times as many vectors at once.)  The job
+// table travels in the kernel arguments and is read with scalar loads (the job index
+// is uniform over the workgroup).
 // JMAX bounds the J of every job of the launch (the host instantiates 1, 2, 4, 8), so
 // that a launch of single gradients does not carry the registers of an 8-gradient one.
 //
@@ -683,11 +691,25 @@ __device__ __forceinline__ void accumulate_job_tile(float *__restrict__ acc, con
     if constexpr (J < JMAX) accumulate_job_tile<BF16, NTA, JMAX, J + 1>(acc, jb, base, len);
 }
 
-template <bool BF16, bool NTA, int JMAX>
-__global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_flat(JobList L, int64_t P, int tile)
+// (job, tile) of workgroup b in a launch of `tiles` tiles per job; at most MAX_JOBS - 1 steps.
+__device__ __forceinline__ void job_and_tile(unsigned b, unsigned tiles, unsigned &job, unsigned &tile_index)
 {
-    const JobView<JMAX> jb = view_job<JMAX>(L.job[blockIdx.y]);
-    const int64_t base = (int64_t)blockIdx.x * tile;
+    job = 0;
+    while (b >= tiles) {
+        b -= tiles;
+        ++job;
+    }
+    tile_index = b;
+}
+
+template <bool BF16, bool NTA, int JMAX>
+__global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_flat(JobList L, int64_t P, int tile, unsigned tiles,
+                                                                 unsigned b0)
+{
+    unsigned job, t;
+    job_and_tile(blockIdx.x + b0, tiles, job, t);
+    const JobView<JMAX> jb = view_job<JMAX>(L.job[job]);
+    const int64_t base = (int64_t)t * tile;
     accumulate_job_tile<BF16, NTA, JMAX>(jb.acc + base, jb, base, tile_len(P, base, tile));
 }
 
@@ -697,10 +719,13 @@ __global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_flat(JobList L, int
 template <bool BF16, bool NTA, int JMAX>
 __global__ __launch_bounds__(ABS_BLOCK) void accumulate_jobs_ragged(const Chunk *__restrict__ chunks,
                                                                    const int64_t *__restrict__ sizes,
-                                                                   JobList L, int tile)
+                                                                   JobList L, int tile, unsigned nchunks,
+                                                                   unsigned b0)
 {
-    const JobView<JMAX> tabs = view_job<JMAX>(L.job[blockIdx.y]);
-    const Chunk c = chunks[blockIdx.x];
+    unsigned job, t;
+    job_and_tile(blockIdx.x + b0, nchunks, job, t);
+    const JobView<JMAX> tabs = view_job<JMAX>(L.job[job]);
+    const Chunk c = chunks[t];
     const int64_t base = (int64_t)c.index * tile;
     JobView<JMAX> jb;
     jb.J = tabs.J;
@@ -725,9 +750,9 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged(const Chunk *__r
                                                                float *const *__restrict__ x_tab,
                                                                float *const *__restrict__ v_tab,
                                                                float *const *__restrict__ p_tab,
-                                                               TabPtrs<K> tabs, int tile, Hyper h)
+                                                               TabPtrs<K> tabs, int tile, Hyper h, unsigned b0)
 {
-    const Chunk c = chunks[blockIdx.x];
+    const Chunk c = chunks[blockIdx.x + b0];
     const int64_t base = (int64_t)c.index * tile;
     float *x = x_tab[c.tensor] + base;
     float *v = v_tab[c.tensor] + base;
@@ -753,11 +778,11 @@ __global__ __launch_bounds__(ABS_BLOCK) void sync_update_ragged_any(const Chunk 
                                                                    float *const *__restrict__ v_tab,
                                                                    float *const *__restrict__ p_tab,
                                                                    TabPtrsAny tabs, int K, int tile,
-                                                                   Hyper h)
+                                                                   Hyper h, unsigned b0)
 {
     __shared__ const float *ptrs[64];
     __shared__ int all_aligned;
-    const Chunk c = chunks[blockIdx.x];
+    const Chunk c = chunks[blockIdx.x + b0];
     const int64_t base = (int64_t)c.index * tile;
     if (threadIdx.x == 0) all_aligned = 1;
     __syncthreads();

@@ -91,10 +91,11 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
                                                                float *const *__restrict__ x_tab,
                                                                float *const *__restrict__ g_tab,
                                                                TabPtrsAny tabs, int K, int tile, float M,
-                                                               double *__restrict__ partials)
+                                                               double *__restrict__ partials, unsigned b0)
 {
     constexpr int U = 4, KC = 4;
-    const Chunk c = chunks[blockIdx.x];
+    const unsigned cb = blockIdx.x + b0;       // chunk of this workgroup (b0: first workgroup of this launch in the call)
+    const Chunk c = chunks[cb];
     const int64_t base = (int64_t)c.index * tile;
     const int len = tile_len(sizes[c.tensor], base, tile);
     const float *__restrict__ x = x_tab[c.tensor] + base;
@@ -160,8 +161,8 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_reduce_ragged(const Chunk *__r
     }
     block_sum2(sx, sg);
     if (tid == 0) {
-        partials[2 * (int64_t)blockIdx.x] = sx;
-        partials[2 * (int64_t)blockIdx.x + 1] = sg;
+        partials[2 * (int64_t)cb] = sx;
+        partials[2 * (int64_t)cb + 1] = sg;
     }
 }
 
@@ -219,10 +220,10 @@ __global__ __launch_bounds__(ABS_BLOCK) void lars_update_ragged(const Chunk *__r
                                                                float *const *__restrict__ v_tab,
                                                                float *const *__restrict__ g_tab,
                                                                const float *__restrict__ step, int tile,
-                                                               float mu, float wd)
+                                                               float mu, float wd, unsigned b0)
 {
     constexpr int U = 4;
-    const Chunk c = chunks[blockIdx.x];
+    const Chunk c = chunks[blockIdx.x + b0];
     const int64_t base = (int64_t)c.index * tile;
     const int len = tile_len(sizes[c.tensor], base, tile);
     float *__restrict__ x = x_tab[c.tensor] + base;

@@ -57,11 +57,13 @@ inline int launch_status()
 // a launch racing with one of the setters reads either the old or the new value.
 std::atomic<int> g_blocks_per_cu{0}, g_max_rows{ABS_MAX_ROWS};
 std::atomic<int> g_policy_acc{-1}, g_policy_upd{-1};
+std::atomic<int64_t> g_slice_bytes{ABS_SLICE_BYTES};
 
 inline Tuning process_tuning()
 {
     return Tuning{g_blocks_per_cu.load(std::memory_order_relaxed), g_max_rows.load(std::memory_order_relaxed),
-                  g_policy_acc.load(std::memory_order_relaxed), g_policy_upd.load(std::memory_order_relaxed)};
+                  g_policy_acc.load(std::memory_order_relaxed), g_policy_upd.load(std::memory_order_relaxed),
+                  g_slice_bytes.load(std::memory_order_relaxed)};
 }
 
 inline bool tuning_ok(int blocks_per_cu, int max_rows) { return blocks_per_cu >= 0 && blocks_per_cu <= 32 && max_rows >= 0; }
@@ -456,7 +458,7 @@ int sync_update_lars(const abs_layout *L, const abs_tensorset *params, const abs
         if (rc == ABS_OK) rc = launch_status();
         if (rc != ABS_OK) return rc;
     }
-    rc = launch_lars(V, reinterpret_cast<float *const *>(params->d_tab),
+    rc = launch_lars(process_tuning(), V, reinterpret_cast<float *const *>(params->d_tab),
                      reinterpret_cast<float *const *>(momentum->d_tab),
                      reinterpret_cast<float *const *>(gbar->d_tab), tabs, c.n, (float)c.M, lr, mu, wd, eta, *sc, s);
     if (rc != ABS_OK) return rc;
@@ -690,6 +692,19 @@ int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile)
     g_blocks_per_cu.store(blocks_per_cu, std::memory_order_relaxed);
     g_max_rows.store(max_rows_per_tile, std::memory_order_relaxed);
     return ABS_OK;
+}
+
+int abs_set_launch_slice_bytes(int64_t bytes)
+{
+    if (bytes < 0) return ABS_EINVAL;
+    g_slice_bytes.store(bytes, std::memory_order_relaxed);
+    return ABS_OK;
+}
+
+int64_t abs_slice_workgroups(int64_t workgroups, int64_t bytes, int resident_workgroups)
+{
+    if (workgroups < 0 || bytes < 0 || resident_workgroups < 1) return ABS_EINVAL;
+    return slice_wgs(process_tuning(), workgroups, bytes, resident_workgroups);
 }
 
 int abs_set_cache_policy(int accumulate_mode, int update_mode)

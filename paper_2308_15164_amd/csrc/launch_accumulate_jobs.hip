@@ -24,25 +24,39 @@ int occupancy_per_cu(Kernel kernel, int fallback)
 template <bool BF16, int JMAX>
 int jobs_flat(const Tuning &tu, const JobList &jobs, int njobs, int64_t P, hipStream_t s)
 {
+    int64_t bytes = 0;
+    for (int i = 0; i < njobs; ++i) bytes += P * (jobs.job[i].J * (BF16 ? 2 : 4) + (jobs.job[i].first ? 4 : 8));
     static const int per_cu = occupancy_per_cu(accumulate_jobs_flat<BF16, false, JMAX>, 4);
     const int64_t tile64 = choose_tile(rows_of(P) * njobs, resident(tu, per_cu), tu.max_rows);
-    if (tile64 > kMaxTile || tiles_for(P, tile64) > kMaxGrid) return ABS_EINVAL;
-    const dim3 grid((unsigned)tiles_for(P, tile64), (unsigned)njobs), block(BLOCK);
-    if (stream_jobs(tu, P, njobs))
-        hipLaunchKernelGGL((accumulate_jobs_flat<BF16, true, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
-    else
-        hipLaunchKernelGGL((accumulate_jobs_flat<BF16, false, JMAX>), grid, block, 0, s, jobs, P, (int)tile64);
+    const int64_t tiles = tiles_for(P, tile64);
+    if (tile64 > kMaxTile || tiles * njobs > kMaxGrid) return ABS_EINVAL;
+    // one-dimensional: workgroup b works on tile b % tiles of job b / tiles, the jobs one after the other
+    const dim3 block(BLOCK);
+    const bool nta = stream_jobs(tu, P, njobs);
+    for_slices(tiles * njobs, slice_wgs(tu, tiles * njobs, bytes, resident(tu, per_cu)), [&](unsigned b0, unsigned n) {
+        if (nta)
+            hipLaunchKernelGGL((accumulate_jobs_flat<BF16, true, JMAX>), dim3(n), block, 0, s, jobs, P, (int)tile64, (unsigned)tiles, b0);
+        else
+            hipLaunchKernelGGL((accumulate_jobs_flat<BF16, false, JMAX>), dim3(n), block, 0, s, jobs, P, (int)tile64, (unsigned)tiles, b0);
+    });
     return ABS_OK;
 }
 
 template <bool BF16, int JMAX>
 int jobs_ragged(const Tuning &tu, const RaggedView &L, const JobList &jobs, int njobs, hipStream_t s)
 {
-    const dim3 grid(L.nchunks, (unsigned)njobs), block(BLOCK);
-    if (stream_jobs(tu, L.total, njobs))
-        hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, true, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);
-    else
-        hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, false, JMAX>), grid, block, 0, s, L.chunks, L.sizes, jobs, L.tile);
+    if ((int64_t)L.nchunks * njobs > kMaxGrid) return ABS_EINVAL;
+    int64_t bytes = 0;
+    for (int i = 0; i < njobs; ++i) bytes += L.total * (jobs.job[i].J * (BF16 ? 2 : 4) + (jobs.job[i].first ? 4 : 8));
+    const dim3 block(BLOCK);
+    const bool nta = stream_jobs(tu, L.total, njobs);
+    const int64_t wgs = (int64_t)L.nchunks * njobs;
+    for_slices(wgs, slice_wgs(tu, wgs, bytes, acc_resident(tu)), [&](unsigned b0, unsigned n) {
+        if (nta)
+            hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, true, JMAX>), dim3(n), block, 0, s, L.chunks, L.sizes, jobs, L.tile, L.nchunks, b0);
+        else
+            hipLaunchKernelGGL((accumulate_jobs_ragged<BF16, false, JMAX>), dim3(n), block, 0, s, L.chunks, L.sizes, jobs, L.tile, L.nchunks, b0);
+    });
     return ABS_OK;
 }
 

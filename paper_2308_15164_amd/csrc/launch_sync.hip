@@ -36,12 +36,16 @@ int sync_flat_k(const Tuning &tu, float *x, float *v, float *xp, const float *co
     const int tile = (int)tile64;
     AccPtrs<K> A;
     for (int k = 0; k < K; ++k) A.p[k] = ptrs[k];
-    const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
+    const dim3 block(BLOCK);
     // x and each state vector are re-read one iteration later
-    if (stream_upd(tu, P, uses_s2<RULE>() ? 3 : 2))
-        hipLaunchKernelGGL((sync_update_flat<K, true, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
-    else
-        hipLaunchKernelGGL((sync_update_flat<K, false, RULE>), grid, block, 0, s, x, v, xp, A, P, tile, h, vec_ok);
+    const bool ntx = stream_upd(tu, P, uses_s2<RULE>() ? 3 : 2);
+    const int64_t wgs = tiles_for(P, tile64);
+    for_slices(wgs, slice_wgs(tu, wgs, P * (4 * K + (uses_s2<RULE>() ? 24 : 16)), resident(tu, per_cu)), [&](unsigned b0, unsigned n) {
+        if (ntx)
+            hipLaunchKernelGGL((sync_update_flat<K, true, RULE>), dim3(n), block, 0, s, x, v, xp, A, P, tile, h, vec_ok, b0);
+        else
+            hipLaunchKernelGGL((sync_update_flat<K, false, RULE>), dim3(n), block, 0, s, x, v, xp, A, P, tile, h, vec_ok, b0);
+    });
     return ABS_OK;
 }
 
@@ -51,11 +55,14 @@ void sync_ragged_k(const Tuning &tu, const RaggedView &L, float *const *xt, floa
 {
     TabPtrs<K> T;
     for (int k = 0; k < K; ++k) T.t[k] = tabs[k];
-    const dim3 grid(L.nchunks), block(BLOCK);
-    if (stream_upd(tu, L.total, uses_s2<RULE>() ? 3 : 2))
-        hipLaunchKernelGGL((sync_update_ragged<K, true, RULE>), grid, block, 0, s, L.chunks, L.sizes, xt, vt, pt, T, L.tile, h);
-    else
-        hipLaunchKernelGGL((sync_update_ragged<K, false, RULE>), grid, block, 0, s, L.chunks, L.sizes, xt, vt, pt, T, L.tile, h);
+    const dim3 block(BLOCK);
+    const bool ntx = stream_upd(tu, L.total, uses_s2<RULE>() ? 3 : 2);
+    for_slices(L.nchunks, slice_wgs(tu, L.nchunks, L.total * (4 * K + (uses_s2<RULE>() ? 24 : 16)), resident(tu, 4)), [&](unsigned b0, unsigned n) {
+        if (ntx)
+            hipLaunchKernelGGL((sync_update_ragged<K, true, RULE>), dim3(n), block, 0, s, L.chunks, L.sizes, xt, vt, pt, T, L.tile, h, b0);
+        else
+            hipLaunchKernelGGL((sync_update_ragged<K, false, RULE>), dim3(n), block, 0, s, L.chunks, L.sizes, xt, vt, pt, T, L.tile, h, b0);
+    });
 }
 
 }  // namespace
@@ -81,11 +88,15 @@ int launch_sync_flat_r(const Tuning &tu, float *x, float *s1, float *s2, const f
         AccPtrsAny A;
         std::memset(&A, 0, sizeof A);
         for (int k = 0; k < n; ++k) A.p[k] = ptrs[k];
-        const dim3 grid((unsigned)tiles_for(P, tile64)), block(BLOCK);
-        if (stream_upd(tu, P, uses_s2<RULE>() ? 3 : 2))
-            hipLaunchKernelGGL((sync_update_flat_any<RULE, true>), grid, block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok);
-        else
-            hipLaunchKernelGGL((sync_update_flat_any<RULE, false>), grid, block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok);
+        const dim3 block(BLOCK);
+        const bool ntx = stream_upd(tu, P, uses_s2<RULE>() ? 3 : 2);
+        const int64_t wgs = tiles_for(P, tile64);
+        for_slices(wgs, slice_wgs(tu, wgs, P * (4 * n + (uses_s2<RULE>() ? 24 : 16)), resident(tu, per_cu)), [&](unsigned b0, unsigned nb) {
+            if (ntx)
+                hipLaunchKernelGGL((sync_update_flat_any<RULE, true>), dim3(nb), block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok, b0);
+            else
+                hipLaunchKernelGGL((sync_update_flat_any<RULE, false>), dim3(nb), block, 0, s, x, s1, s2, A, n, P, (int)tile64, h, vec_ok, b0);
+        });
         return ABS_OK;
     }
     }
@@ -105,11 +116,14 @@ int launch_sync_ragged_r(const Tuning &tu, const RaggedView &L, float *const *xt
         TabPtrsAny T;
         std::memset(&T, 0, sizeof T);
         for (int k = 0; k < n; ++k) T.t[k] = tabs[k];
-        const dim3 grid(L.nchunks), block(BLOCK);
-        if (stream_upd(tu, L.total, uses_s2<RULE>() ? 3 : 2))
-            hipLaunchKernelGGL((sync_update_ragged_any<RULE, true>), grid, block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h);
-        else
-            hipLaunchKernelGGL((sync_update_ragged_any<RULE, false>), grid, block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h);
+        const dim3 block(BLOCK);
+        const bool ntx = stream_upd(tu, L.total, uses_s2<RULE>() ? 3 : 2);
+        for_slices(L.nchunks, slice_wgs(tu, L.nchunks, L.total * (4 * n + (uses_s2<RULE>() ? 24 : 16)), resident(tu, 3)), [&](unsigned b0, unsigned nb) {
+            if (ntx)
+                hipLaunchKernelGGL((sync_update_ragged_any<RULE, true>), dim3(nb), block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h, b0);
+            else
+                hipLaunchKernelGGL((sync_update_ragged_any<RULE, false>), dim3(nb), block, 0, s, L.chunks, L.sizes, xt, s1t, s2t, T, n, L.tile, h, b0);
+        });
         return ABS_OK;
     }
     }

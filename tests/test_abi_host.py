@@ -366,3 +366,40 @@ def test_job_list_host_side_without_a_gpu():
     with pytest.raises(absgd.AbsError):
         ctx.abs_set_launch_tuning(0, -1)
     ctx.close()
+
+
+def test_launch_slicing_rule():
+    """abs_slice_workgroups: a call is cut into floor(bytes / slice_bytes) launches (one below
+    twice the unit), every launch but the last a whole number of resident rounds, together
+    covering every workgroup once; 0 switches the cutting off."""
+    L = absgd.lib()
+    rng = np.random.default_rng(5)
+    try:
+        for unit in (1 << 30, 1 << 20, 12345):
+            absgd.abs_set_launch_slice_bytes(unit)
+            for _ in range(300):
+                wgs = int(rng.integers(0, 200_000))
+                nbytes = int(rng.integers(0, 40 * unit))
+                resident = int(rng.integers(1, 3000))
+                per = L.abs_slice_workgroups(wgs, nbytes, resident)
+                if nbytes < 2 * unit or wgs <= resident:
+                    assert per == wgs
+                    continue
+                assert 1 <= per <= max(wgs, resident) and per % resident == 0
+                launches = -(-wgs // per)
+                assert 1 <= launches <= nbytes // unit
+                # cutting never makes launches smaller than half of what was asked for, except the last
+                assert per >= wgs // (nbytes // unit)
+        absgd.abs_set_launch_slice_bytes(0)
+        assert L.abs_slice_workgroups(10**6, 10**15, 7) == 10**6
+        assert L.abs_set_launch_slice_bytes(-1) == absgd.ABS_EINVAL
+        assert L.abs_slice_workgroups(-1, 0, 1) == absgd.ABS_EINVAL
+        assert L.abs_slice_workgroups(1, -1, 1) == absgd.ABS_EINVAL
+        assert L.abs_slice_workgroups(1, 1, 0) == absgd.ABS_EINVAL
+    finally:
+        absgd.abs_set_launch_slice_bytes()
+    # the default: the VGG16-sized accumulate (1.66 GB) goes in one launch, the sync-update over
+    # 16 such accumulators (11 GB, ten units) in nine launches of five resident rounds each
+    assert L.abs_slice_workgroups(33_779, 12 * 138_357_544, 2048) == 33_779
+    per = L.abs_slice_workgroups(33_779, 80 * 138_357_544, 768)
+    assert per == 5 * 768 and -(-33_779 // per) == 9

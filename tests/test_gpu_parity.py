@@ -1434,6 +1434,58 @@ def test_special_values(absgd):
 
 
 # ---------------------------------------------------------------------------
+# calls cut into several launches over consecutive workgroup ranges
+# ---------------------------------------------------------------------------
+
+@pytest.fixture
+def sliced(absgd, request):
+    """One-row tiles, one resident workgroup per CU and a tiny launch length: calls over a
+    million elements or more go in 4 to 40 launches (the default cuts only multi-GB calls)."""
+    absgd.abs_set_launch_tuning(1, request.param)
+    absgd.abs_set_launch_slice_bytes(1 << 20)
+    yield request.param
+    absgd.abs_set_launch_slice_bytes()     # the defaults
+    absgd.abs_set_launch_tuning(0, 4)
+
+
+@pytest.mark.parametrize("sliced", [1, 2], indirect=True)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sliced_accumulate(absgd, sliced, dtype):
+    for P in (1_048_576 + 13, 2_500_007):
+        test_accumulate_matches_oracle(absgd, dtype, P)
+    print(f"[case] sliced accumulate_jobs {dtype}", flush=True)
+    _jobs_case(absgd, 700_001, [2, 5, 1, 0, 3], dtype, 1, seed=7400, start_counts=[0, 32, 0, 0, 64])
+    _jobs_case(absgd, 700_001, [2, 9, 1, 0, 3], dtype, 8, seed=7401)
+
+
+@pytest.mark.parametrize("sliced", [1, 2], indirect=True)
+@pytest.mark.parametrize("K", [3, 9, 16, 19])
+def test_sliced_sync_update(absgd, sliced, K):
+    P = 1_048_576 + 13
+    counts = [32 * (1 + k % 3) for k in range(K)]
+    print(f"[case] sliced sync_update K={K} rows per tile <= {sliced}", flush=True)
+    _sync_case(absgd, K, P, counts, seed=7500 + K)
+    _sync_dc_case(absgd, K, P, counts, seed=7510 + K)
+    _sync_dcm_case(absgd, K, P, counts, seed=7520 + K)
+    _sync_adam_case(absgd, K, P, counts, seed=7530 + K)
+
+
+@pytest.mark.parametrize("sliced", [1], indirect=True)
+@pytest.mark.parametrize("K,dtype", [(3, "f32"), (17, "bf16")])
+def test_sliced_ragged_calls(absgd, sliced, K, dtype):
+    _ragged_case(absgd, [700_001, 5, 300_000, 1_048_576 + 13, 0, 77], [32 * (1 + k % 3) for k in range(K)],
+                 seed=7600 + K, dtype=dtype)
+    _lars_case(absgd, [700_001, 5, 300_000, 1_048_576 + 13, 0, 77], [32 * (1 + k % 3) for k in range(K)],
+               seed=7610 + K)
+
+
+@pytest.mark.parametrize("sliced", [1], indirect=True)
+@pytest.mark.parametrize("fold", [None, 1, 8])
+def test_sliced_trajectory(absgd, sliced, fold):
+    _trajectory_case(absgd, "cfg1_small", step_fold=fold)
+
+
+# ---------------------------------------------------------------------------
 # seeded random draws: the grids above vary one thing at a time, these vary all at once
 # ---------------------------------------------------------------------------
 
