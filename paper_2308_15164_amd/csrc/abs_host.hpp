@@ -85,7 +85,14 @@ inline int acc_resident(const Tuning &tu) { return resident(tu, kAccBlocksPerCU)
 // vector (6.6 GB) 6 % in 4-8 -- and a job list of four 553 MB accumulators in one launch
 // is 4-8 % SLOWER than four launches.  So a call is cut into floor(bytes / slice_bytes)
 // launches over consecutive workgroup ranges (one launch below twice that), each a whole
-// number of resident rounds.  Returns the workgroups per launch.
+// number of resident rounds.  One unit for every kernel, 1 GiB: kernels over few vectors
+// (one to four gradients into an accumulator, the sync-update over up to four workers) are
+// indifferent between 0.5 and 2 GiB and lose 1-3 % at 256 MiB; kernels over many vectors
+// would take another 2-4 % from launches of one or two resident rounds (sync-update over 16
+// workers: 5.6 TB/s uncut, 6.0 at 1 GiB, 6.1-6.2 at 48-256 MiB), but a step of the GPT-2-
+// sized configuration then needs 270 launches and waits for the host, and launches that
+// short lose where the buffers sit in the memory-side cache.
+// Returns the workgroups per launch.
 inline int64_t slice_wgs(const Tuning &tu, int64_t wgs, int64_t bytes, int resident_wgs)
 {
     if (tu.slice_bytes <= 0) return wgs;
