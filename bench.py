@@ -109,22 +109,27 @@ def timed_region(run, plans, t0, steps, torch):
 def kernel_event_pass(run, plans, t0, steps, torch):
     """Replay the timed steps on ONE stream with a HIP event pair per step around that step's
     accumulate launches and one around its sync-update launch, recorded on the stream the
-    kernels run on.  Returns per step: accumulate bracket ms, its launches, sync-update bracket ms
-    (None for a step that applied nothing)."""
+    kernels run on.  Returns per step: accumulate bracket ms, the kernel launches in it (the
+    library's own count: a long call goes in several launches), sync-update bracket ms (None for
+    a step that applied nothing) and the kernel launches of that call."""
+    import paper_2308_15164_amd as absgd
     ev = lambda: torch.cuda.Event(enable_timing=True)
     rows = []
     torch.cuda.synchronize()
     for t in range(t0, t0 + steps):
         es, e0, e1 = ev(), ev(), ev()
+        n0 = absgd.abs_launch_count()
         es.record(run.s_acc)
         applied = run.sync_update()
         e0.record(run.s_acc)
-        n_launch = run.accumulate(plans[t])
+        n1 = absgd.abs_launch_count()
+        run.accumulate(plans[t])
         e1.record(run.s_acc)
+        n2 = absgd.abs_launch_count()
         run.ctx.abs_swap_buffers()
-        rows.append((e0, e1, n_launch, (es, e0) if applied else None))
+        rows.append((e0, e1, n2 - n1, (es, e0) if applied else None, n1 - n0))
     torch.cuda.synchronize()
-    return [(a.elapsed_time(b), n, s[0].elapsed_time(s[1]) if s else None) for a, b, n, s in rows]
+    return [(a.elapsed_time(b), n, s[0].elapsed_time(s[1]) if s else None, ns) for a, b, n, s, ns in rows]
 
 
 def probe_ceilings(torch, Ks=(), nbytes=4 * 138_357_544, reps=20):
@@ -345,12 +350,13 @@ def measure(torch, absgd, wl, w, args, mode, K_steps, W, repeats, all_plans=True
     step_bytes = sum((a + s) * P for a, s in bpp)
     acc_bytes = [a * P for a, _ in bpp] * repeats
     gbs = step_bytes / dt / 1e9
-    launches = sum(n for _, n, _ in rows)
-    kern_ms = sum(ms for ms, _, _ in rows) / launches
+    launches = sum(r[1] for r in rows)
+    kern_ms = sum(r[0] for r in rows) / launches
     kern_bytes = sum(acc_bytes) / launches
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
-    per_step_rate = [b / (ms * 1e-3) / 1e9 for b, (ms, _, _) in zip(acc_bytes, rows)]
-    sync_ms = [s for _, _, s in rows if s is not None]
+    per_step_rate = [b / (r[0] * 1e-3) / 1e9 for b, r in zip(acc_bytes, rows)]
+    sync_ms = [r[2] for r in rows if r[2] is not None]
+    sync_launches = [r[3] for r in rows if r[2] is not None]
     sync_bytes = bpp[0][1] * P
     sync_med = statistics.median(sync_ms)
     sync_gbs = sync_bytes / (sync_med * 1e-3) / 1e9
@@ -382,6 +388,8 @@ def measure(torch, absgd, wl, w, args, mode, K_steps, W, repeats, all_plans=True
             "achieved": sync_gbs, "frac": sync_gbs / HBM_PEAK_GBS,
             "algorithmic_bytes_per_launch": sync_bytes, "median_launch_ms": sync_med,
             "min_launch_ms": min(sync_ms), "max_launch_ms": max(sync_ms), "launches_timed": len(sync_ms),
+            # a call over several GB goes in several kernel launches over consecutive ranges
+            "kernel_launches_per_call": sum(sync_launches) / len(sync_launches),
         },
     }
     return res, (x0, pool, sched)
@@ -504,13 +512,15 @@ def main():
             "step_rate_GBs": {"median": ak["median_step_rate"], "min": ak["min_step_rate"],
                               "max": ak["max_step_rate"]},
             "measured": "HIP events around each step's accumulate launches on their stream, one-stream plan "
-                        "(the kernel alone on the GPU), every timed step of every repeat, no step left out",
+                        "(the kernel alone on the GPU), every timed step of every repeat, no step left out; "
+                        "launches are kernel launches as the library counts them (abs_launch_count)",
         },
         "sync_update_kernel": dict(sk, unit="GB/s",
-                                   measured="HIP events around the single sync-update launch of each step, "
-                                            "one-stream plan; a bracket around ONE launch also holds a few us "
-                                            "of dispatch latency, so this is a lower bound on the kernel's rate "
-                                            "(the kernel trace under profiles/ has its own duration)"),
+                                   measured="HIP events around the sync-update CALL of each step (its kernel "
+                                            "launches: kernel_launches_per_call, consecutive ranges of one pass), "
+                                            "one-stream plan; a bracket around one call also holds a few us of "
+                                            "dispatch latency, so this is a lower bound on the kernels' rate (the "
+                                            "kernel trace under profiles/ has their own durations)"),
     }
 
     table_Ks = {w.K}
@@ -526,7 +536,8 @@ def main():
                 k: r[k] for k in ("value", "pct_of_8TBs", "ms_per_step", "params_per_s", "plan",
                                   "algorithmic_bytes_per_step", "host_issue_ms_per_step")}
             out["accumulate_variants"][m]["accumulate_kernel_frac"] = r["accumulate_kernel"]["frac"]
-            out["accumulate_variants"][m]["launches_per_step"] = r["accumulate_kernel"]["launches_per_step"] + 1
+            out["accumulate_variants"][m]["launches_per_step"] = (r["accumulate_kernel"]["launches_per_step"] +
+                                                                  r["sync_update_kernel"]["kernel_launches_per_call"])
     if plain and not args.no_table:
         def row(r):
             return {"value": r["value"], "pct_of_8TBs": r["pct_of_8TBs"], "ms_per_step": r["ms_per_step"],
@@ -535,7 +546,7 @@ def main():
                     "accumulate_frac": r["accumulate_kernel"]["frac"], "sync_update_frac": r["sync_update_kernel"]["frac"],
                     "accumulate_launch_ms": r["accumulate_kernel"]["avg_launch_ms"],
                     "sync_update_launch_ms": r["sync_update_kernel"]["median_launch_ms"],
-                    "launches_per_step": r["accumulate_kernel"]["launches_per_step"] + 1,
+                    "launches_per_step": r["accumulate_kernel"]["launches_per_step"] + r["sync_update_kernel"]["kernel_launches_per_call"],
                     "host_issue_ms_per_step": r["host_issue_ms_per_step"]}
         out["per_config"] = {}
         for name in STATED:

@@ -91,6 +91,9 @@ int abs_set_launch_tuning(int blocks_per_cu, int max_rows_per_tile);
  * change: every element is still written once, by the same arithmetic.  Process-wide,
  * read once per call; ABS_EINVAL for a negative value. */
 int abs_set_launch_slice_bytes(int64_t bytes);
+/* Kernel launches the calling thread has enqueued through the library so far (a
+ * counter that only grows; the difference around a call is the launches of that call). */
+int64_t abs_launch_count(void);
 /* The rule itself, for callers that want to know how a call is enqueued: workgroups
  * per launch for a call of `workgroups` workgroups moving `bytes` bytes when
  * `resident_workgroups` of them run at once (every launch but the last is a whole number

@@ -29,6 +29,7 @@ SYMBOLS = {
     "abs_row_elems": (_i64, []),
     "abs_set_launch_tuning": (_int, [_int, _int]),
     "abs_set_launch_slice_bytes": (_int, [_i64]),
+    "abs_launch_count": (_i64, []),
     "abs_slice_workgroups": (_i64, [_i64, _i64, _int]),
     "abs_set_cache_policy": (_int, [_int, _int]),
     "abs_accumulate": (_int, [_vp, _vp, _int, _i64, _i64, _pi64, _vp]),
@@ -181,6 +182,11 @@ def abs_set_launch_tuning(blocks_per_cu=0, max_rows_per_tile=4):
 def abs_set_launch_slice_bytes(nbytes=1 << 30):
     """See abs_set_launch_slice_bytes in abs_sgd.h; the default is the library's own; 0 = never cut."""
     return _check("abs_set_launch_slice_bytes", lib().abs_set_launch_slice_bytes(int(nbytes)))
+
+
+def abs_launch_count():
+    """Kernel launches this thread has enqueued through the library so far."""
+    return int(lib().abs_launch_count())
 
 
 def abs_suggest_accumulate_streams(P, K):

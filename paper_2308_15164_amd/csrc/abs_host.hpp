@@ -102,11 +102,17 @@ inline int64_t slice_wgs(const Tuning &tu, int64_t wgs, int64_t bytes, int resid
     return ((per + resident_wgs - 1) / resident_wgs) * resident_wgs;
 }
 
+// Kernel launches this thread has enqueued through the library (abs_launch_count).
+inline thread_local int64_t t_launches = 0;
+
 // launch(b0, n) for every slice [b0, b0 + n) of `wgs` workgroups, `per` at a time.
 template <class Launch>
 inline void for_slices(int64_t wgs, int64_t per, Launch launch)
 {
-    for (int64_t b0 = 0; b0 < wgs; b0 += per) launch((unsigned)b0, (unsigned)(wgs - b0 < per ? wgs - b0 : per));
+    for (int64_t b0 = 0; b0 < wgs; b0 += per) {
+        launch((unsigned)b0, (unsigned)(wgs - b0 < per ? wgs - b0 : per));
+        ++t_launches;
+    }
 }
 
 // Accumulators, x and v are touched again soon after a kernel ends.  When they

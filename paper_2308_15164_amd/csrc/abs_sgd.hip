@@ -701,6 +701,8 @@ int abs_set_launch_slice_bytes(int64_t bytes)
     return ABS_OK;
 }
 
+int64_t abs_launch_count(void) { return t_launches; }
+
 int64_t abs_slice_workgroups(int64_t workgroups, int64_t bytes, int resident_workgroups)
 {
     if (workgroups < 0 || bytes < 0 || resident_workgroups < 1) return ABS_EINVAL;

@@ -106,6 +106,7 @@ int launch_copy_flat(const Tuning &tu, float *dst, const float *src, int64_t P, 
     const int vec_ok = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) == 0;
     hipLaunchKernelGGL(copy_flat, dim3((unsigned)tiles_for(P, tile64)), dim3(BLOCK), 0, s, dst, src, P,
                        (int)tile64, vec_ok);
+    ++t_launches;
     return ABS_OK;
 }
 
@@ -113,6 +114,7 @@ int launch_copy_ragged(const RaggedView &L, float *const *dst_tab, float *const 
 {
     hipLaunchKernelGGL(copy_ragged, dim3(L.nchunks), dim3(BLOCK), 0, s, L.chunks, L.sizes, dst_tab, src_tab,
                        L.tile);
+    ++t_launches;
     return ABS_OK;
 }
 
@@ -121,6 +123,7 @@ int launch_lars_chunk_begin(const RaggedView &L, int32_t *chunk_begin, hipStream
     const unsigned threads = L.nchunks + 1;
     hipLaunchKernelGGL(lars_chunk_begin, dim3((threads + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, s, L.chunks,
                        (int)L.nchunks, L.ntensors, chunk_begin);
+    ++t_launches;
     return ABS_OK;
 }
 
@@ -140,6 +143,7 @@ int launch_lars(const Tuning &tu, const RaggedView &L, float *const *xt, float *
     });
     hipLaunchKernelGGL(lars_rates, dim3((unsigned)L.ntensors), dim3(BLOCK), 0, s, sc.chunk_begin, sc.partials,
                        sc.step, (double)lr, (double)wd, (double)eta);
+    ++t_launches;
     for_slices(L.nchunks, slice_wgs(tu, L.nchunks, L.total * 20, resident(tu, 4)), [&](unsigned b0, unsigned nb) {
         hipLaunchKernelGGL(lars_update_ragged, dim3(nb), block, 0, s, L.chunks, L.sizes, xt, vt, gt, sc.step, L.tile, mu,
                            wd, b0);
