@@ -292,6 +292,9 @@ def test_accumulate_jobs_more_jobs_than_one_launch_carries(absgd):
     Js = [1 + (w * 7) % 9 for w in range(37)]                  # 1..9: some need two launches at fold 8
     _jobs_case(absgd, 3 * 4096 + 5, Js, "bf16", 8, seed=2300)
     _jobs_case(absgd, 3 * 4096 + 5, Js, "f32", 1, seed=2301)
+    print("[case] accumulate_jobs 64 workers (the most a call takes)", flush=True)
+    _jobs_case(absgd, 4096 + 9, [(w * 5) % 4 for w in range(64)], "f32", 2, seed=2302,
+               start_counts=[32 * (w % 2) for w in range(64)])
 
 
 @pytest.mark.parametrize("shift", [1, 2, 3])
